@@ -1,0 +1,604 @@
+// C ABI of libpaac: context, workspace carving, parameter layout, the kernel sequences of
+// paac_select_actions / paac_train_step, HIP-graph capture and replay, per-kernel timing.
+#include "../../include/paac.h"
+#include "internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+#include <string>
+#include <vector>
+
+using namespace paac;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kHpSlots = 16;
+constexpr int kMaxGraphs = 64;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+int pad64(int n) { return (n + 63) / 64 * 64; }
+
+// Internal parameter arena: every tensor starts at a multiple of 64 floats; padding stays zero.
+//   conv l : W[k][c_out] with k = (c,ky,kx) for the first layer (uint8 NCHW input) and (ky,kx,c)
+//            for later layers (NHWC activations); b[c_out]
+//   fc     : W[(y,x,c)][fc], b[fc];  pi: W[A][fc], b[A];  v: W[fc], b[1]
+struct Arena {
+    int conv_w[3], conv_b[3], fc_w, fc_b, pi_w, pi_b, v_w, v_b;
+    int p_int;       // padded length
+    size_t P;        // canonical length
+    std::vector<int> map;   // canonical index -> arena index
+};
+
+Arena make_arena(const NetDesc& n) {
+    Arena a{};
+    int off = 0;
+    auto take = [&](int cnt) { int o = off; off += pad64(cnt); return o; };
+    for (int l = 0; l < n.n_conv; ++l) {
+        a.conv_w[l] = take(n.conv[l].kk * n.conv[l].cout);
+        a.conv_b[l] = take(n.conv[l].cout);
+    }
+    a.fc_w = take(n.flat * n.fc); a.fc_b = take(n.fc);
+    a.pi_w = take(n.n_actions * n.fc); a.pi_b = take(n.n_actions);
+    a.v_w = take(n.fc); a.v_b = take(1);
+    a.p_int = off;
+    for (int l = 0; l < n.n_conv; ++l) {
+        const ConvDesc& c = n.conv[l];
+        for (int co = 0; co < c.cout; ++co)
+            for (int ci = 0; ci < c.cin; ++ci)
+                for (int ky = 0; ky < c.ks; ++ky)
+                    for (int kx = 0; kx < c.ks; ++kx) {
+                        const int k = l == 0 ? (ci * c.ks + ky) * c.ks + kx : (ky * c.ks + kx) * c.cin + ci;
+                        a.map.push_back(a.conv_w[l] + k * c.cout + co);
+                    }
+        for (int co = 0; co < c.cout; ++co) a.map.push_back(a.conv_b[l] + co);
+    }
+    const ConvDesc& last = n.conv[n.n_conv - 1];
+    for (int j = 0; j < n.fc; ++j)
+        for (int c = 0; c < last.cout; ++c)
+            for (int y = 0; y < last.ho; ++y)
+                for (int x = 0; x < last.wo; ++x)
+                    a.map.push_back(a.fc_w + ((y * last.wo + x) * last.cout + c) * n.fc + j);
+    for (int j = 0; j < n.fc; ++j) a.map.push_back(a.fc_b + j);
+    for (int i = 0; i < n.n_actions * n.fc; ++i) a.map.push_back(a.pi_w + i);
+    for (int i = 0; i < n.n_actions; ++i) a.map.push_back(a.pi_b + i);
+    for (int i = 0; i < n.fc; ++i) a.map.push_back(a.v_w + i);
+    a.map.push_back(a.v_b);
+    a.P = a.map.size();
+    return a;
+}
+
+struct Plan {
+    int n_e, T, B, Bp;
+    Split sel_fc, trn_fc, wg[3], fc_wg;
+    int head_chunks, n_loss_blocks;
+};
+
+Plan make_plan(const NetDesc& n, int n_e, int T) {
+    Plan p{};
+    p.n_e = n_e; p.T = T; p.B = n_e * T; p.Bp = n_e * (T + 1);
+    p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
+    p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
+    for (int l = 0; l < n.n_conv; ++l)
+        p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 32, 512);
+    p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 512);
+    p.head_chunks = p.B / 64 < 1 ? 1 : (p.B / 64 > 64 ? 64 : p.B / 64);
+    p.n_loss_blocks = loss_blocks(n_e);
+    return p;
+}
+
+// Device workspace, carved in one pass (the same pass computes the size).
+struct Buffers {
+    float *theta, *g2, *grads, *hp, *block_ss, *loss_partials;
+    StatsOut* stats;
+    float* act[3];          // conv outputs, NHWC, Bp rows
+    float *fc_partial, *h, *logits, *values, *returns, *dz, *dv, *dh;
+    float* dact[3];         // gradient w.r.t. conv outputs, B rows
+    float *pw[3], *pb[3], *fc_pw, *fc_pb, *hd_pw, *hd_pb;
+    size_t bytes;
+};
+
+Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, char* base) {
+    Buffers b{};
+    size_t off = 0;
+    auto take = [&](size_t floats) {
+        float* ptr = base ? reinterpret_cast<float*>(base + off) : nullptr;
+        off += align_up(floats * sizeof(float));
+        return ptr;
+    };
+    b.theta = take(a.p_int); b.g2 = take(a.p_int); b.grads = take(a.p_int);
+    b.hp = take(HP_COUNT); b.block_ss = take(kNormBlocks); b.loss_partials = take((size_t)p.n_loss_blocks * 4);
+    b.stats = reinterpret_cast<StatsOut*>(take(16));
+    for (int l = 0; l < n.n_conv; ++l) {
+        const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout;
+        b.act[l] = take(per * p.Bp);
+        b.dact[l] = take(per * p.B);
+    }
+    const size_t fcp_sel = (size_t)p.sel_fc.n * p.n_e * n.fc, fcp_trn = (size_t)p.trn_fc.n * p.Bp * n.fc;
+    b.fc_partial = take(fcp_sel > fcp_trn ? fcp_sel : fcp_trn);
+    b.h = take((size_t)p.Bp * n.fc);
+    b.logits = take((size_t)p.Bp * n.n_actions); b.values = take(p.Bp); b.returns = take(p.B);
+    b.dz = take((size_t)p.B * n.n_actions); b.dv = take(p.B); b.dh = take((size_t)p.B * n.fc);
+    for (int l = 0; l < n.n_conv; ++l) {
+        b.pw[l] = take((size_t)p.wg[l].n * n.conv[l].kk * n.conv[l].cout);
+        b.pb[l] = take((size_t)p.wg[l].n * n.conv[l].cout);
+    }
+    b.fc_pw = take((size_t)p.fc_wg.n * n.flat * n.fc); b.fc_pb = take((size_t)p.fc_wg.n * n.fc);
+    b.hd_pw = take((size_t)p.head_chunks * (n.n_actions + 1) * n.fc);
+    b.hd_pb = take((size_t)p.head_chunks * (n.n_actions + 1));
+    b.bytes = off;
+    return b;
+}
+
+enum KernelId {
+    K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
+    K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_DH, K_TRN_HEADS_WG,
+    K_TRN_FC_WG, K_TRN_FC_DG, K_TRN_CONV3_WG, K_TRN_CONV3_DG, K_TRN_CONV2_WG, K_TRN_CONV2_DG, K_TRN_CONV1_WG,
+    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_COUNT
+};
+const char* const kKernelNames[K_COUNT] = {
+    "select.conv1_fwd", "select.conv2_fwd", "select.conv3_fwd", "select.fc_fwd", "select.heads_sample",
+    "train.conv1_fwd", "train.conv2_fwd", "train.conv3_fwd", "train.fc_fwd", "train.heads_fwd", "train.returns_loss",
+    "train.heads_dh", "train.heads_wgrad", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
+    "train.conv3_dgrad", "train.conv2_wgrad", "train.conv2_dgrad", "train.conv1_wgrad", "train.grad_reduce_norm",
+    "train.clip_rmsprop"};
+
+struct GraphKey {
+    int kind;                 // 0 select, 1 train
+    const void* p[6];
+    bool operator==(const GraphKey& o) const { return kind == o.kind && memcmp(p, o.p, sizeof(p)) == 0; }
+};
+struct GraphEntry { GraphKey key; hipGraph_t graph; hipGraphExec_t exec; };
+
+}  // namespace
+
+struct paac_ctx {
+    paac_config cfg;
+    NetDesc net;
+    Arena arena;
+    Plan plan;
+    Buffers buf;
+    hipStream_t stream;       // caller's stream: all work is enqueued here
+    hipStream_t cap_stream;   // private stream used only for graph capture
+    int device;
+    bool have_params;
+    bool use_graphs, profiling;
+    std::vector<GraphEntry> graphs;
+    // hyper-parameter staging: pinned ring, one event per slot
+    float* hp_pinned;
+    hipEvent_t hp_ev[kHpSlots];
+    bool hp_ev_used[kHpSlots];
+    int hp_next;
+    paac_hparams hp_last;
+    bool hp_valid;
+    // profiling
+    struct Pending { int id; hipEvent_t a, b; };
+    std::vector<Pending> pending;
+    std::vector<hipEvent_t> ev_pool;
+    double k_ms[K_COUNT];
+    int k_calls[K_COUNT];
+    std::string err;
+};
+
+namespace {
+
+int fail(paac_ctx* c, int code, const std::string& msg) {
+    if (c) c->err = msg;
+    return code;
+}
+#define HIP_TRY(ctx, expr)                                                                              \
+    do {                                                                                                \
+        hipError_t e__ = (expr);                                                                        \
+        if (e__ != hipSuccess)                                                                          \
+            return fail(ctx, PAAC_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e__));           \
+    } while (0)
+
+int check_config(const paac_config* cfg, std::string* why) {
+    if (cfg->arch != PAAC_ARCH_NIPS && cfg->arch != PAAC_ARCH_NATURE) { *why = "arch must be 0 (nips) or 1 (nature)"; return PAAC_E_BADCONFIG; }
+    if (cfg->n_e < 1 || cfg->n_e > (1 << 20)) { *why = "n_e out of range"; return PAAC_E_BADCONFIG; }
+    if (cfg->t_max < 1 || cfg->t_max > 4096) { *why = "t_max out of range"; return PAAC_E_BADCONFIG; }
+    if (cfg->n_actions < 2 || cfg->n_actions > PAAC_MAX_ACTIONS) { *why = "n_actions must be 2..32"; return PAAC_E_BADCONFIG; }
+    if (cfg->in_c != 4 || cfg->in_h != 84 || cfg->in_w != 84) { *why = "input must be 4x84x84"; return PAAC_E_BADCONFIG; }
+    if (cfg->precision != PAAC_PREC_FP32) { *why = "only PAAC_PREC_FP32 is implemented"; return PAAC_E_BADCONFIG; }
+    // row counts are held in int: (t_max+1) n_e 400 output positions must fit
+    if ((double)cfg->n_e * (cfg->t_max + 1) * 400.0 * 64.0 > 2.0e9) { *why = "n_e*(t_max+1) too large"; return PAAC_E_BADCONFIG; }
+    return PAAC_OK;
+}
+
+// ---- profiling helpers ----
+hipEvent_t get_event(paac_ctx* c) {
+    if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+int drain_profile(paac_ctx* c) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (auto& p : c->pending) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) { c->k_ms[p.id] += ms; c->k_calls[p.id] += 1; }
+        c->ev_pool.push_back(p.a); c->ev_pool.push_back(p.b);
+    }
+    c->pending.clear();
+    return PAAC_OK;
+}
+
+struct Launcher {
+    paac_ctx* c; hipStream_t s; bool prof; hipError_t err; int err_id;
+    template <class F> void run(int id, F&& f) {
+        if (err != hipSuccess) return;
+        hipEvent_t a = nullptr, b = nullptr;
+        if (prof) { a = get_event(c); b = get_event(c); if (a) hipEventRecord(a, s); }
+        hipError_t e = f();
+        if (prof && a && b) { hipEventRecord(b, s); c->pending.push_back({id, a, b}); }
+        if (e != hipSuccess) { err = e; err_id = id; }
+    }
+};
+
+struct SelectArgs { const uint8_t* states; const float* uniforms; int32_t* actions; float* values; float* probs; };
+struct TrainArgs { const uint8_t* states; const int32_t* actions; const float* rewards; const uint8_t* dones; paac_train_stats* stats; };
+
+// Forward trunk shared by select and train: convs, fc partial sums.
+void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0) {
+    const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf;
+    const void* in = states;
+    for (int l = 0; l < n.n_conv; ++l) {
+        L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], b.act[l], ns); });
+        in = b.act[l];
+    }
+    L.run(id0 + 3, [&] { return fc_fwd(L.s, n.arch, b.act[n.n_conv - 1], b.theta + a.fc_w, b.fc_partial, ns, fc_split); });
+}
+
+hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int* err_id) {
+    Launcher L{c, s, prof, hipSuccess, -1};
+    const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
+    enqueue_trunk(c, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1);
+    HeadsArgs h{};
+    h.fc_partial = b.fc_partial; h.n_split = p.sel_fc.n; h.split_stride = (size_t)p.n_e * n.fc;
+    h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
+    h.v_w = b.theta + a.v_w; h.v_b = b.theta + a.v_b;
+    h.rows = p.n_e; h.A = n.n_actions;
+    h.values_out = x.values; h.uniforms = x.uniforms; h.actions_out = x.actions; h.probs_out = x.probs;
+    L.run(K_SEL_HEADS, [&] { return heads_fwd(L.s, n.fc, h); });
+    *err_id = L.err_id;
+    return L.err;
+}
+
+hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs& x, int* err_id) {
+    Launcher L{c, s, prof, hipSuccess, -1};
+    const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
+    const int A = n.n_actions, F = n.fc, last = n.n_conv - 1;
+    // forward over all (t_max+1) n_e states: rows [0, B) are the batch, rows [B, Bp) the bootstrap
+    enqueue_trunk(c, L, x.states, p.Bp, p.trn_fc, K_TRN_CONV1);
+    HeadsArgs h{};
+    h.fc_partial = b.fc_partial; h.n_split = p.trn_fc.n; h.split_stride = (size_t)p.Bp * F;
+    h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
+    h.v_w = b.theta + a.v_w; h.v_b = b.theta + a.v_b;
+    h.rows = p.Bp; h.A = A; h.h_out = b.h; h.logits_out = b.logits; h.values_out = b.values;
+    L.run(K_TRN_HEADS, [&] { return heads_fwd(L.s, F, h); });
+    LossArgs la{};
+    la.logits = b.logits; la.values = b.values; la.actions = x.actions; la.rewards = x.rewards; la.dones = x.dones;
+    la.hp = b.hp; la.T = p.T; la.n_e = p.n_e; la.A = A;
+    la.returns = b.returns; la.dz = b.dz; la.dv = b.dv; la.loss_partials = b.loss_partials;
+    L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
+    // heads backward
+    L.run(K_TRN_HEADS_DH, [&] { return heads_dh(L.s, F, A, p.B, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, b.dh); });
+    L.run(K_TRN_HEADS_WG, [&] { return heads_wgrad(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.h, b.hd_pw, b.hd_pb); });
+    // fc backward
+    L.run(K_TRN_FC_WG, [&] { return fc_wgrad(L.s, n.arch, b.act[last], b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
+    L.run(K_TRN_FC_DG, [&] { return fc_dgrad(L.s, n.arch, b.dh, b.theta + a.fc_w, b.act[last], b.dact[last], p.B); });
+    // conv backward, last layer first
+    for (int l = last; l >= 0; --l) {
+        const void* in = l == 0 ? (const void*)x.states : (const void*)b.act[l - 1];
+        const int wg_id = l == 2 ? K_TRN_CONV3_WG : l == 1 ? K_TRN_CONV2_WG : K_TRN_CONV1_WG;
+        L.run(wg_id, [&] { return conv_wgrad(L.s, n.arch, l, in, b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
+        if (l > 0) {
+            const int dg_id = l == 2 ? K_TRN_CONV3_DG : K_TRN_CONV2_DG;
+            L.run(dg_id, [&] { return conv_dgrad(L.s, n.arch, l, b.dact[l], b.theta + a.conv_w[l], b.act[l - 1], b.dact[l - 1], p.B); });
+        }
+    }
+    // reduce split gradients, global norm, clip + RMSProp
+    GradSegments g{};
+    auto seg = [&](const float* ptr, int nsplit, size_t stride, int count, int off) {
+        g.partial[g.n] = ptr; g.n_split[g.n] = nsplit; g.stride[g.n] = stride; g.count[g.n] = count; g.off[g.n] = off;
+        g.padded[g.n] = pad64(count); ++g.n;
+    };
+    for (int l = 0; l < n.n_conv; ++l) {
+        const int wn = n.conv[l].kk * n.conv[l].cout;
+        seg(b.pw[l], p.wg[l].n, wn, wn, a.conv_w[l]);
+        seg(b.pb[l], p.wg[l].n, n.conv[l].cout, n.conv[l].cout, a.conv_b[l]);
+    }
+    seg(b.fc_pw, p.fc_wg.n, (size_t)n.flat * F, n.flat * F, a.fc_w);
+    seg(b.fc_pb, p.fc_wg.n, F, F, a.fc_b);
+    seg(b.hd_pw, p.head_chunks, (size_t)(A + 1) * F, A * F, a.pi_w);
+    seg(b.hd_pb, p.head_chunks, A + 1, A, a.pi_b);
+    seg(b.hd_pw + (size_t)A * F, p.head_chunks, (size_t)(A + 1) * F, F, a.v_w);
+    seg(b.hd_pb + A, p.head_chunks, A + 1, 1, a.v_b);
+    L.run(K_TRN_GRAD_REDUCE, [&] { return grad_reduce_norm(L.s, g, a.p_int, b.grads, b.block_ss); });
+    L.run(K_TRN_RMSPROP, [&] {
+        return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, b.hp, b.loss_partials, p.n_loss_blocks,
+                              b.stats, reinterpret_cast<StatsOut*>(x.stats));
+    });
+    *err_id = L.err_id;
+    return L.err;
+}
+
+template <class Enq>
+int run_or_replay(paac_ctx* c, const GraphKey& key, Enq&& enq) {
+    int err_id = -1;
+    if (c->profiling || !c->use_graphs) {
+        if (c->profiling && c->pending.size() > 16384) { int r = drain_profile(c); if (r) return r; }
+        hipError_t e = enq(c->stream, c->profiling, &err_id);
+        if (e != hipSuccess)
+            return fail(c, PAAC_E_HIP, std::string("launch of ") + (err_id >= 0 ? kKernelNames[err_id] : "?") + ": " + hipGetErrorString(e));
+        return PAAC_OK;
+    }
+    for (auto& g : c->graphs)
+        if (g.key == key) { HIP_TRY(c, hipGraphLaunch(g.exec, c->stream)); return PAAC_OK; }
+    if ((int)c->graphs.size() >= kMaxGraphs) {      // too many distinct argument tuples: launch directly
+        hipError_t e = enq(c->stream, false, &err_id);
+        if (e != hipSuccess) return fail(c, PAAC_E_HIP, std::string("launch: ") + hipGetErrorString(e));
+        return PAAC_OK;
+    }
+    // Capture on the private stream.  It must see everything already enqueued on the caller's stream
+    // only at replay time, and the replay is launched on the caller's stream, so no dependency is
+    // needed here.
+    GraphEntry ge{};
+    ge.key = key;
+    HIP_TRY(c, hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeThreadLocal));
+    hipError_t e = enq(c->cap_stream, false, &err_id);
+    hipError_t e2 = hipStreamEndCapture(c->cap_stream, &ge.graph);
+    if (e != hipSuccess || e2 != hipSuccess) {
+        if (e2 == hipSuccess && ge.graph) hipGraphDestroy(ge.graph);
+        return fail(c, PAAC_E_HIP, std::string("graph capture failed at ") + (err_id >= 0 ? kKernelNames[err_id] : "end") +
+                                       ": " + hipGetErrorString(e != hipSuccess ? e : e2));
+    }
+    hipError_t e3 = hipGraphInstantiate(&ge.exec, ge.graph, nullptr, nullptr, 0);
+    if (e3 != hipSuccess) { hipGraphDestroy(ge.graph); return fail(c, PAAC_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e3)); }
+    c->graphs.push_back(ge);
+    HIP_TRY(c, hipGraphLaunch(ge.exec, c->stream));
+    return PAAC_OK;
+}
+
+int upload_hparams(paac_ctx* c, const paac_hparams* hp) {
+    if (c->hp_valid && memcmp(&c->hp_last, hp, sizeof(*hp)) == 0) return PAAC_OK;
+    const int slot = c->hp_next;
+    c->hp_next = (c->hp_next + 1) % kHpSlots;
+    if (c->hp_ev_used[slot]) HIP_TRY(c, hipEventSynchronize(c->hp_ev[slot]));
+    float* dst = c->hp_pinned + slot * HP_COUNT;
+    dst[HP_GAMMA] = hp->gamma; dst[HP_BETA] = hp->beta; dst[HP_VCOEF] = hp->value_coef; dst[HP_LR] = hp->lr;
+    dst[HP_ALPHA] = hp->rms_alpha; dst[HP_EPS] = hp->rms_eps; dst[HP_CLIP] = hp->clip_norm; dst[7] = 0.f;
+    HIP_TRY(c, hipMemcpyAsync(c->buf.hp, dst, HP_COUNT * sizeof(float), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipEventRecord(c->hp_ev[slot], c->stream));
+    c->hp_ev_used[slot] = true;
+    c->hp_last = *hp;
+    c->hp_valid = true;
+    return PAAC_OK;
+}
+
+struct DeviceGuard {
+    int prev; bool ok;
+    explicit DeviceGuard(int dev) : prev(-1), ok(false) {
+        if (hipGetDevice(&prev) == hipSuccess) { ok = (prev == dev) || hipSetDevice(dev) == hipSuccess; }
+    }
+    ~DeviceGuard() { if (prev >= 0) hipSetDevice(prev); }
+};
+
+}  // namespace
+
+extern "C" {
+
+int paac_workspace_bytes(const paac_config* cfg, size_t* bytes_out) {
+    if (!cfg || !bytes_out) return PAAC_E_NULL;
+    std::string why;
+    int r = check_config(cfg, &why);
+    if (r) return r;
+    const NetDesc n = make_net(cfg->arch, cfg->n_actions);
+    const Arena a = make_arena(n);
+    const Plan p = make_plan(n, cfg->n_e, cfg->t_max);
+    *bytes_out = carve(n, a, p, nullptr).bytes;
+    return PAAC_OK;
+}
+
+int paac_create(const paac_config* cfg, void* workspace_dev, size_t workspace_bytes, void* hip_stream, paac_ctx** ctx_out) {
+    if (!cfg || !ctx_out) return PAAC_E_NULL;
+    *ctx_out = nullptr;
+    std::string why;
+    int r = check_config(cfg, &why);
+    if (r) return r;
+    if (!workspace_dev) return PAAC_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign != 0) return PAAC_E_WORKSPACE;
+    paac_ctx* c = new paac_ctx();
+    c->cfg = *cfg;
+    c->net = make_net(cfg->arch, cfg->n_actions);
+    c->arena = make_arena(c->net);
+    c->plan = make_plan(c->net, cfg->n_e, cfg->t_max);
+    c->buf = carve(c->net, c->arena, c->plan, static_cast<char*>(workspace_dev));
+    if (c->buf.bytes > workspace_bytes) { delete c; return PAAC_E_WORKSPACE; }
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->have_params = false; c->use_graphs = true; c->profiling = false;
+    c->hp_next = 0; c->hp_valid = false;
+    memset(c->hp_ev_used, 0, sizeof(c->hp_ev_used));
+    memset(c->k_ms, 0, sizeof(c->k_ms)); memset(c->k_calls, 0, sizeof(c->k_calls));
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->hp_pinned), kHpSlots * HP_COUNT * sizeof(float), hipHostMallocDefault);
+    for (int i = 0; i < kHpSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->hp_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) { delete c; return PAAC_E_HIP; }
+    *ctx_out = c;
+    return PAAC_OK;
+}
+
+void paac_destroy(paac_ctx* c) {
+    if (!c) return;
+    hipStreamSynchronize(c->stream);
+    for (auto& g : c->graphs) { hipGraphExecDestroy(g.exec); hipGraphDestroy(g.graph); }
+    for (auto& p : c->pending) { hipEventDestroy(p.a); hipEventDestroy(p.b); }
+    for (auto e : c->ev_pool) hipEventDestroy(e);
+    for (int i = 0; i < kHpSlots; ++i) hipEventDestroy(c->hp_ev[i]);
+    if (c->hp_pinned) hipHostFree(c->hp_pinned);
+    if (c->cap_stream) hipStreamDestroy(c->cap_stream);
+    delete c;
+}
+
+size_t paac_param_count(const paac_ctx* c) { return c ? c->arena.P : 0; }
+
+int paac_set_state(paac_ctx* c, const float* params_host, const float* rms_host) {
+    if (!c || !params_host) return c ? fail(c, PAAC_E_NULL, "params_host is NULL") : PAAC_E_NULL;
+    const Arena& a = c->arena;
+    std::vector<float> th(a.p_int, 0.f), g2(a.p_int, 0.f);
+    for (size_t i = 0; i < a.P; ++i) {
+        th[a.map[i]] = params_host[i];
+        if (rms_host) g2[a.map[i]] = rms_host[i];
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(c->buf.theta, th.data(), a.p_int * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->buf.g2, g2.data(), a.p_int * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemset(c->buf.grads, 0, a.p_int * sizeof(float)));
+    HIP_TRY(c, hipDeviceSynchronize());
+    c->have_params = true;
+    return PAAC_OK;
+}
+
+int paac_get_state(paac_ctx* c, float* params_host, float* rms_host, float* grads_host) {
+    if (!c) return PAAC_E_NULL;
+    if (!c->have_params) return fail(c, PAAC_E_STATE, "no parameters: call paac_init_params or paac_set_state first");
+    const Arena& a = c->arena;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::vector<float> tmp(a.p_int);
+    float* dst[3] = {params_host, rms_host, grads_host};
+    const float* src[3] = {c->buf.theta, c->buf.g2, c->buf.grads};
+    for (int k = 0; k < 3; ++k) {
+        if (!dst[k]) continue;
+        HIP_TRY(c, hipMemcpy(tmp.data(), src[k], a.p_int * sizeof(float), hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < a.P; ++i) dst[k][i] = tmp[a.map[i]];
+    }
+    return PAAC_OK;
+}
+
+int paac_init_params(paac_ctx* c, uint64_t seed) {
+    if (!c) return PAAC_E_NULL;
+    const NetDesc& n = c->net;
+    const size_t P = c->arena.P;
+    std::vector<float> u(P), th(P, 0.f);
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (size_t blk = 0; blk * 4 < P; ++blk) {
+        const uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)((uint64_t)blk >> 32), 0u, 0u};
+        uint32_t w[4];
+        philox4x32_10(ctr, key, w);
+        for (int i = 0; i < 4 && blk * 4 + i < P; ++i) u[blk * 4 + i] = (float)(w[i] >> 8) * (1.0f / 16777216.0f);
+    }
+    size_t off = 0;
+    auto glorot = [&](size_t cnt, double fan_in, double fan_out) {
+        const float l = (float)sqrt(6.0 / (fan_in + fan_out));
+        for (size_t i = 0; i < cnt; ++i) th[off + i] = l * (2.0f * u[off + i] - 1.0f);
+        off += cnt;
+    };
+    for (int l = 0; l < n.n_conv; ++l) {
+        const ConvDesc& cv = n.conv[l];
+        const double kk = (double)cv.ks * cv.ks;
+        glorot((size_t)cv.cout * cv.cin * cv.ks * cv.ks, cv.cin * kk, cv.cout * kk);
+        off += cv.cout;
+    }
+    glorot((size_t)n.fc * n.flat, n.flat, n.fc); off += n.fc;
+    glorot((size_t)n.n_actions * n.fc, n.fc, n.n_actions); off += n.n_actions;
+    glorot((size_t)n.fc, n.fc, 1); off += 1;
+    return paac_set_state(c, th.data(), nullptr);
+}
+
+int paac_select_actions(paac_ctx* c, const uint8_t* states_dev, const float* uniforms_dev, int32_t* actions_dev,
+                        float* values_dev, float* probs_dev) {
+    if (!c) return PAAC_E_NULL;
+    if (!states_dev || !uniforms_dev || !actions_dev) return fail(c, PAAC_E_NULL, "states, uniforms and actions are required");
+    if (!c->have_params) return fail(c, PAAC_E_STATE, "no parameters: call paac_init_params or paac_set_state first");
+    if (reinterpret_cast<uintptr_t>(states_dev) % 4 != 0) return fail(c, PAAC_E_BADCONFIG, "states_dev must be 4-byte aligned");
+    DeviceGuard dg(c->device);
+    const SelectArgs x{states_dev, uniforms_dev, actions_dev, values_dev, probs_dev};
+    GraphKey key{};
+    key.kind = 0; key.p[0] = states_dev; key.p[1] = uniforms_dev; key.p[2] = actions_dev; key.p[3] = values_dev; key.p[4] = probs_dev;
+    return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, s, prof, x, id); });
+}
+
+int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actions_dev, const float* rewards_dev,
+                    const uint8_t* dones_dev, const paac_hparams* hp_host, paac_train_stats* stats_dev) {
+    if (!c) return PAAC_E_NULL;
+    if (!states_dev || !actions_dev || !rewards_dev || !dones_dev || !hp_host)
+        return fail(c, PAAC_E_NULL, "states, actions, rewards, dones and hp are required");
+    if (!c->have_params) return fail(c, PAAC_E_STATE, "no parameters: call paac_init_params or paac_set_state first");
+    if (reinterpret_cast<uintptr_t>(states_dev) % 4 != 0) return fail(c, PAAC_E_BADCONFIG, "states_dev must be 4-byte aligned");
+    const paac_hparams& h = *hp_host;
+    if (!(h.gamma >= 0.f && h.gamma <= 1.f) || !(h.rms_alpha >= 0.f && h.rms_alpha < 1.f) || !(h.rms_eps > 0.f) ||
+        !(h.clip_norm > 0.f) || !isfinite(h.lr) || !isfinite(h.beta) || !isfinite(h.value_coef))
+        return fail(c, PAAC_E_BADCONFIG, "hyper-parameter out of range");
+    DeviceGuard dg(c->device);
+    int r = upload_hparams(c, hp_host);
+    if (r) return r;
+    const TrainArgs x{states_dev, actions_dev, rewards_dev, dones_dev, stats_dev};
+    GraphKey key{};
+    key.kind = 1; key.p[0] = states_dev; key.p[1] = actions_dev; key.p[2] = rewards_dev; key.p[3] = dones_dev; key.p[4] = stats_dev;
+    return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_train(c, s, prof, x, id); });
+}
+
+int paac_get_train_outputs(paac_ctx* c, float* logits_host, float* values_host, float* returns_host) {
+    if (!c) return PAAC_E_NULL;
+    const Plan& p = c->plan;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (logits_host) HIP_TRY(c, hipMemcpy(logits_host, c->buf.logits, (size_t)p.Bp * c->net.n_actions * sizeof(float), hipMemcpyDeviceToHost));
+    if (values_host) HIP_TRY(c, hipMemcpy(values_host, c->buf.values, (size_t)p.Bp * sizeof(float), hipMemcpyDeviceToHost));
+    if (returns_host) HIP_TRY(c, hipMemcpy(returns_host, c->buf.returns, (size_t)p.B * sizeof(float), hipMemcpyDeviceToHost));
+    return PAAC_OK;
+}
+
+int paac_fill_uniforms(paac_ctx* c, uint64_t seed, uint64_t offset, float* out_dev, size_t n) {
+    if (!c) return PAAC_E_NULL;
+    if (!out_dev && n) return fail(c, PAAC_E_NULL, "out_dev is NULL");
+    DeviceGuard dg(c->device);
+    HIP_TRY(c, fill_uniforms(c->stream, seed, offset, out_dev, n));
+    return PAAC_OK;
+}
+
+int paac_set_graphs(paac_ctx* c, int use_graphs) {
+    if (!c) return PAAC_E_NULL;
+    c->use_graphs = use_graphs != 0;
+    return PAAC_OK;
+}
+
+int paac_set_profiling(paac_ctx* c, int enabled) {
+    if (!c) return PAAC_E_NULL;
+    int r = drain_profile(c);
+    if (r) return r;
+    if (enabled && !c->profiling) { memset(c->k_ms, 0, sizeof(c->k_ms)); memset(c->k_calls, 0, sizeof(c->k_calls)); }
+    c->profiling = enabled != 0;
+    return PAAC_OK;
+}
+
+int paac_kernel_times(paac_ctx* c, int cap, const char** name_out, float* ms_out, int32_t* calls_out, int32_t* n_out) {
+    if (!c || !name_out || !ms_out || !calls_out || !n_out) return PAAC_E_NULL;
+    int r = drain_profile(c);
+    if (r) return r;
+    int n = 0;
+    for (int i = 0; i < K_COUNT && n < cap; ++i) {
+        if (c->k_calls[i] == 0) continue;
+        name_out[n] = kKernelNames[i]; ms_out[n] = (float)c->k_ms[i]; calls_out[n] = c->k_calls[i]; ++n;
+    }
+    *n_out = n;
+    return PAAC_OK;
+}
+
+int paac_flops(const paac_ctx* c, double* select_flops, double* train_flops) {
+    if (!c) return PAAC_E_NULL;
+    const NetDesc& n = c->net;
+    double fwd = 0.0;
+    for (int l = 0; l < n.n_conv; ++l) fwd += 2.0 * n.conv[l].ho * n.conv[l].wo * n.conv[l].kk * n.conv[l].cout;
+    fwd += 2.0 * n.flat * n.fc + 2.0 * n.fc * (n.n_actions + 1);
+    const double conv1 = 2.0 * n.conv[0].ho * n.conv[0].wo * n.conv[0].kk * n.conv[0].cout;
+    const double bwd = 2.0 * fwd - conv1;   // weight + data gradient of every layer, no data gradient for the input
+    if (select_flops) *select_flops = fwd * c->plan.n_e;
+    if (train_flops) *train_flops = fwd * c->plan.Bp + bwd * c->plan.B;
+    return PAAC_OK;
+}
+
+const char* paac_last_error(const paac_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Internal interfaces between the translation units of libpaac (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace paac {
+
+// Static description of one of the two networks (Experiments: arch_nips, arch_nature).
+struct ConvDesc { int cin, h, w, ks, st, cout, ho, wo, kk; };
+struct NetDesc {
+    int arch, n_conv;
+    ConvDesc conv[3];
+    int flat, fc, n_actions;
+};
+NetDesc make_net(int arch, int n_actions);
+
+// How one contraction is split over workgroups along its reduction dimension.
+struct Split { int n; int k_per; };
+Split plan_split(int k_total, int tiles, int granule, int target_wgs);
+
+// ---- dense layers (layers.hip); all activations are NHWC, weights are [K][c_out] ----
+// conv forward + bias + ReLU over `ns` samples.  Layer 0 reads uint8 NCHW states (k = c,ky,kx),
+// later layers read float NHWC (k = ky,kx,c).
+hipError_t conv_fwd(hipStream_t s, int arch, int layer, const void* in, const float* W, const float* b,
+                    float* out, int ns);
+// dX = dY (*) W^T in gather form, multiplied by ReLU'(act_in); layer >= 1.
+hipError_t conv_dgrad(hipStream_t s, int arch, int layer, const float* dy, const float* W,
+                      const float* act_in, float* dx, int ns);
+// partial_w[split][K][c_out], partial_b[split][c_out]; rows of the reduction are output positions.
+int conv_wgrad_tiles(int arch, int layer);
+hipError_t conv_wgrad(hipStream_t s, int arch, int layer, const void* in, const float* dy, float* partial_w,
+                      float* partial_b, int ns, Split sp);
+// fc forward: partial[split][ns][fc] = x[ns][flat(k-range)] . W[flat][fc]   (no bias, no ReLU)
+int fc_fwd_tiles(int arch, int ns);
+hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float* partial, int ns, Split sp);
+// dx[ns][flat] = (dh[ns][fc] . W^T) * 1[act > 0]
+hipError_t fc_dgrad(hipStream_t s, int arch, const float* dh, const float* W, const float* act, float* dx, int ns);
+// partial_w[split][flat][fc] = x^T . dh over a range of samples; partial_b[split][fc] = column sums of dh
+int fc_wgrad_tiles(int arch);
+hipError_t fc_wgrad(hipStream_t s, int arch, const float* x, const float* dh, float* partial_w, float* partial_b,
+                    int ns, Split sp);
+
+// ---- small kernels (small_kernels.hip) ----
+struct HeadsArgs {
+    const float* fc_partial; int n_split; size_t split_stride;   // [split][rows][F]
+    const float* fc_b; const float* pi_w; const float* pi_b; const float* v_w; const float* v_b;
+    int rows, A;
+    float* h_out;          // [rows][F] or null
+    float* logits_out;     // [rows][A] or null
+    float* values_out;     // [rows] or null
+    const float* uniforms; // select mode when non-null
+    int32_t* actions_out;  // [rows]
+    float* probs_out;      // [rows][A] or null
+};
+hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a);
+
+struct LossArgs {
+    const float* logits; const float* values;           // [(T+1) n_e][A], [(T+1) n_e]
+    const int32_t* actions; const float* rewards; const uint8_t* dones;
+    const float* hp;                                     // device hyper-parameters (HP_* indices)
+    int T, n_e, A;
+    float* returns; float* dz; float* dv;                // [T n_e], [T n_e][A], [T n_e]
+    float* loss_partials;                                // [blocks][4]
+};
+int loss_blocks(int n_e);
+hipError_t returns_loss(hipStream_t s, const LossArgs& a);
+
+hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
+                    const float* v_w, const float* h, float* dh);
+// partial_w[chunk][A+1][F] (row A = value head), partial_b[chunk][A+1]
+hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
+                       const float* h, float* partial_w, float* partial_b);
+
+enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };
+
+constexpr int kMaxSeg = 12;
+constexpr int kNormBlocks = 256;
+struct GradSegments {
+    int n;
+    const float* partial[kMaxSeg]; int n_split[kMaxSeg]; size_t stride[kMaxSeg];
+    int count[kMaxSeg]; int off[kMaxSeg]; int padded[kMaxSeg];
+};
+// grads[i] = sum over splits of the partial gradients; block_ss[kNormBlocks] = partial sums of g^2
+hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss);
+struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
+hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
+                          const float* block_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
+                          StatsOut* stats_a, StatsOut* stats_b);
+hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n);
+
+// host-side Philox4x32-10 (api uses it for parameter initialisation)
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+}  // namespace paac

@@ -1,0 +1,199 @@
+// Dense layers of the PAAC network on the MFMA GEMM core: convolution forward / data gradient /
+// weight gradient and the hidden fully connected layer, for the two networks of the paper's
+// Experiments section (arch_nips: 16@8x8/4, 32@4x4/2, fc 256; arch_nature: 32@8x8/4, 64@4x4/2,
+// 64@3x3/1, fc 512; input 4x84x84, no padding).
+#include "gemm_core.hip.h"
+#include "internal.h"
+
+namespace paac {
+
+typedef ConvGeom<4, 84, 84, 8, 4, 16> NipsC1;
+typedef ConvGeom<16, 20, 20, 4, 2, 32> NipsC2;
+typedef ConvGeom<4, 84, 84, 8, 4, 32> NatC1;
+typedef ConvGeom<32, 20, 20, 4, 2, 64> NatC2;
+typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
+
+// tile shapes: BM, BN, BK, waves along m, waves along n, MFMA edge
+typedef Tile<128, 16, 32, 4, 1, 16> T128x16;
+typedef Tile<128, 32, 32, 4, 1, 32> T128x32;
+typedef Tile<64, 64, 32, 2, 2, 32> T64x64;
+typedef Tile<32, 128, 32, 1, 4, 32> T32x128;
+typedef Tile<64, 16, 32, 4, 1, 16> T64x16;
+
+template <int N> struct TileForN;
+template <> struct TileForN<16> { typedef T128x16 type; typedef T64x16 wg; };
+template <> struct TileForN<32> { typedef T128x32 type; typedef T128x32 wg; };
+template <> struct TileForN<64> { typedef T64x64 type; typedef T64x64 wg; };
+
+NetDesc make_net(int arch, int n_actions) {
+    NetDesc n{};
+    n.arch = arch;
+    n.n_actions = n_actions;
+    auto set = [](ConvDesc& c, int cin, int h, int w, int ks, int st, int cout) {
+        c.cin = cin; c.h = h; c.w = w; c.ks = ks; c.st = st; c.cout = cout;
+        c.ho = (h - ks) / st + 1; c.wo = (w - ks) / st + 1; c.kk = ks * ks * cin;
+    };
+    if (arch == 0) {
+        n.n_conv = 2;
+        set(n.conv[0], 4, 84, 84, 8, 4, 16);
+        set(n.conv[1], 16, 20, 20, 4, 2, 32);
+        n.fc = 256;
+    } else {
+        n.n_conv = 3;
+        set(n.conv[0], 4, 84, 84, 8, 4, 32);
+        set(n.conv[1], 32, 20, 20, 4, 2, 64);
+        set(n.conv[2], 64, 9, 9, 3, 1, 64);
+        n.fc = 512;
+    }
+    const ConvDesc& l = n.conv[n.n_conv - 1];
+    n.flat = l.ho * l.wo * l.cout;
+    return n;
+}
+
+Split plan_split(int k_total, int tiles, int granule, int target_wgs) {
+    int n = target_wgs / (tiles > 0 ? tiles : 1);
+    if (n < 1) n = 1;
+    int k_per = (k_total + n - 1) / n;
+    k_per = (k_per + granule - 1) / granule * granule;
+    if (k_per < granule) k_per = granule;
+    Split s;
+    s.k_per = k_per;
+    s.n = (k_total + k_per - 1) / k_per;
+    if (s.n < 1) s.n = 1;
+    return s;
+}
+
+// ---------------------------------------------------------------------------------- forward
+template <class G>
+static hipError_t conv_fwd_u8(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
+    typedef typename TileForN<G::COUT>::type T;
+    const int M = ns * G::HO * G::WO;
+    ConvU8RowsK<G> al{(const uint8_t*)in, M};
+    DenseKCols bl{W, G::COUT, G::COUT};
+    EpiBiasRelu ep{out, b, G::COUT};
+    return launch_gemm<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+}
+template <class G>
+static hipError_t conv_fwd_f32(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
+    typedef typename TileForN<G::COUT>::type T;
+    const int M = ns * G::HO * G::WO;
+    ConvNHWCRowsK<G> al{(const float*)in, M};
+    DenseKCols bl{W, G::COUT, G::COUT};
+    EpiBiasRelu ep{out, b, G::COUT};
+    return launch_gemm<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+}
+
+hipError_t conv_fwd(hipStream_t s, int arch, int layer, const void* in, const float* W, const float* b,
+                    float* out, int ns) {
+    if (arch == 0) {
+        if (layer == 0) return conv_fwd_u8<NipsC1>(s, in, W, b, out, ns);
+        if (layer == 1) return conv_fwd_f32<NipsC2>(s, in, W, b, out, ns);
+    } else {
+        if (layer == 0) return conv_fwd_u8<NatC1>(s, in, W, b, out, ns);
+        if (layer == 1) return conv_fwd_f32<NatC2>(s, in, W, b, out, ns);
+        if (layer == 2) return conv_fwd_f32<NatC3>(s, in, W, b, out, ns);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- data gradient
+template <class G>
+static hipError_t conv_dgrad_t(hipStream_t s, const float* dy, const float* W, const float* act_in, float* dx, int ns) {
+    typedef typename TileForN<G::CIN>::type T;
+    const int M = ns * G::HC * G::WC;     // rows per parity class
+    DgradGatherRowsK<G> al{dy, M};
+    DgradWeightColsK<G> bl{W};
+    EpiDgradMask<G> ep{dx, act_in};
+    return launch_gemm<T>(s, al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0);
+}
+
+hipError_t conv_dgrad(hipStream_t s, int arch, int layer, const float* dy, const float* W,
+                      const float* act_in, float* dx, int ns) {
+    if (arch == 0 && layer == 1) return conv_dgrad_t<NipsC2>(s, dy, W, act_in, dx, ns);
+    if (arch == 1 && layer == 1) return conv_dgrad_t<NatC2>(s, dy, W, act_in, dx, ns);
+    if (arch == 1 && layer == 2) return conv_dgrad_t<NatC3>(s, dy, W, act_in, dx, ns);
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- weight gradient
+template <class G> static int wgrad_tiles_t() {
+    typedef typename TileForN<G::COUT>::wg T;
+    return ((G::KK + T::BM - 1) / T::BM) * ((G::COUT + T::BN - 1) / T::BN);
+}
+int conv_wgrad_tiles(int arch, int layer) {
+    if (arch == 0) return layer == 0 ? wgrad_tiles_t<NipsC1>() : wgrad_tiles_t<NipsC2>();
+    return layer == 0 ? wgrad_tiles_t<NatC1>() : layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
+}
+
+template <class G, bool U8>
+static hipError_t conv_wgrad_t(hipStream_t s, const void* in, const float* dy, float* pw, float* pb, int ns, Split sp) {
+    typedef typename TileForN<G::COUT>::wg T;
+    const int R = ns * G::HO * G::WO;     // reduction length
+    DenseKCols bl{dy, G::COUT, G::COUT};
+    EpiPartial<true> ep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
+    if constexpr (U8) {
+        ConvU8KCols<G> al{(const uint8_t*)in, R};
+        return launch_gemm<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
+    } else {
+        ConvNHWCKCols<G> al{(const float*)in, R};
+        return launch_gemm<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
+    }
+}
+
+hipError_t conv_wgrad(hipStream_t s, int arch, int layer, const void* in, const float* dy, float* pw, float* pb,
+                      int ns, Split sp) {
+    if (arch == 0) {
+        if (layer == 0) return conv_wgrad_t<NipsC1, true>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NipsC2, false>(s, in, dy, pw, pb, ns, sp);
+    } else {
+        if (layer == 0) return conv_wgrad_t<NatC1, true>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NatC2, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 2) return conv_wgrad_t<NatC3, false>(s, in, dy, pw, pb, ns, sp);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- fully connected
+static void fc_dims(int arch, int& flat, int& fc) {
+    if (arch == 0) { flat = 2592; fc = 256; } else { flat = 3136; fc = 512; }
+}
+static bool fc_small(int ns) { return ns <= 48; }
+
+int fc_fwd_tiles(int arch, int ns) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    if (fc_small(ns)) return ((ns + 31) / 32) * (fc / 128);
+    return ((ns + 63) / 64) * (fc / 64);
+}
+
+hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float* partial, int ns, Split sp) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseRowsK al{x, ns, flat};
+    DenseKCols bl{W, fc, fc};
+    EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
+    if (fc_small(ns)) return launch_gemm<T32x128>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+    return launch_gemm<T64x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+}
+
+hipError_t fc_dgrad(hipStream_t s, int arch, const float* dh, const float* W, const float* act, float* dx, int ns) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseRowsK al{dh, ns, fc};
+    DenseRowsK bl{W, flat, fc};          // B(k = j, n = i) = W[i][j]
+    EpiDenseMask ep{dx, act, flat};
+    if (fc_small(ns)) return launch_gemm<T32x128>(s, al, bl, ep, ns, flat, fc, 1, 0);
+    return launch_gemm<T64x64>(s, al, bl, ep, ns, flat, fc, 1, 0);
+}
+
+int fc_wgrad_tiles(int arch) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    return ((flat + 63) / 64) * (fc / 64);
+}
+
+hipError_t fc_wgrad(hipStream_t s, int arch, const float* x, const float* dh, float* pw, float* pb, int ns, Split sp) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseKCols al{x, flat, flat};        // A(m = i, k = sample) = x[sample][i]
+    DenseKCols bl{dh, fc, fc};
+    EpiPartial<true> ep{pw, (size_t)flat * fc, fc, pb, fc};
+    return launch_gemm<T64x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per);
+}
+
+}  // namespace paac

@@ -1,0 +1,333 @@
+// The non-GEMM kernels of the PAAC step: policy/value heads with softmax and the categorical
+// draw (Algorithm 1, action selection), the n-step return scan with advantages, losses and their
+// derivatives w.r.t. logits and V (Algorithm 1, bootstrap / recursion / gradient lines; Section 4),
+// the head gradients, the split-gradient reduction with the global L2 norm, and the fused
+// clip + RMSProp update (Experiments: RMSProp, gradient clipping).  All arithmetic is fp32.
+#include "internal.h"
+#include <math.h>
+
+namespace paac {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------------------------ heads
+// One wavefront per state row.  The fc layer's split partial sums are added, bias and ReLU applied,
+// then A+1 dot products (policy logits, value) are reduced across the 64 lanes; lane k ends up
+// holding logit k.  In select mode the same wavefront computes the softmax and draws the action.
+template <int F>
+__global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
+    constexpr int C = F / 256;            // float4 chunks per lane
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= a.rows) return;
+    float4 h[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const int col = c * 256 + lane * 4;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < a.n_split; ++s) {
+            const float4 p = *reinterpret_cast<const float4*>(a.fc_partial + s * a.split_stride + (size_t)row * F + col);
+            acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
+        }
+        const float4 b = *reinterpret_cast<const float4*>(a.fc_b + col);
+        acc.x = fmaxf(acc.x + b.x, 0.f); acc.y = fmaxf(acc.y + b.y, 0.f);
+        acc.z = fmaxf(acc.z + b.z, 0.f); acc.w = fmaxf(acc.w + b.w, 0.f);
+        h[c] = acc;
+        if (a.h_out) *reinterpret_cast<float4*>(a.h_out + (size_t)row * F + col) = acc;
+    }
+    float z = -INFINITY, v = 0.f;
+    for (int k = 0; k <= a.A; ++k) {
+        const float* w = k < a.A ? a.pi_w + (size_t)k * F : a.v_w;
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const float4 w4 = *reinterpret_cast<const float4*>(w + c * 256 + lane * 4);
+            d += h[c].x * w4.x + h[c].y * w4.y + h[c].z * w4.z + h[c].w * w4.w;
+        }
+        d = wave_sum(d);
+        if (k < a.A) { if (lane == k) z = d + a.pi_b[k]; }
+        else v = d + a.v_b[0];
+    }
+    if (a.values_out && lane == 0) a.values_out[row] = v;
+    if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
+    if (a.uniforms) {
+        const float m = wave_max(z);
+        const float e = lane < a.A ? expf(z - m) : 0.f;
+        const float p = e / wave_sum(e);
+        if (a.probs_out && lane < a.A) a.probs_out[(size_t)row * a.A + lane] = p;
+        const float u = a.uniforms[row];
+        float cdf = 0.f;
+        int act = a.A - 1;
+        bool found = false;
+        for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
+            cdf = cdf + __shfl(p, k, 64);
+            if (!found && u < cdf) { act = k; found = true; }
+        }
+        if (lane == 0) a.actions_out[row] = act;
+    }
+}
+
+hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a) {
+    if (a.rows <= 0) return hipErrorInvalidValue;
+    dim3 grid((a.rows + 3) / 4);
+    if (F == 256) hipLaunchKernelGGL(heads_fwd_kernel<256>, grid, dim3(256), 0, s, a);
+    else if (F == 512) hipLaunchKernelGGL(heads_fwd_kernel<512>, grid, dim3(256), 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ returns + loss
+// A block owns kEnvPerBlock environments.  Phase 1: one thread per environment runs the backward
+// recursion R_t = r_t + gamma (1 - d_t) R_{t+1} from R_{T+1} = V(s_{T+1}).  Phase 2: one thread per
+// (t, e) row forms adv = R - V, the three loss terms and dL/dlogits, dL/dV.
+constexpr int kEnvPerBlock = 32;
+int loss_blocks(int n_e) { return (n_e + kEnvPerBlock - 1) / kEnvPerBlock; }
+
+__global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
+    const int tid = threadIdx.x;
+    const int e0 = blockIdx.x * kEnvPerBlock;
+    const int ne_blk = min(kEnvPerBlock, a.n_e - e0);
+    const int B = a.T * a.n_e;
+    const float gamma = a.hp[HP_GAMMA], beta = a.hp[HP_BETA], cv = a.hp[HP_VCOEF];
+    if (tid < ne_blk) {
+        const int e = e0 + tid;
+        float R = a.values[B + e];
+        for (int t = a.T - 1; t >= 0; --t) {
+            const int i = t * a.n_e + e;
+            R = a.rewards[i] + gamma * (a.dones[i] ? 0.f : 1.f) * R;
+            a.returns[i] = R;
+        }
+    }
+    __syncthreads();
+    float s_pl = 0.f, s_h = 0.f, s_vl = 0.f;
+    const float invB = 1.0f / (float)B;
+    for (int idx = tid; idx < a.T * ne_blk; idx += 256) {
+        const int t = idx / ne_blk, e = e0 + idx % ne_blk;
+        const int i = t * a.n_e + e;
+        const float* z = a.logits + (size_t)i * a.A;
+        float m = z[0];
+        for (int k = 1; k < a.A; ++k) m = fmaxf(m, z[k]);
+        float se = 0.f;
+        for (int k = 0; k < a.A; ++k) se += expf(z[k] - m);
+        const float lse = logf(se);
+        float H = 0.f;
+        for (int k = 0; k < a.A; ++k) {
+            const float lp = z[k] - m - lse;
+            H -= expf(z[k] - m) / se * lp;
+        }
+        const float V = a.values[i], R = a.returns[i], adv = R - V;
+        int act = a.actions[i];
+        act = act < 0 ? 0 : (act >= a.A ? a.A - 1 : act);
+        s_pl += -adv * (z[act] - m - lse);
+        s_h += H;
+        s_vl += (R - V) * (R - V);
+        for (int k = 0; k < a.A; ++k) {
+            const float lp = z[k] - m - lse, p = expf(z[k] - m) / se;
+            a.dz[(size_t)i * a.A + k] = (-adv * ((k == act ? 1.f : 0.f) - p) + beta * p * (lp + H)) * invB;
+        }
+        a.dv[i] = 2.f * cv * (V - R) * invB;
+    }
+    __shared__ float red[3][256];
+    red[0][tid] = s_pl * invB; red[1][tid] = s_h * invB; red[2][tid] = s_vl * invB;   // means over the batch
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) { red[0][tid] += red[0][tid + o]; red[1][tid] += red[1][tid + o]; red[2][tid] += red[2][tid + o]; }
+        __syncthreads();
+    }
+    if (tid < 3) a.loss_partials[blockIdx.x * 4 + tid] = red[tid][0];
+}
+
+hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
+    hipLaunchKernelGGL(returns_loss_kernel, dim3(loss_blocks(a.n_e)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ head backward
+// dh[row][j] = 1[h > 0] * (sum_a dz[row][a] pi_w[a][j] + dv[row] v_w[j])
+__global__ __launch_bounds__(256) void heads_dh_kernel(int F4, int A, int rows, const float* dz, const float* dv,
+                                                       const float* pi_w, const float* v_w, const float* h, float* dh) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * F4) return;
+    const int row = idx / F4, j = (idx % F4) * 4, F = F4 * 4;
+    const float d = dv[row];
+    const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
+    float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
+    for (int k = 0; k < A; ++k) {
+        const float g = dz[(size_t)row * A + k];
+        const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
+        acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+    }
+    const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
+    acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
+    acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
+    *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+}
+
+hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
+                    const float* v_w, const float* h, float* dh) {
+    const int n = rows * (F / 4);
+    hipLaunchKernelGGL(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), 0, s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh);
+    return hipGetLastError();
+}
+
+// partial_w[chunk][a][j] = sum over the chunk's rows of coef(row, a) * h[row][j], coef = dz (a < A)
+// or dv (a == A); partial_b[chunk][a] = sum of coef.
+__global__ __launch_bounds__(256) void heads_wgrad_kernel(int F, int A, int rows, int rows_per_chunk, const float* dz,
+                                                          const float* dv, const float* h, float* pw, float* pb) {
+    const int j = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y, c = blockIdx.z;
+    const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+    float acc = 0.f, accb = 0.f;
+    for (int r = r0; r < r1; ++r) {
+        const float g = k < A ? dz[(size_t)r * A + k] : dv[r];
+        acc += g * h[(size_t)r * F + j];
+        accb += g;
+    }
+    pw[((size_t)c * (A + 1) + k) * F + j] = acc;
+    if (j == 0) pb[c * (A + 1) + k] = accb;
+}
+
+hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
+                       const float* h, float* pw, float* pb) {
+    const int rpc = (rows + n_chunk - 1) / n_chunk;
+    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(F / 256, A + 1, n_chunk), dim3(256), 0, s, F, A, rows, rpc, dz, dv, h, pw, pb);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ gradient reduction + norm
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    const int tid = threadIdx.x;
+    red[tid] = v;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+// Sums the split partial gradients in a fixed order (bit-stable from run to run), writes the
+// gradient arena and one partial sum of squares per block.
+__global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegments seg, int p_int, float* grads, float* block_ss) {
+    __shared__ float red[256];
+    float ss = 0.f;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < p_int; i += gridDim.x * 256) {
+        int sidx = 0;
+        for (int q = 1; q < seg.n; ++q) if (i >= seg.off[q]) sidx = q;
+        const int local = i - seg.off[sidx];
+        float g = 0.f;
+        if (local < seg.count[sidx]) {
+            const float* p = seg.partial[sidx] + local;
+            for (int q = 0; q < seg.n_split[sidx]; ++q) g += p[q * seg.stride[sidx]];
+        }
+        grads[i] = g;
+        ss += g * g;
+    }
+    const float tot = block_sum_256(ss, red);
+    if (threadIdx.x == 0) block_ss[blockIdx.x] = tot;
+}
+
+hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss) {
+    hipLaunchKernelGGL(grad_reduce_norm_kernel, dim3(kNormBlocks), dim3(256), 0, s, seg, p_int, grads, block_ss);
+    return hipGetLastError();
+}
+
+// Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
+//   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
+// Every block re-derives the norm from the kNormBlocks partial sums (same order everywhere).
+__global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
+                                                             const float* block_ss, const float* hp,
+                                                             const float* loss_partials, int n_loss_blocks,
+                                                             StatsOut* stats_a, StatsOut* stats_b) {
+    __shared__ float red[256];
+    const float tot = block_sum_256(block_ss[threadIdx.x], red);
+    const float norm = sqrtf(tot);
+    const float clip = hp[HP_CLIP], lr = hp[HP_LR], alpha = hp[HP_ALPHA], eps = hp[HP_EPS];
+    const float scale = norm > clip ? clip / norm : 1.0f;
+    const float oma = 1.0f - alpha;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n4; i += gridDim.x * 256) {
+        float4 g = grads[i], v = g2[i], t = theta[i];
+        g.x *= scale; g.y *= scale; g.z *= scale; g.w *= scale;
+        v.x = alpha * v.x + oma * g.x * g.x; v.y = alpha * v.y + oma * g.y * g.y;
+        v.z = alpha * v.z + oma * g.z * g.z; v.w = alpha * v.w + oma * g.w * g.w;
+        t.x -= lr * g.x / sqrtf(v.x + eps); t.y -= lr * g.y / sqrtf(v.y + eps);
+        t.z -= lr * g.z / sqrtf(v.z + eps); t.w -= lr * g.w / sqrtf(v.w + eps);
+        g2[i] = v; theta[i] = t;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        float pl = 0.f, en = 0.f, vl = 0.f;
+        for (int b = 0; b < n_loss_blocks; ++b) { pl += loss_partials[b * 4]; en += loss_partials[b * 4 + 1]; vl += loss_partials[b * 4 + 2]; }
+        StatsOut st;
+        // each block's partial already carries the 1/B of the batch mean
+        st.policy_loss = pl; st.entropy = en; st.value_loss = vl;
+        st.total_loss = pl - hp[HP_BETA] * en + hp[HP_VCOEF] * vl;
+        st.grad_norm = norm; st.clip_scale = scale;
+        st.nonfinite = (isfinite(st.total_loss) && isfinite(norm)) ? 0 : 1;
+        if (stats_a) *stats_a = st;
+        if (stats_b) *stats_b = st;
+    }
+}
+
+hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads, const float* block_ss,
+                          const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b) {
+    const int n4 = p_int / 4;
+    int blocks = (n4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(rmsprop_update_kernel, dim3(blocks), dim3(256), 0, s, n4, (float4*)theta, (float4*)g2,
+                       (const float4*)grads, block_ss, hp, loss_partials, n_loss_blocks, stats_a, stats_b);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ Philox4x32-10
+// Salmon, Moraes, Dror, Shaw (SC'11).  Same function on host (parameter init) and device.
+__host__ __device__ inline void philox_round(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3, uint32_t k0, uint32_t k1) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+}
+__host__ __device__ inline void philox_block(uint64_t ctr, uint64_t key, uint32_t out[4]) {
+    uint32_t c0 = (uint32_t)ctr, c1 = (uint32_t)(ctr >> 32), c2 = 0, c3 = 0;
+    uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
+    for (int r = 0; r < 10; ++r) {
+        philox_round(c0, c1, c2, c3, k0, k1);
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        philox_round(c0, c1, c2, c3, k0, k1);
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__global__ __launch_bounds__(256) void fill_uniforms_kernel(uint64_t seed, uint64_t offset, float* out, size_t n) {
+    const size_t b = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (b * 4 >= n) return;
+    uint32_t w[4];
+    philox_block(offset + b, seed, w);
+    for (int i = 0; i < 4; ++i)
+        if (b * 4 + i < n) out[b * 4 + i] = (float)(w[i] >> 8) * (1.0f / 16777216.0f);
+}
+
+hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n) {
+    if (n == 0) return hipSuccess;
+    const size_t blocks = ((n + 3) / 4 + 255) / 256;
+    hipLaunchKernelGGL(fill_uniforms_kernel, dim3((unsigned)blocks), dim3(256), 0, s, seed, offset, out, n);
+    return hipGetLastError();
+}
+
+}  // namespace paac
