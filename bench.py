@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the PAAC hot path on one MI355X.
+
+One "step" is one PAAC iteration without the environments (Algorithm 1, the body of the repeat
+loop): t_max calls of paac_select_actions, one per timestep slab, followed by one
+paac_train_step over the n_e x t_max rollout.  Inputs are synthetic, seeded, and resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..2] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def kernel_work(net, n_e, t_max):
+    """Algorithmic work per launch of every kernel: ('flop', 2 x MACs) or ('byte', HBM bytes)."""
+    B, Bp, A = n_e * t_max, n_e * (t_max + 1), net.n_actions
+    shapes = net.conv_out_shapes()
+    cin = net.in_c
+    conv = []
+    for (co, k, s), (c, h, w) in zip(net.conv, shapes):
+        conv.append(2.0 * h * w * (k * k * cin) * co)
+        cin = co
+    fc = 2.0 * net.flat() * net.fc
+    hd = 2.0 * net.fc * (A + 1)
+    P = net.param_count()
+    w = {}
+    for l, f in enumerate(conv):
+        w[f"select.conv{l + 1}_fwd"] = ("flop", f * n_e)
+        w[f"train.conv{l + 1}_fwd"] = ("flop", f * Bp)
+        w[f"train.conv{l + 1}_wgrad"] = ("flop", f * B)
+        if l > 0:
+            w[f"train.conv{l + 1}_dgrad"] = ("flop", f * B)
+    w["select.fc_fwd"] = ("flop", fc * n_e)
+    w["train.fc_fwd"] = ("flop", fc * Bp)
+    w["train.fc_wgrad"] = ("flop", fc * B)
+    w["train.fc_dgrad"] = ("flop", fc * B)
+    w["select.heads_sample"] = ("flop", hd * n_e)
+    w["train.heads_fwd"] = ("flop", hd * Bp)
+    w["train.heads_dh"] = ("flop", hd * B)
+    w["train.heads_wgrad"] = ("flop", hd * B)
+    w["train.returns_loss"] = ("byte", 4.0 * (Bp * (A + 1) + B * (A + 4)))
+    w["train.grad_reduce_norm"] = ("byte", 8.0 * P)      # read one gradient copy, write the arena
+    w["train.clip_rmsprop"] = ("byte", 20.0 * P)         # read theta, g, g2; write theta, g2
+    return w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", type=int, default=2, help="index into the measurement configurations")
+    ap.add_argument("--rollouts", type=int, default=4, help="distinct resident rollouts rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_1705_04862_amd import inputs as I
+    from paper_1705_04862_amd import paac as P
+
+    cfg = I.CONFIGS[args.config]
+    net, n_e, T = cfg.net, cfg.n_e, cfg.t_max
+    torch.cuda.set_device(0)
+    ctx = P.Paac(net.arch, n_e, T, net.n_actions, cfg.precision)
+    params = I.config_params(cfg)
+    ctx.set_state(params)
+
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    host_rollouts = [I.config_rollout(cfg, k) for k in range(args.rollouts)]
+    R = []
+    for ro in host_rollouts:
+        R.append(dict(states=to_dev(ro.states), rewards=to_dev(ro.rewards), dones=to_dev(ro.dones),
+                      uniforms=to_dev(ro.uniforms),
+                      actions=torch.zeros(T, n_e, dtype=torch.int32, device="cuda:0"),
+                      values=torch.zeros(T, n_e, dtype=torch.float32, device="cuda:0")))
+    stats = torch.zeros(8, dtype=torch.float32, device="cuda:0")
+
+    def step(i, what="both"):
+        r = R[i % len(R)]
+        if what in ("both", "select"):
+            for t in range(T):
+                ctx.select_actions(r["states"][t], r["uniforms"][t], r["actions"][t], r["values"][t])
+        if what in ("both", "train"):
+            ctx.train_step(r["states"], r["actions"], r["rewards"], r["dones"], cfg.hp, stats)
+
+    def timed(k, what="both"):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(k):
+            step(i, what)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for i in range(args.warmup):
+        step(i)
+    elapsed = timed(args.steps)
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = args.steps * n_e * T / elapsed
+
+    # context figures: the halves of the step, and the same step launched kernel by kernel
+    k2 = max(10, args.steps // 10)
+    ms_select = 1e3 * timed(k2, "select") / k2
+    ms_train = 1e3 * timed(k2, "train") / k2
+    ctx.set_graphs(False)
+    for i in range(5):
+        step(i)
+    ms_eager = 1e3 * timed(k2) / k2
+    ctx.set_graphs(True)
+
+    # per-kernel durations with HIP events on the library's stream
+    ctx.set_profiling(True)
+    for i in range(args.profile_steps):
+        step(i)
+    times = ctx.kernel_times()
+    ctx.set_profiling(False)
+    work = kernel_work(net, n_e, T)
+    per_kernel = {}
+    for name, t in times.items():
+        avg_us = 1e3 * t["ms"] / t["calls"]
+        kind, amount = work[name]
+        per_kernel[name] = dict(avg_us=round(avg_us, 3), calls_per_step=t["calls"] / args.profile_steps,
+                                us_per_step=round(1e3 * t["ms"] / args.profile_steps, 3))
+        if kind == "flop":
+            per_kernel[name]["tflops"] = round(amount / (avg_us * 1e-6) / 1e12, 3)
+        else:
+            per_kernel[name]["gbs"] = round(amount / (avg_us * 1e-6) / 1e9, 1)
+    dom = max(per_kernel, key=lambda n: per_kernel[n]["us_per_step"])
+    kind, amount = work[dom]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
+    if kind == "flop":
+        ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e12
+        roof = dict(bound="mfma", kernel=dom, achieved=round(ach, 3), peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                    frac=round(ach / PEAK_FP32_MFMA_TFLOPS, 4), traffic=traffic,
+                    avg_launch_us=per_kernel[dom]["avg_us"], algorithmic_flop_per_launch=amount)
+    else:
+        ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e9
+        roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic,
+                    avg_launch_us=per_kernel[dom]["avg_us"], algorithmic_bytes_per_launch=amount)
+
+    sel_f, trn_f = ctx.flops()
+    step_flop = T * sel_f + trn_f
+    out = {
+        "metric": "env-timesteps/sec (select+train) at n_e=%d,t_max=%d; %% MFMA peak" % (n_e, T),
+        "value": round(value, 1), "unit": "env-timesteps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "net": net.name, "n_e": n_e, "t_max": T, "n_actions": net.n_actions,
+                   "rollouts_rotated": len(R), "launch": "hip-graph replay (t_max select graphs + 1 train graph)"},
+        "roofline": roof,
+        "step_gflop": round(step_flop / 1e9, 3),
+        "pct_fp32_mfma_peak_whole_step": round(100 * step_flop / elapsed * args.steps / (PEAK_FP32_MFMA_TFLOPS * 1e12), 3),
+        "ms_select_x_tmax": round(ms_select, 4), "ms_train": round(ms_train, 4), "ms_per_step_eager": round(ms_eager, 4),
+        "kernels": per_kernel,
+        "paper_context": "derived from the paper's Table 1 training times and time split on a GTX 980 Ti: "
+                         "about 7200 (arch_nips) / 4100-4300 (arch_nature) env-timesteps/s for this path",
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import paac_oracle as O
+        ro = host_rollouts[0]
+        rms = I.make_rms(0, net)
+
+        def oracle_iter():
+            for t in range(T):
+                O.select_actions(net, params, ro.states[t], ro.uniforms[t])
+            O.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp)
+        t0 = time.perf_counter()
+        oracle_iter()
+        first = time.perf_counter() - t0
+        reps = int(max(1, min(20, 10.0 / max(first, 1e-3))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle_iter()
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(reps * n_e * T / el, 2), "unit": "env-timesteps/s",
+                               "cores": O.threads(), "kind": "oracle",
+                               "sample": "%d full iterations (t_max selects + 1 train) of %s" % (reps, cfg.name)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -81,9 +81,9 @@ Plan make_plan(const NetDesc& n, int n_e, int T) {
     p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
     p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
     for (int l = 0; l < n.n_conv; ++l)
-        p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 32, 512);
-    p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 512);
-    p.head_chunks = p.B / 64 < 1 ? 1 : (p.B / 64 > 64 ? 64 : p.B / 64);
+        p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 64, 256);
+    p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 256);
+    p.head_chunks = p.B / 8 < 1 ? 1 : (p.B / 8 > 128 ? 128 : p.B / 8);
     p.n_loss_blocks = loss_blocks(n_e);
     return p;
 }
@@ -108,7 +108,7 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, char* base) {
         return ptr;
     };
     b.theta = take(a.p_int); b.g2 = take(a.p_int); b.grads = take(a.p_int);
-    b.hp = take(HP_COUNT); b.block_ss = take(kNormBlocks); b.loss_partials = take((size_t)p.n_loss_blocks * 4);
+    b.hp = take(HP_COUNT); b.block_ss = take(norm_blocks(a.p_int)); b.loss_partials = take((size_t)p.n_loss_blocks * 4);
     b.stats = reinterpret_cast<StatsOut*>(take(16));
     for (int l = 0; l < n.n_conv; ++l) {
         const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout;
@@ -253,6 +253,7 @@ void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Spli
 hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int* err_id) {
     Launcher L{c, s, prof, hipSuccess, -1};
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
+    if (prof) delay_us(s, 250);
     enqueue_trunk(c, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1);
     HeadsArgs h{};
     h.fc_partial = b.fc_partial; h.n_split = p.sel_fc.n; h.split_stride = (size_t)p.n_e * n.fc;
@@ -270,6 +271,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
     const int A = n.n_actions, F = n.fc, last = n.n_conv - 1;
     // forward over all (t_max+1) n_e states: rows [0, B) are the batch, rows [B, Bp) the bootstrap
+    if (prof) delay_us(s, 800);
     enqueue_trunk(c, L, x.states, p.Bp, p.trn_fc, K_TRN_CONV1);
     HeadsArgs h{};
     h.fc_partial = b.fc_partial; h.n_split = p.trn_fc.n; h.split_stride = (size_t)p.Bp * F;

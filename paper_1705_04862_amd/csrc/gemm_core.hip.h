@@ -1,4 +1,4 @@
-// Tiled fp32 GEMM core on CDNA4 matrix cores (v_mfma_f32_32x32x2f32 / v_mfma_f32_16x16x4f32)
+// Tiled fp32 GEMM core on CDNA4 matrix cores (v_mfma_f32_32x32x2f32)
 // with functor-defined operand addressing, used for every dense contraction of the PAAC step:
 // convolution forward (implicit im2col rows), data gradient (gather form), weight gradient
 // (reduction over output positions, split over workgroups) and the fully connected layer.
@@ -6,19 +6,36 @@
 //   C[m][n] = sum_k A(m,k) * B(k,n)          m < M, n < N, k in this workgroup's k-range
 //
 // A workgroup of 256 threads (4 wavefronts of 64) owns a BM x BN tile.  Both operands are staged
-// through LDS in k-major order (As[k][m], Bs[k][n]) so that the 32 (or 16) lanes that feed one
+// through LDS in k-major order (As[k][m], Bs[k][n]) so that the 32 lanes that feed one
 // MFMA operand read consecutive words: bank-conflict free without swizzling.  An operand whose
 // global layout is contiguous along k ("kContig") is transposed on its way into LDS; an operand
-// contiguous along m/n is copied with 16-byte stores.  Global loads for k-tile i+1 are issued
-// before the MFMAs of k-tile i (register double buffering, two LDS buffers, one barrier per tile).
+// contiguous along m/n is copied with 16-byte stores.  Global loads run S k-tiles ahead of the
+// MFMAs through S register stages (two LDS buffers, one barrier per tile): these layers are bound by
+// memory latency, not bandwidth, at the paper's batch sizes.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace paac {
 
+#ifdef PAAC_KERNEL_TIMING
+// diagnostic build only: per-workgroup phase time stamps (100 MHz wall clock); record 0 is a counter
+extern __device__ unsigned long long* g_kernel_timing;
+#define PAAC_STAMP_INIT() unsigned long long* stamp__ = nullptr; \
+    if (g_kernel_timing && threadIdx.x == 0) { stamp__ = g_kernel_timing + 16 * (1 + atomicAdd(g_kernel_timing, 1ull)); stamp__[8] = stamp__[9] = stamp__[10] = stamp__[11] = 0; \
+        stamp__[5] = gridDim.x; stamp__[6] = K; stamp__[7] = M; }
+#define PAAC_STAMP(i) do { if (stamp__) stamp__[i] = wall_clock64(); } while (0)
+#define PAAC_PHASE_BEGIN() unsigned long long ph__ = clock64()
+#define PAAC_PHASE_END(i) do { const unsigned long long n__ = clock64(); if (stamp__) stamp__[8 + (i)] += n__ - ph__; ph__ = n__; } while (0)
+#else
+#define PAAC_PHASE_BEGIN() do {} while (0)
+#define PAAC_PHASE_END(i) do {} while (0)
+#define PAAC_STAMP_INIT() do {} while (0)
+#define PAAC_STAMP(i) do {} while (0)
+#endif
+
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // ----------------------------------------------------------------------------------------------
 // Wave-level MFMA fragments.  Lane l supplies A[idx = l % MF][k = l / MF] and B[k = l / MF][idx].
@@ -33,21 +50,17 @@ template <> struct Mma<32> {
     static __device__ __forceinline__ int row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
     static __device__ __forceinline__ int col(int lane) { return lane & 31; }
 };
-template <> struct Mma<16> {
-    typedef f32x4 Acc;
-    static constexpr int KSTEP = 4, NACC = 4;
-    static __device__ __forceinline__ Acc mma(float a, float b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int row(int r, int lane) { return (lane >> 4) * 4 + r; }
-    static __device__ __forceinline__ int col(int lane) { return lane & 15; }
-};
-
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MF_>
+// BM x BN x BK tile; the four waves are arranged WM (along m) x WN (along n) x WK (along k): with
+// WK > 1 several waves accumulate the same output fragments over different k-steps of every tile
+// and their accumulators are added through LDS before the epilogue.  This keeps four MFMA pipes
+// busy on a tile as small as 32 x 32, which the small-batch layers need.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int WK_, int MF_, int STAGES_ = 3>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MF = MF_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, WK = WK_, MF = MF_, STAGES = STAGES_;
+    static_assert(STAGES >= 2 && STAGES <= 4, "register prefetch depth");
     static constexpr int TM = BM / (WM * MF), TN = BN / (WN * MF);
-    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(WM * WN * WK == 4, "four wavefronts per workgroup");
+    static_assert((BK / Mma<MF>::KSTEP) % WK == 0, "k-steps must divide among the k-waves");
     static_assert(TM * WM * MF == BM && TN * WN * MF == BN, "tile must be whole fragments");
     static_assert(BK % 4 == 0 && BK % Mma<MF>::KSTEP == 0, "BK granularity");
 };
@@ -58,11 +71,17 @@ struct Tile {
 //   struct Fixed;                                   per-thread state of the coordinate that does
 //   Fixed prep(int fixed_idx, int z) const;         not change across k-tiles: a row (kContig) or
 //                                                   the first of 4 columns (!kContig)
-//   float4 load(const Fixed&, int var_idx) const;   kContig: 4 values at k = var_idx .. +3
+//   Raw load(const Fixed&, int var_idx, bool pred, bool& ok) const;
+//                                                   kContig: 4 values at k = var_idx .. +3
 //                                                   else   : 4 columns at reduction index var_idx
-// Out-of-range coordinates return zeros.
-// Epilogue: static constexpr bool kColSum; void store(int row, int col, float v, int z) const;
-//           void store_colsum(int col, float v, int z) const   (only if kColSum)
+//     always issues the load from a clamped, valid address (branch free) and reports in `ok`
+//     whether the coordinate was in range (and pred held);
+//   static float4 finish(Raw, bool ok);             conversion + zeroing, applied when the registers
+//                                                   are written to LDS
+// Epilogue: static constexpr bool kColSum; typedef Aux;
+//           Aux aux(int row, int col, int z, bool ok) const;      auxiliary load (bias / mask), clamped
+//           void store(int row, int col, float v, int z, Aux) const;
+//           void store_colsum(int col, float v, int z) const      (only if kColSum)
 
 template <class T, class AL, class BL, class EP>
 __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
@@ -75,17 +94,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, con
     constexpr int A_F4 = BM * BK / 4, B_F4 = BN * BK / 4;
     constexpr int A_IT = (A_F4 + 255) / 256, B_IT = (B_F4 + 255) / 256;
 
-    __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
+    constexpr int A_BUF = BK * LDA, B_BUF = BK * LDB;      // floats per LDS buffer (multiples of 4)
+    __shared__ __attribute__((aligned(16))) float smem[2 * A_BUF + 2 * B_BUF];
+    float* const As = smem;                 // As[buf] = As + buf * A_BUF
+    float* const Bs = smem + 2 * A_BUF;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % T::WM, wn = wave / T::WM;
+    const int wm = wave % T::WM, wn = (wave / T::WM) % T::WN, wk = wave / (T::WM * T::WN);
     const int mt = blockIdx.x % m_tiles, nt = blockIdx.x / m_tiles;
     const int z = blockIdx.y;
     const int m0 = mt * BM, n0 = nt * BN;
     const int k_begin = k_per_split > 0 ? z * k_per_split : 0;
     const int k_end = k_per_split > 0 ? min(K, k_begin + k_per_split) : K;
     const int nk = (k_end - k_begin + BK - 1) / BK;
+    PAAC_STAMP_INIT();
+    PAAC_STAMP(0);
 
     // per-thread fixed coordinates of the staging loads
     typename AL::Fixed afix[A_IT];
@@ -122,73 +145,98 @@ __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, con
         }
     }
 
-    float4 areg[A_IT], breg[B_IT];
-    auto gload = [&](int kt) {
+    // S register stages: k-tile j travels through stage j % S; while tile i is multiplied the global
+    // loads of tiles i+1 .. i+S are in flight
+    // The loaded registers are not touched (no conversion, no zeroing) until they are stored to LDS:
+    // any earlier use would make the wavefront wait for the load it has just issued.
+    constexpr int S = T::STAGES;
+    typename AL::Raw areg[S][A_IT];
+    typename BL::Raw breg[S][B_IT];
+    unsigned okbits[S];
+    auto gload = [&](int kt, auto stage) {
+        constexpr int G = decltype(stage)::value;
         const int kb = k_begin + kt * BK;
+        unsigned bits = 0;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
             const int kk = kb + a_var[i];
-            areg[i] = (tid + i * 256 < A_F4 && kk < k_end) ? al.load(afix[i], kk) : make_float4(0.f, 0.f, 0.f, 0.f);
+            bool ok;
+            areg[G][i] = al.load(afix[i], kk, (A_F4 % 256 == 0 || tid + i * 256 < A_F4) && kk < k_end, ok);
+            bits |= ok ? (1u << i) : 0u;
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
             const int kk = kb + b_var[i];
-            breg[i] = (tid + i * 256 < B_F4 && kk < k_end) ? bl.load(bfix[i], kk) : make_float4(0.f, 0.f, 0.f, 0.f);
+            bool ok;
+            breg[G][i] = bl.load(bfix[i], kk, (B_F4 % 256 == 0 || tid + i * 256 < B_F4) && kk < k_end, ok);
+            bits |= ok ? (1u << (16 + i)) : 0u;
         }
+        okbits[G] = bits;
     };
-    auto lstore = [&](int buf) {
+    auto lstore = [&](auto stage, int buf) {      // register stage -> LDS buffer
+        constexpr int G = decltype(stage)::value;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
             if (tid + i * 256 < A_F4) {
-                float* p = &As[buf][a_lds[i]];
-                if (AL::kContig) { p[0] = areg[i].x; p[LDA] = areg[i].y; p[2 * LDA] = areg[i].z; p[3 * LDA] = areg[i].w; }
-                else *reinterpret_cast<float4*>(p) = areg[i];
+                float* p = As + buf * A_BUF + a_lds[i];
+                const float4 v = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
+                if (AL::kContig) { p[0] = v.x; p[LDA] = v.y; p[2 * LDA] = v.z; p[3 * LDA] = v.w; }
+                else *reinterpret_cast<float4*>(p) = v;
             }
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
             if (tid + i * 256 < B_F4) {
-                float* p = &Bs[buf][b_lds[i]];
-                if (BL::kContig) { p[0] = breg[i].x; p[LDB] = breg[i].y; p[2 * LDB] = breg[i].z; p[3 * LDB] = breg[i].w; }
-                else *reinterpret_cast<float4*>(p) = breg[i];
+                float* p = Bs + buf * B_BUF + b_lds[i];
+                const float4 v = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
+                if (BL::kContig) { p[0] = v.x; p[LDB] = v.y; p[2 * LDB] = v.z; p[3 * LDB] = v.w; }
+                else *reinterpret_cast<float4*>(p) = v;
             }
         }
     };
 
-    typename MM::Acc acc[TM][TN];
+    // a wave with a single output fragment alternates between two accumulators so that consecutive
+    // MFMAs do not wait on each other; the two are added in the epilogue
+    constexpr int KACC = (TM * TN == 1) ? 2 : 1;
+    typename MM::Acc acc[KACC][TM][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int q = 0; q < KACC; ++q)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < MM::NACC; ++r) acc[i][j][r] = 0.f;
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < MM::NACC; ++r) acc[q][i][j][r] = 0.f;
 
     float colsum = 0.f;   // used only when EP::kColSum (bias gradient = column sums of B)
 
     const int fidx = lane % MF, fk = lane / MF;
     const int a_base = wm * (TM * MF) + fidx, b_base = wn * (TN * MF) + fidx;
 
-    if (nk > 0) {
-        gload(0);
-        lstore(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
-        const float* as = As[buf];
-        const float* bs = Bs[buf];
+    auto compute = [&](int buf) {
+        const float* as = As + buf * A_BUF;
+        const float* bs = Bs + buf * B_BUF;
+        // every LDS read of the tile is issued before the first MFMA: one LDS latency per tile
+        // instead of one per group of MFMAs (a workgroup often has its compute unit to itself)
+        constexpr int NS = BK / MM::KSTEP / T::WK;      // k-steps of this wave: wk, wk + WK, ...
+        float a[NS][TM], b[NS][TN];
 #pragma unroll
-        for (int ks = 0; ks < BK; ks += MM::KSTEP) {
-            float a[TM], b[TN];
+        for (int st = 0; st < NS; ++st) {
+            const int krow = (st * T::WK + wk) * MM::KSTEP + fk;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = as[(ks + fk) * LDA + a_base + i * MF];
+            for (int i = 0; i < TM; ++i) a[st][i] = as[krow * LDA + a_base + i * MF];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bs[(ks + fk) * LDB + b_base + j * MF];
+            for (int j = 0; j < TN; ++j) b[st][j] = bs[krow * LDB + b_base + j * MF];
+        }
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = MM::mma(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) {
+                    const int q = st % KACC;
+                    acc[q][i][j] = MM::mma(a[st][i], b[st][j], acc[q][i][j]);
+                }
         }
         if constexpr (EP::kColSum) {
             if (mt == 0 && tid < BN) {
@@ -196,24 +244,92 @@ __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, con
                 for (int k = 0; k < BK; ++k) colsum += bs[k * LDB + tid];
             }
         }
-        if (kt + 1 < nk) lstore(buf ^ 1);
+    };
+
+    // one pipeline step for the tile in register-stage position G (= kt % S)
+    auto step = [&](int kt, auto stage) {
+        constexpr int G = decltype(stage)::value;
+        constexpr int GN = (G + 1) % S;
+        PAAC_PHASE_BEGIN();
+        gload(kt + S, stage);      // stage G was stored to LDS one step ago; past the end: clamped, zeroed
+        PAAC_PHASE_END(0);
+        compute(kt & 1);
+        PAAC_PHASE_END(1);
+        if (kt + 1 < nk) lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);
+        PAAC_PHASE_END(2);
         __syncthreads();
+        PAAC_PHASE_END(3);
+    };
+    PAAC_STAMP(1);
+    gload(0, std::integral_constant<int, 0>());
+    gload(1, std::integral_constant<int, 1>());
+    if constexpr (S > 2) gload(2, std::integral_constant<int, 2>());
+    if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
+    lstore(std::integral_constant<int, 0>(), 0);
+    __syncthreads();
+    PAAC_STAMP(2);
+    for (int kt = 0; kt < nk; kt += S) {
+        step(kt, std::integral_constant<int, 0>());
+        if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>());
+        if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
+        if constexpr (S > 3) { if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>()); }
     }
 
+    PAAC_STAMP(3);
+    if constexpr (EP::kColSum) {
+        if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
+    }
+    if constexpr (KACC == 2) {
+#pragma unroll
+        for (int r = 0; r < MM::NACC; ++r) acc[0][0][0][r] += acc[1][0][0][r];
+    }
+    if constexpr (T::WK > 1) {
+        // add the accumulators of the k-waves: waves wk > 0 park theirs in LDS (the staging buffers are
+        // free now: the loop ended with a barrier), wave wk == 0 of each (wm, wn) adds them and stores
+        constexpr int PER_WAVE = TM * TN * MM::NACC * 64;
+        static_assert((T::WK - 1) * T::WM * T::WN * PER_WAVE <= 2 * A_BUF + 2 * B_BUF, "reduction scratch must fit the staging buffers");
+        float* red = smem;
+        if (wk > 0) {
+            float* dst = red + ((wk - 1) * (T::WM * T::WN) + (wave % (T::WM * T::WN))) * PER_WAVE + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < MM::NACC; ++r) dst[((i * TN + j) * MM::NACC + r) * 64] = acc[0][i][j][r];
+        }
+        __syncthreads();
+        if (wk > 0) return;
+#pragma unroll
+        for (int q = 1; q < T::WK; ++q) {
+            const float* src = red + ((q - 1) * (T::WM * T::WN) + wave) * PER_WAVE + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < MM::NACC; ++r) acc[0][i][j][r] += src[((i * TN + j) * MM::NACC + r) * 64];
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * (TN * MF) + j * MF + MM::col(lane);
+            // first every auxiliary load of the fragment (bias, ReLU mask), then the stores
+            typename EP::Aux aux[MM::NACC];
 #pragma unroll
             for (int r = 0; r < MM::NACC; ++r) {
                 const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
-                if (row < M && col < N) ep.store(row, col, acc[i][j][r], z);
+                aux[r] = ep.aux(row, col, z, row < M && col < N);
+            }
+#pragma unroll
+            for (int r = 0; r < MM::NACC; ++r) {
+                const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
+                if (row < M && col < N) ep.store(row, col, acc[0][i][j][r], z, aux[r]);
             }
         }
-    if constexpr (EP::kColSum) {
-        if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
-    }
+    PAAC_STAMP(4);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -232,47 +348,59 @@ struct ConvGeom {
 };
 
 __device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ float4 keep_if(bool ok, float4 v) {
+    return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+}
 __device__ __forceinline__ float4 u8x4_to_unit(uint32_t w) {
     const float s = 1.0f / 255.0f;
     return make_float4((float)(w & 255u) * s, (float)((w >> 8) & 255u) * s, (float)((w >> 16) & 255u) * s,
                        (float)(w >> 24) * s);
 }
 
+// All loaders are branch free: an out-of-range coordinate is clamped to a valid address, the load
+// is always issued, and the value is replaced by zero afterwards.  (A load under a branch makes the
+// compiler wait for every outstanding load at the join, which would serialise the prefetch stages.)
+//   load(fixed, var, ok): `ok` = the caller's own predicate (k-range, tile bounds)
+
 // im2col rows of a uint8 NCHW image batch, k = (c, ky, kx); value = byte / 255.
 template <class G> struct ConvU8RowsK {
     static constexpr bool kContig = true;
+    typedef uint32_t Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, u8x4_to_unit(r)); }
     const uint8_t* x; int rows;
-    struct Fixed { const uint8_t* p; };
+    struct Fixed { const uint8_t* p; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.p = nullptr;
-        if (row < rows) {
-            const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-            f.p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
-        }
+        Fixed f; f.ok = row < rows;
+        row = f.ok ? row : 0;
+        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
+        f.p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        if (!f.p) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        k = ok ? k : 0;
         const int c = k / (G::KS * G::KS), r = k % (G::KS * G::KS), ky = r / G::KS, kx = r % G::KS;
-        return u8x4_to_unit(*reinterpret_cast<const uint32_t*>(f.p + c * (G::H * G::W) + ky * G::W + kx));
+        return *reinterpret_cast<const uint32_t*>(f.p + c * (G::H * G::W) + ky * G::W + kx);
     }
 };
 
 // im2col rows of a float NHWC activation, k = (ky, kx, c).
 template <class G> struct ConvNHWCRowsK {
     static constexpr bool kContig = true;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* x; int rows;
-    struct Fixed { const float* p; };
+    struct Fixed { const float* p; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.p = nullptr;
-        if (row < rows) {
-            const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-            f.p = x + ((size_t)(n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN;
-        }
+        Fixed f; f.ok = row < rows;
+        row = f.ok ? row : 0;
+        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
+        f.p = x + ((size_t)(n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN;
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        if (!f.p) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        k = ok ? k : 0;
         const int ky = k / (G::KS * G::CIN), rem = k % (G::KS * G::CIN);
         return *reinterpret_cast<const float4*>(f.p + ky * (G::W * G::CIN) + rem);
     }
@@ -281,26 +409,32 @@ template <class G> struct ConvNHWCRowsK {
 // Row-major matrix read along its rows: element (row, k) = base[row*ld + k].
 struct DenseRowsK {
     static constexpr bool kContig = true;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* base; int rows, ld;
-    struct Fixed { const float* p; };
+    struct Fixed { const float* p; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.p = row < rows ? base + (size_t)row * ld : nullptr; return f;
+        Fixed f; f.ok = row < rows; f.p = base + (size_t)(f.ok ? row : 0) * ld; return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        return f.p ? *reinterpret_cast<const float4*>(f.p + k) : zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        return *reinterpret_cast<const float4*>(f.p + (ok ? k : 0));
     }
 };
 
 // Row-major matrix read along its columns: element (k, col) = base[k*ld + col].
 struct DenseKCols {
     static constexpr bool kContig = false;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* base; int cols, ld;
-    struct Fixed { const float* p; };
+    struct Fixed { const float* p; bool ok; };
     __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.p = col < cols ? base + col : nullptr; return f;
+        Fixed f; f.ok = col < cols; f.p = base + (f.ok ? col : 0); return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        return f.p ? *reinterpret_cast<const float4*>(f.p + (size_t)k * ld) : zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        return *reinterpret_cast<const float4*>(f.p + (size_t)(ok ? k : 0) * ld);
     }
 };
 
@@ -308,22 +442,25 @@ struct DenseKCols {
 // value = dY[n][yy - ty][xx - tx][co] when that output position exists, else 0.
 template <class G> struct DgradGatherRowsK {
     static constexpr bool kContig = true;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* dy; int rows;
-    struct Fixed { const float* p; int yy, xx; };
+    struct Fixed { const float* p; int yy, xx; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.p = nullptr; f.yy = 0; f.xx = 0;
-        if (row < rows) {
-            const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC);
-            f.yy = r / G::WC; f.xx = r % G::WC;
-            f.p = dy + (size_t)n * (G::HO * G::WO * G::COUT);
-        }
+        Fixed f; f.ok = row < rows;
+        row = f.ok ? row : 0;
+        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC);
+        f.yy = r / G::WC; f.xx = r % G::WC;
+        f.p = dy + (size_t)n * (G::HO * G::WO * G::COUT);
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        if (!f.p) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        k = ok ? k : 0;
         const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
-        const int oy = f.yy - ty, ox = f.xx - tx;
-        if (oy < 0 || oy >= G::HO || ox < 0 || ox >= G::WO) return zero4();
+        int oy = f.yy - ty, ox = f.xx - tx;
+        ok = ok && oy >= 0 && oy < G::HO && ox >= 0 && ox < G::WO;
+        oy = ok ? oy : 0; ox = ok ? ox : 0;
         return *reinterpret_cast<const float4*>(f.p + (oy * G::WO + ox) * G::COUT + co);
     }
 };
@@ -332,15 +469,18 @@ template <class G> struct DgradGatherRowsK {
 // ky = py + ST*ty, kx = px + ST*tx for parity class z = py*ST + px.
 template <class G> struct DgradWeightColsK {
     static constexpr bool kContig = true;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* w;
-    struct Fixed { const float* p; int py, px; };
+    struct Fixed { const float* p; int py, px; bool ok; };
     __device__ __forceinline__ Fixed prep(int ci, int z) const {
-        Fixed f; f.py = z / G::ST; f.px = z % G::ST;
-        f.p = ci < G::CIN ? w + (size_t)ci * G::COUT : nullptr;
+        Fixed f; f.py = z / G::ST; f.px = z % G::ST; f.ok = ci < G::CIN;
+        f.p = w + (size_t)(f.ok ? ci : 0) * G::COUT;
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int k) const {
-        if (!f.p) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        k = ok ? k : 0;
         const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
         const int ky = f.py + G::ST * ty, kx = f.px + G::ST * tx;
         return *reinterpret_cast<const float4*>(f.p + (size_t)(ky * G::KS + kx) * (G::CIN * G::COUT) + co);
@@ -350,39 +490,43 @@ template <class G> struct DgradWeightColsK {
 // Weight gradient of the first layer: A(m = (c,ky,kx), k = output position) = byte / 255.
 template <class G> struct ConvU8KCols {
     static constexpr bool kContig = false;
+    typedef uint32_t Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, u8x4_to_unit(r)); }
     const uint8_t* x; int rows;
-    struct Fixed { int off; };
+    struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.off = -1;
-        if (col < G::KK) {
-            const int c = col / (G::KS * G::KS), r = col % (G::KS * G::KS), ky = r / G::KS, kx = r % G::KS;
-            f.off = c * (G::H * G::W) + ky * G::W + kx;
-        }
+        Fixed f; f.ok = col < G::KK;
+        col = f.ok ? col : 0;
+        const int c = col / (G::KS * G::KS), r = col % (G::KS * G::KS), ky = r / G::KS, kx = r % G::KS;
+        f.off = c * (G::H * G::W) + ky * G::W + kx;
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int row) const {
-        if (f.off < 0 || row >= rows) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int row, bool pred, bool& ok) const {
+        ok = pred && f.ok && row < rows;
+        row = ok ? row : 0;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
         const uint8_t* p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST + f.off;
-        return u8x4_to_unit(*reinterpret_cast<const uint32_t*>(p));
+        return *reinterpret_cast<const uint32_t*>(p);
     }
 };
 
 // Weight gradient of the later conv layers: A(m = (ky,kx,c), k = output position) from NHWC input.
 template <class G> struct ConvNHWCKCols {
     static constexpr bool kContig = false;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
     const float* x; int rows;
-    struct Fixed { int off; };
+    struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.off = -1;
-        if (col < G::KK) {
-            const int ky = col / (G::KS * G::CIN), rem = col % (G::KS * G::CIN);
-            f.off = ky * (G::W * G::CIN) + rem;
-        }
+        Fixed f; f.ok = col < G::KK;
+        col = f.ok ? col : 0;
+        const int ky = col / (G::KS * G::CIN), rem = col % (G::KS * G::CIN);
+        f.off = ky * (G::W * G::CIN) + rem;
         return f;
     }
-    __device__ __forceinline__ float4 load(const Fixed& f, int row) const {
-        if (f.off < 0 || row >= rows) return zero4();
+    __device__ __forceinline__ Raw load(const Fixed& f, int row, bool pred, bool& ok) const {
+        ok = pred && f.ok && row < rows;
+        row = ok ? row : 0;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
         return *reinterpret_cast<const float4*>(x + ((size_t)(n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN + f.off);
     }
@@ -392,16 +536,20 @@ template <class G> struct ConvNHWCKCols {
 // Epilogues
 struct EpiBiasRelu {            // out[row][col] = max(v + bias[col], 0)
     static constexpr bool kColSum = false;
+    typedef float Aux;
     float* out; const float* bias; int ldo;
-    __device__ __forceinline__ void store(int row, int col, float v, int) const {
-        out[(size_t)row * ldo + col] = fmaxf(v + bias[col], 0.f);
+    __device__ __forceinline__ Aux aux(int, int col, int, bool ok) const { return bias[ok ? col : 0]; }
+    __device__ __forceinline__ void store(int row, int col, float v, int, Aux b) const {
+        out[(size_t)row * ldo + col] = fmaxf(v + b, 0.f);
     }
 };
 
 template <bool COLSUM> struct EpiPartial {   // out[z][row][col] = v ; optional column sums of B
     static constexpr bool kColSum = COLSUM;
+    typedef int Aux;
     float* out; size_t z_stride; int ldo; float* colsum; int colsum_stride;
-    __device__ __forceinline__ void store(int row, int col, float v, int z) const {
+    __device__ __forceinline__ Aux aux(int, int, int, bool) const { return 0; }
+    __device__ __forceinline__ void store(int row, int col, float v, int z, Aux) const {
         out[z * z_stride + (size_t)row * ldo + col] = v;
     }
     __device__ __forceinline__ void store_colsum(int col, float v, int z) const {
@@ -411,21 +559,26 @@ template <bool COLSUM> struct EpiPartial {   // out[z][row][col] = v ; optional 
 
 template <class G> struct EpiDgradMask {     // scatter a parity class back to NHWC, times ReLU'
     static constexpr bool kColSum = false;
+    typedef float Aux;
     float* dx; const float* act;
-    __device__ __forceinline__ void store(int row, int col, float v, int z) const {
+    __device__ __forceinline__ size_t addr(int row, int col, int z) const {
         const int py = z / G::ST, px = z % G::ST;
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
-        const size_t a = ((size_t)(n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN + col;
-        dx[a] = act[a] > 0.f ? v : 0.f;
+        return ((size_t)(n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN + col;
+    }
+    __device__ __forceinline__ Aux aux(int row, int col, int z, bool ok) const { return act[ok ? addr(row, col, z) : 0]; }
+    __device__ __forceinline__ void store(int row, int col, float v, int z, Aux a) const {
+        dx[addr(row, col, z)] = a > 0.f ? v : 0.f;
     }
 };
 
 struct EpiDenseMask {           // out[row][col] = act[row][col] > 0 ? v : 0
     static constexpr bool kColSum = false;
+    typedef float Aux;
     float* out; const float* act; int ld;
-    __device__ __forceinline__ void store(int row, int col, float v, int) const {
-        const size_t a = (size_t)row * ld + col;
-        out[a] = act[a] > 0.f ? v : 0.f;
+    __device__ __forceinline__ Aux aux(int row, int col, int, bool ok) const { return act[ok ? (size_t)row * ld + col : 0]; }
+    __device__ __forceinline__ void store(int row, int col, float v, int, Aux a) const {
+        out[(size_t)row * ld + col] = a > 0.f ? v : 0.f;
     }
 };
 

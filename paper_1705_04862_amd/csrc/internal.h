@@ -75,19 +75,21 @@ hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };
 
 constexpr int kMaxSeg = 12;
-constexpr int kNormBlocks = 256;
+inline int norm_blocks(int p_int) { return (p_int + 255) / 256; }   // one sum of squares per block
 struct GradSegments {
     int n;
     const float* partial[kMaxSeg]; int n_split[kMaxSeg]; size_t stride[kMaxSeg];
     int count[kMaxSeg]; int off[kMaxSeg]; int padded[kMaxSeg];
 };
-// grads[i] = sum over splits of the partial gradients; block_ss[kNormBlocks] = partial sums of g^2
+// grads[i] = sum over splits of the partial gradients; block_ss[norm_blocks(p_int)] = partial sums of g^2
 hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss);
 struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
                           const float* block_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
                           StatsOut* stats_a, StatsOut* stats_b);
 hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n);
+
+hipError_t delay_us(hipStream_t s, unsigned us);
 
 // host-side Philox4x32-10 (api uses it for parameter initialisation)
 void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);

@@ -13,17 +13,31 @@ typedef ConvGeom<4, 84, 84, 8, 4, 32> NatC1;
 typedef ConvGeom<32, 20, 20, 4, 2, 64> NatC2;
 typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
 
-// tile shapes: BM, BN, BK, waves along m, waves along n, MFMA edge
-typedef Tile<128, 16, 32, 4, 1, 16> T128x16;
-typedef Tile<128, 32, 32, 4, 1, 32> T128x32;
-typedef Tile<64, 64, 32, 2, 2, 32> T64x64;
-typedef Tile<32, 128, 32, 1, 4, 32> T32x128;
-typedef Tile<64, 16, 32, 4, 1, 16> T64x16;
+// tile shapes: BM, BN, BK, waves along m / n / k, MFMA edge, register prefetch stages
+typedef Tile<128, 32, 32, 4, 1, 1, 32, 3> T128x32;
+typedef Tile<64, 32, 64, 2, 1, 2, 32, 4> T64x32;
+typedef Tile<32, 32, 64, 1, 1, 4, 32, 4> T32x32;
+typedef Tile<64, 64, 32, 2, 2, 1, 32, 3> T64x64;
+typedef Tile<32, 64, 64, 1, 2, 2, 32, 4> T32x64;
 
+// big / middle / small tile per output width; wg = tile of the weight-gradient GEMMs.  A 16-wide
+// output (first layer of arch_nips) runs on the 32-wide tiles: the upper 16 columns load zeros and
+// are not stored (these launches are bound by latency, not by the matrix pipes).
 template <int N> struct TileForN;
-template <> struct TileForN<16> { typedef T128x16 type; typedef T64x16 wg; };
-template <> struct TileForN<32> { typedef T128x32 type; typedef T128x32 wg; };
-template <> struct TileForN<64> { typedef T64x64 type; typedef T64x64 wg; };
+template <> struct TileForN<16> { typedef T128x32 big; typedef T64x32 mid; typedef T32x32 small; typedef T64x32 wg; };
+template <> struct TileForN<32> { typedef T128x32 big; typedef T64x32 mid; typedef T32x32 small; typedef T64x32 wg; };
+template <> struct TileForN<64> { typedef T64x64 big; typedef T32x64 mid; typedef T32x32 small; typedef T64x64 wg; };
+
+// Workgroups are dispatched at a finite rate (on the order of 100 per microsecond), so a launch of
+// thousands of small workgroups is bound by dispatch: take the largest tile that still gives about
+// one workgroup per compute unit (256 of them).
+template <class TBig, class TMid, class TSmall, class AL, class BL, class EP>
+static hipError_t launch_auto(hipStream_t s, const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int z) {
+    auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * z; };
+    if (wgs(TBig::BM, TBig::BN) >= 192) return launch_gemm<TBig>(s, al, bl, ep, M, N, K, z, 0);
+    if (wgs(TMid::BM, TMid::BN) >= 192) return launch_gemm<TMid>(s, al, bl, ep, M, N, K, z, 0);
+    return launch_gemm<TSmall>(s, al, bl, ep, M, N, K, z, 0);
+}
 
 NetDesc make_net(int arch, int n_actions) {
     NetDesc n{};
@@ -66,21 +80,21 @@ Split plan_split(int k_total, int tiles, int granule, int target_wgs) {
 // ---------------------------------------------------------------------------------- forward
 template <class G>
 static hipError_t conv_fwd_u8(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
-    typedef typename TileForN<G::COUT>::type T;
+    typedef TileForN<G::COUT> TS;
     const int M = ns * G::HO * G::WO;
     ConvU8RowsK<G> al{(const uint8_t*)in, M};
     DenseKCols bl{W, G::COUT, G::COUT};
     EpiBiasRelu ep{out, b, G::COUT};
-    return launch_gemm<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+    return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::COUT, G::KK, 1);
 }
 template <class G>
 static hipError_t conv_fwd_f32(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
-    typedef typename TileForN<G::COUT>::type T;
+    typedef TileForN<G::COUT> TS;
     const int M = ns * G::HO * G::WO;
     ConvNHWCRowsK<G> al{(const float*)in, M};
     DenseKCols bl{W, G::COUT, G::COUT};
     EpiBiasRelu ep{out, b, G::COUT};
-    return launch_gemm<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+    return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::COUT, G::KK, 1);
 }
 
 hipError_t conv_fwd(hipStream_t s, int arch, int layer, const void* in, const float* W, const float* b,
@@ -99,12 +113,12 @@ hipError_t conv_fwd(hipStream_t s, int arch, int layer, const void* in, const fl
 // ---------------------------------------------------------------------------------- data gradient
 template <class G>
 static hipError_t conv_dgrad_t(hipStream_t s, const float* dy, const float* W, const float* act_in, float* dx, int ns) {
-    typedef typename TileForN<G::CIN>::type T;
+    typedef TileForN<G::CIN> TS;
     const int M = ns * G::HC * G::WC;     // rows per parity class
     DgradGatherRowsK<G> al{dy, M};
     DgradWeightColsK<G> bl{W};
     EpiDgradMask<G> ep{dx, act_in};
-    return launch_gemm<T>(s, al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0);
+    return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST);
 }
 
 hipError_t conv_dgrad(hipStream_t s, int arch, int layer, const float* dy, const float* W,
@@ -161,7 +175,7 @@ static bool fc_small(int ns) { return ns <= 48; }
 
 int fc_fwd_tiles(int arch, int ns) {
     int flat, fc; fc_dims(arch, flat, fc);
-    if (fc_small(ns)) return ((ns + 31) / 32) * (fc / 128);
+    if (fc_small(ns)) return ((ns + 31) / 32) * (fc / 64);
     return ((ns + 63) / 64) * (fc / 64);
 }
 
@@ -170,7 +184,7 @@ hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float
     DenseRowsK al{x, ns, flat};
     DenseKCols bl{W, fc, fc};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
-    if (fc_small(ns)) return launch_gemm<T32x128>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+    if (fc_small(ns)) return launch_gemm<T32x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
     return launch_gemm<T64x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
 }
 
@@ -179,8 +193,7 @@ hipError_t fc_dgrad(hipStream_t s, int arch, const float* dh, const float* W, co
     DenseRowsK al{dh, ns, fc};
     DenseRowsK bl{W, flat, fc};          // B(k = j, n = i) = W[i][j]
     EpiDenseMask ep{dx, act, flat};
-    if (fc_small(ns)) return launch_gemm<T32x128>(s, al, bl, ep, ns, flat, fc, 1, 0);
-    return launch_gemm<T64x64>(s, al, bl, ep, ns, flat, fc, 1, 0);
+    return launch_auto<T64x64, T32x64, T32x64>(s, al, bl, ep, ns, flat, fc, 1);
 }
 
 int fc_wgrad_tiles(int arch) {

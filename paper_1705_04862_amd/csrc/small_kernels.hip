@@ -8,22 +8,36 @@
 
 namespace paac {
 
+// Wavefront (64-lane) reductions: four DPP steps reduce each row of 16 lanes (quad swaps, half-row
+// mirror, row mirror), then the four row results are read with v_readlane and combined.  The result
+// is uniform across the wavefront.
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_mov<0xB1>(v);     // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);     // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);    // row_half_mirror
+    v += dpp_mov<0x140>(v);    // row_mirror
+    const int i = __float_as_int(v);
+    return (__int_as_float(__builtin_amdgcn_readlane(i, 0)) + __int_as_float(__builtin_amdgcn_readlane(i, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(i, 32)) + __int_as_float(__builtin_amdgcn_readlane(i, 48)));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, dpp_mov<0xB1>(v));
+    v = fmaxf(v, dpp_mov<0x4E>(v));
+    v = fmaxf(v, dpp_mov<0x141>(v));
+    v = fmaxf(v, dpp_mov<0x140>(v));
+    const int i = __float_as_int(v);
+    return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(i, 0)), __int_as_float(__builtin_amdgcn_readlane(i, 16))),
+                 fmaxf(__int_as_float(__builtin_amdgcn_readlane(i, 32)), __int_as_float(__builtin_amdgcn_readlane(i, 48))));
 }
 
 // ------------------------------------------------------------------------------------ heads
 // One wavefront per state row.  The fc layer's split partial sums are added, bias and ReLU applied,
 // then A+1 dot products (policy logits, value) are reduced across the 64 lanes; lane k ends up
 // holding logit k.  In select mode the same wavefront computes the softmax and draws the action.
-template <int F>
+template <int F, int KMAX>                 // KMAX >= A + 1 outputs (logits + the value)
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
     constexpr int C = F / 256;            // float4 chunks per lane
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -33,9 +47,18 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int col = c * 256 + lane * 4;
+        const float* src = a.fc_partial + (size_t)row * F + col;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s = 0; s < a.n_split; ++s) {
-            const float4 p = *reinterpret_cast<const float4*>(a.fc_partial + s * a.split_stride + (size_t)row * F + col);
+        int s = 0;
+        for (; s + 8 <= a.n_split; s += 8) {          // eight independent loads in flight
+            float4 p[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) p[q] = *reinterpret_cast<const float4*>(src + (size_t)(s + q) * a.split_stride);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { acc.x += p[q].x; acc.y += p[q].y; acc.z += p[q].z; acc.w += p[q].w; }
+        }
+        for (; s < a.n_split; ++s) {
+            const float4 p = *reinterpret_cast<const float4*>(src + (size_t)s * a.split_stride);
             acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w;
         }
         const float4 b = *reinterpret_cast<const float4*>(a.fc_b + col);
@@ -44,19 +67,28 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
         h[c] = acc;
         if (a.h_out) *reinterpret_cast<float4*>(a.h_out + (size_t)row * F + col) = acc;
     }
-    float z = -INFINITY, v = 0.f;
-    for (int k = 0; k <= a.A; ++k) {
+    // all dot products first, then all reductions: the shuffles of different outputs are independent
+    // (branch-free: outputs beyond A re-read the value row and are ignored)
+    float d[KMAX];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
         const float* w = k < a.A ? a.pi_w + (size_t)k * F : a.v_w;
-        float d = 0.f;
+        d[k] = 0.f;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             const float4 w4 = *reinterpret_cast<const float4*>(w + c * 256 + lane * 4);
-            d += h[c].x * w4.x + h[c].y * w4.y + h[c].z * w4.z + h[c].w * w4.w;
+            d[k] += h[c].x * w4.x + h[c].y * w4.y + h[c].z * w4.z + h[c].w * w4.w;
         }
-        d = wave_sum(d);
-        if (k < a.A) { if (lane == k) z = d + a.pi_b[k]; }
-        else v = d + a.v_b[0];
     }
+    float z = -INFINITY, v = 0.f;
+    const float my_b = lane < a.A ? a.pi_b[lane] : 0.f;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+        const float t = wave_sum(d[k]);
+        z = (lane == k && k < a.A) ? t + my_b : z;
+        v = (k == a.A) ? t : v;
+    }
+    v += a.v_b[0];
     if (a.values_out && lane == 0) a.values_out[row] = v;
     if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
     if (a.uniforms) {
@@ -69,7 +101,7 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
         int act = a.A - 1;
         bool found = false;
         for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
-            cdf = cdf + __shfl(p, k, 64);
+            cdf = cdf + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), k));
             if (!found && u < cdf) { act = k; found = true; }
         }
         if (lane == 0) a.actions_out[row] = act;
@@ -79,9 +111,16 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
 hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a) {
     if (a.rows <= 0) return hipErrorInvalidValue;
     dim3 grid((a.rows + 3) / 4);
-    if (F == 256) hipLaunchKernelGGL(heads_fwd_kernel<256>, grid, dim3(256), 0, s, a);
-    else if (F == 512) hipLaunchKernelGGL(heads_fwd_kernel<512>, grid, dim3(256), 0, s, a);
-    else return hipErrorInvalidValue;
+    const int outs = a.A + 1;
+    if (F == 256) {
+        if (outs <= 8) hipLaunchKernelGGL((heads_fwd_kernel<256, 8>), grid, dim3(256), 0, s, a);
+        else if (outs <= 19) hipLaunchKernelGGL((heads_fwd_kernel<256, 19>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((heads_fwd_kernel<256, 33>), grid, dim3(256), 0, s, a);
+    } else if (F == 512) {
+        if (outs <= 8) hipLaunchKernelGGL((heads_fwd_kernel<512, 8>), grid, dim3(256), 0, s, a);
+        else if (outs <= 19) hipLaunchKernelGGL((heads_fwd_kernel<512, 19>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((heads_fwd_kernel<512, 33>), grid, dim3(256), 0, s, a);
+    } else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -92,6 +131,7 @@ hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a) {
 constexpr int kEnvPerBlock = 32;
 int loss_blocks(int n_e) { return (n_e + kEnvPerBlock - 1) / kEnvPerBlock; }
 
+template <int AMAX>
 __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
     const int tid = threadIdx.x;
     const int e0 = blockIdx.x * kEnvPerBlock;
@@ -101,10 +141,21 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
     if (tid < ne_blk) {
         const int e = e0 + tid;
         float R = a.values[B + e];
-        for (int t = a.T - 1; t >= 0; --t) {
-            const int i = t * a.n_e + e;
-            R = a.rewards[i] + gamma * (a.dones[i] ? 0.f : 1.f) * R;
-            a.returns[i] = R;
+        for (int t1 = a.T; t1 > 0; t1 -= 8) {          // eight timesteps of loads in flight, then the scan
+            float r[8]; uint8_t d[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int t = max(t1 - 1 - q, 0);
+                r[q] = a.rewards[t * a.n_e + e]; d[q] = a.dones[t * a.n_e + e];
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int t = t1 - 1 - q;
+                if (t >= 0) {
+                    R = r[q] + gamma * (d[q] ? 0.f : 1.f) * R;
+                    a.returns[t * a.n_e + e] = R;
+                }
+            }
         }
     }
     __syncthreads();
@@ -113,26 +164,34 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
     for (int idx = tid; idx < a.T * ne_blk; idx += 256) {
         const int t = idx / ne_blk, e = e0 + idx % ne_blk;
         const int i = t * a.n_e + e;
-        const float* z = a.logits + (size_t)i * a.A;
-        float m = z[0];
-        for (int k = 1; k < a.A; ++k) m = fmaxf(m, z[k]);
-        float se = 0.f;
-        for (int k = 0; k < a.A; ++k) se += expf(z[k] - m);
-        const float lse = logf(se);
-        float H = 0.f;
-        for (int k = 0; k < a.A; ++k) {
-            const float lp = z[k] - m - lse;
-            H -= expf(z[k] - m) / se * lp;
-        }
+        const float* zp = a.logits + (size_t)i * a.A;
+        float z[AMAX];
+#pragma unroll
+        for (int k = 0; k < AMAX; ++k) z[k] = zp[min(k, a.A - 1)];      // clamped: no divergent loads
         const float V = a.values[i], R = a.returns[i], adv = R - V;
         int act = a.actions[i];
         act = act < 0 ? 0 : (act >= a.A ? a.A - 1 : act);
-        s_pl += -adv * (z[act] - m - lse);
+        float m = z[0];
+#pragma unroll
+        for (int k = 1; k < AMAX; ++k) m = fmaxf(m, z[k]);
+        float ex[AMAX], se = 0.f;
+#pragma unroll
+        for (int k = 0; k < AMAX; ++k) { ex[k] = k < a.A ? expf(z[k] - m) : 0.f; se += ex[k]; }
+        const float lse = logf(se), inv_se = 1.0f / se;
+        float H = 0.f, lp_act = 0.f;
+#pragma unroll
+        for (int k = 0; k < AMAX; ++k) {
+            const float lp = z[k] - m - lse;
+            H -= (k < a.A) ? ex[k] * inv_se * lp : 0.f;
+            lp_act = (k == act) ? lp : lp_act;
+        }
+        s_pl += -adv * lp_act;
         s_h += H;
         s_vl += (R - V) * (R - V);
-        for (int k = 0; k < a.A; ++k) {
-            const float lp = z[k] - m - lse, p = expf(z[k] - m) / se;
-            a.dz[(size_t)i * a.A + k] = (-adv * ((k == act ? 1.f : 0.f) - p) + beta * p * (lp + H)) * invB;
+#pragma unroll
+        for (int k = 0; k < AMAX; ++k) {
+            const float lp = z[k] - m - lse, p = ex[k] * inv_se;
+            if (k < a.A) a.dz[(size_t)i * a.A + k] = (-adv * ((k == act ? 1.f : 0.f) - p) + beta * p * (lp + H)) * invB;
         }
         a.dv[i] = 2.f * cv * (V - R) * invB;
     }
@@ -147,7 +206,10 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
 }
 
 hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
-    hipLaunchKernelGGL(returns_loss_kernel, dim3(loss_blocks(a.n_e)), dim3(256), 0, s, a);
+    const dim3 grid(loss_blocks(a.n_e));
+    if (a.A <= 8) hipLaunchKernelGGL(returns_loss_kernel<8>, grid, dim3(256), 0, s, a);
+    else if (a.A <= 18) hipLaunchKernelGGL(returns_loss_kernel<18>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(returns_loss_kernel<32>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -186,10 +248,18 @@ __global__ __launch_bounds__(256) void heads_wgrad_kernel(int F, int A, int rows
     const int j = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y, c = blockIdx.z;
     const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
     float acc = 0.f, accb = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const float g = k < A ? dz[(size_t)r * A + k] : dv[r];
-        acc += g * h[(size_t)r * F + j];
-        accb += g;
+    for (int r = r0; r < r1; r += 8) {                 // eight rows of loads in flight
+        float g[8], hv[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int rr = min(r + q, r1 - 1);
+            g[q] = k < A ? dz[(size_t)rr * A + k] : dv[rr];
+            hv[q] = h[(size_t)rr * F + j];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (r + q < r1) { acc += g[q] * hv[q]; accb += g[q]; }
+        }
     }
     pw[((size_t)c * (A + 1) + k) * F + j] = acc;
     if (j == 0) pb[c * (A + 1) + k] = accb;
@@ -217,40 +287,50 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 }
 
 // Sums the split partial gradients in a fixed order (bit-stable from run to run), writes the
-// gradient arena and one partial sum of squares per block.
+// gradient arena and one partial sum of squares per block.  One arena element per thread.
 __global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegments seg, int p_int, float* grads, float* block_ss) {
     __shared__ float red[256];
-    float ss = 0.f;
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < p_int; i += gridDim.x * 256) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    float g = 0.f;
+    if (i < p_int) {
         int sidx = 0;
         for (int q = 1; q < seg.n; ++q) if (i >= seg.off[q]) sidx = q;
         const int local = i - seg.off[sidx];
-        float g = 0.f;
         if (local < seg.count[sidx]) {
             const float* p = seg.partial[sidx] + local;
-            for (int q = 0; q < seg.n_split[sidx]; ++q) g += p[q * seg.stride[sidx]];
+            const size_t st = seg.stride[sidx];
+            const int ns = seg.n_split[sidx];
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            int q = 0;
+            for (; q + 8 <= ns; q += 8) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) acc[r] += p[(size_t)(q + r) * st];
+            }
+            for (; q < ns; ++q) acc[0] += p[(size_t)q * st];
+            g = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
         }
         grads[i] = g;
-        ss += g * g;
     }
-    const float tot = block_sum_256(ss, red);
+    const float tot = block_sum_256(g * g, red);
     if (threadIdx.x == 0) block_ss[blockIdx.x] = tot;
 }
 
 hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss) {
-    hipLaunchKernelGGL(grad_reduce_norm_kernel, dim3(kNormBlocks), dim3(256), 0, s, seg, p_int, grads, block_ss);
+    hipLaunchKernelGGL(grad_reduce_norm_kernel, dim3(norm_blocks(p_int)), dim3(256), 0, s, seg, p_int, grads, block_ss);
     return hipGetLastError();
 }
 
 // Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
 //   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
-// Every block re-derives the norm from the kNormBlocks partial sums (same order everywhere).
+// Every block re-derives the norm from the per-block partial sums (same order everywhere).
 __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
-                                                             const float* block_ss, const float* hp,
+                                                             const float* block_ss, int n_ss, const float* hp,
                                                              const float* loss_partials, int n_loss_blocks,
                                                              StatsOut* stats_a, StatsOut* stats_b) {
     __shared__ float red[256];
-    const float tot = block_sum_256(block_ss[threadIdx.x], red);
+    float part = 0.f;
+    for (int q = threadIdx.x; q < n_ss; q += 256) part += block_ss[q];
+    const float tot = block_sum_256(part, red);
     const float norm = sqrtf(tot);
     const float clip = hp[HP_CLIP], lr = hp[HP_LR], alpha = hp[HP_ALPHA], eps = hp[HP_EPS];
     const float scale = norm > clip ? clip / norm : 1.0f;
@@ -284,7 +364,7 @@ hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, con
     int blocks = (n4 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(rmsprop_update_kernel, dim3(blocks), dim3(256), 0, s, n4, (float4*)theta, (float4*)g2,
-                       (const float4*)grads, block_ss, hp, loss_partials, n_loss_blocks, stats_a, stats_b);
+                       (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b);
     return hipGetLastError();
 }
 
@@ -327,6 +407,22 @@ hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* o
     if (n == 0) return hipSuccess;
     const size_t blocks = ((n + 3) / 4 + 255) / 256;
     hipLaunchKernelGGL(fill_uniforms_kernel, dim3((unsigned)blocks), dim3(256), 0, s, seed, offset, out, n);
+    return hipGetLastError();
+}
+
+// Holds the stream busy for about `us` microseconds (bounded spin on the 100 MHz wall clock) so that
+// the launches that follow are already queued when the GPU reaches them: used only by the per-kernel
+// timing mode, whose event pairs would otherwise also measure the host's launch rate.
+__global__ void delay_kernel(unsigned us) {
+    const unsigned long long t0 = wall_clock64();
+    const unsigned long long ticks = (unsigned long long)us * 100ull;
+    for (int it = 0; it < 2000000; ++it) {             // hard bound: the kernel always exits
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(32);
+    }
+}
+hipError_t delay_us(hipStream_t s, unsigned us) {
+    hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(1), 0, s, us);
     return hipGetLastError();
 }
 
