@@ -63,16 +63,31 @@ def main():
     ap.add_argument("--rollouts", type=int, default=4, help="distinct resident rollouts rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=50)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a 256 MiB device-to-device copy 10 times (calibrates the HBM byte counters)")
+    ap.add_argument("--n_e", type=int, default=0, help="override the configuration's environment count (n_e sweep)")
+    ap.add_argument("--t_max", type=int, default=0, help="override the configuration's rollout length")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     import numpy as np
     import torch
+    if args.copy_probe:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": 256 << 20, "copy_probe_bytes_written": 256 << 20, "launches": 10}))
+        return
     from paper_1705_04862_amd import inputs as I
     from paper_1705_04862_amd import paac as P
 
     cfg = I.CONFIGS[args.config]
+    if args.n_e or args.t_max:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, n_e=args.n_e or cfg.n_e, t_max=args.t_max or cfg.t_max)
     net, n_e, T = cfg.net, cfg.n_e, cfg.t_max
     torch.cuda.set_device(0)
     ctx = P.Paac(net.arch, n_e, T, net.n_actions, cfg.precision)
