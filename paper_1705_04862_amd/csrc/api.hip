@@ -11,6 +11,8 @@
 
 using namespace paac;
 
+namespace paac { thread_local ProfEvents tl_prof = {nullptr, nullptr}; }
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -229,9 +231,10 @@ struct Launcher {
     template <class F> void run(int id, F&& f) {
         if (err != hipSuccess) return;
         hipEvent_t a = nullptr, b = nullptr;
-        if (prof) { a = get_event(c); b = get_event(c); if (a) hipEventRecord(a, s); }
-        hipError_t e = f();
-        if (prof && a && b) { hipEventRecord(b, s); c->pending.push_back({id, a, b}); }
+        if (prof) { a = get_event(c); b = get_event(c); if (a && b) tl_prof = ProfEvents{a, b}; }
+        hipError_t e = f();                        // exactly one kernel launch
+        tl_prof = ProfEvents{nullptr, nullptr};
+        if (prof && a && b) c->pending.push_back({id, a, b});
         if (e != hipSuccess) { err = e; err_id = id; }
     }
 };

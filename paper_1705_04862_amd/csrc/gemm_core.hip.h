@@ -15,6 +15,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "internal.h"
 #include <type_traits>
 
 namespace paac {
@@ -589,7 +590,7 @@ inline hipError_t launch_gemm(hipStream_t s, const AL& al, const BL& bl, const E
     const int m_tiles = (M + T::BM - 1) / T::BM, n_tiles = (N + T::BN - 1) / T::BN;
     if (M <= 0 || N <= 0 || z_count <= 0) return hipErrorInvalidValue;
     dim3 grid(m_tiles * n_tiles, z_count, 1);
-    hipLaunchKernelGGL((gemm_kernel<T, AL, BL, EP>), grid, dim3(256), 0, s, al, bl, ep, M, N, K, k_per_split, m_tiles);
+    launch_k((gemm_kernel<T, AL, BL, EP>), grid, dim3(256), s, al, bl, ep, M, N, K, k_per_split, m_tiles);
     return hipGetLastError();
 }
 

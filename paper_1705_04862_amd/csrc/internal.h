@@ -1,10 +1,22 @@
 // Internal interfaces between the translation units of libpaac (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
 namespace paac {
+
+// Every kernel of the library is launched through launch_k.  In the per-kernel timing mode the
+// caller sets tl_prof around one launch; the launch then carries a start/stop event pair that is
+// stamped with the kernel's own begin and end on the GPU (independent of the host's launch rate).
+struct ProfEvents { hipEvent_t start, stop; };
+extern thread_local ProfEvents tl_prof;
+template <class K, class... Args>
+inline void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t s, Args... args) {
+    if (tl_prof.start) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, tl_prof.start, tl_prof.stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
 
 // Static description of one of the two networks (Experiments: arch_nips, arch_nature).
 struct ConvDesc { int cin, h, w, ks, st, cout, ho, wo, kk; };

@@ -113,13 +113,13 @@ hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a) {
     dim3 grid((a.rows + 3) / 4);
     const int outs = a.A + 1;
     if (F == 256) {
-        if (outs <= 8) hipLaunchKernelGGL((heads_fwd_kernel<256, 8>), grid, dim3(256), 0, s, a);
-        else if (outs <= 19) hipLaunchKernelGGL((heads_fwd_kernel<256, 19>), grid, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL((heads_fwd_kernel<256, 33>), grid, dim3(256), 0, s, a);
+        if (outs <= 8) launch_k((heads_fwd_kernel<256, 8>), grid, dim3(256), s, a);
+        else if (outs <= 19) launch_k((heads_fwd_kernel<256, 19>), grid, dim3(256), s, a);
+        else launch_k((heads_fwd_kernel<256, 33>), grid, dim3(256), s, a);
     } else if (F == 512) {
-        if (outs <= 8) hipLaunchKernelGGL((heads_fwd_kernel<512, 8>), grid, dim3(256), 0, s, a);
-        else if (outs <= 19) hipLaunchKernelGGL((heads_fwd_kernel<512, 19>), grid, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL((heads_fwd_kernel<512, 33>), grid, dim3(256), 0, s, a);
+        if (outs <= 8) launch_k((heads_fwd_kernel<512, 8>), grid, dim3(256), s, a);
+        else if (outs <= 19) launch_k((heads_fwd_kernel<512, 19>), grid, dim3(256), s, a);
+        else launch_k((heads_fwd_kernel<512, 33>), grid, dim3(256), s, a);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -207,9 +207,9 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
 
 hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
     const dim3 grid(loss_blocks(a.n_e));
-    if (a.A <= 8) hipLaunchKernelGGL(returns_loss_kernel<8>, grid, dim3(256), 0, s, a);
-    else if (a.A <= 18) hipLaunchKernelGGL(returns_loss_kernel<18>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(returns_loss_kernel<32>, grid, dim3(256), 0, s, a);
+    if (a.A <= 8) launch_k(returns_loss_kernel<8>, grid, dim3(256), s, a);
+    else if (a.A <= 18) launch_k(returns_loss_kernel<18>, grid, dim3(256), s, a);
+    else launch_k(returns_loss_kernel<32>, grid, dim3(256), s, a);
     return hipGetLastError();
 }
 
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void heads_dh_kernel(int F4, int A, int rows, 
 hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
                     const float* v_w, const float* h, float* dh) {
     const int n = rows * (F / 4);
-    hipLaunchKernelGGL(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), 0, s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh);
+    launch_k(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh);
     return hipGetLastError();
 }
 
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256) void heads_wgrad_kernel(int F, int A, int rows
 hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
                        const float* h, float* pw, float* pb) {
     const int rpc = (rows + n_chunk - 1) / n_chunk;
-    hipLaunchKernelGGL(heads_wgrad_kernel, dim3(F / 256, A + 1, n_chunk), dim3(256), 0, s, F, A, rows, rpc, dz, dv, h, pw, pb);
+    launch_k(heads_wgrad_kernel, dim3(F / 256, A + 1, n_chunk), dim3(256), s, F, A, rows, rpc, dz, dv, h, pw, pb);
     return hipGetLastError();
 }
 
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegment
 }
 
 hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss) {
-    hipLaunchKernelGGL(grad_reduce_norm_kernel, dim3(norm_blocks(p_int)), dim3(256), 0, s, seg, p_int, grads, block_ss);
+    launch_k(grad_reduce_norm_kernel, dim3(norm_blocks(p_int)), dim3(256), s, seg, p_int, grads, block_ss);
     return hipGetLastError();
 }
 
@@ -363,7 +363,7 @@ hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, con
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(rmsprop_update_kernel, dim3(blocks), dim3(256), 0, s, n4, (float4*)theta, (float4*)g2,
+    launch_k(rmsprop_update_kernel, dim3(blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
                        (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b);
     return hipGetLastError();
 }
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256) void fill_uniforms_kernel(uint64_t seed, uint6
 hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n) {
     if (n == 0) return hipSuccess;
     const size_t blocks = ((n + 3) / 4 + 255) / 256;
-    hipLaunchKernelGGL(fill_uniforms_kernel, dim3((unsigned)blocks), dim3(256), 0, s, seed, offset, out, n);
+    launch_k(fill_uniforms_kernel, dim3((unsigned)blocks), dim3(256), s, seed, offset, out, n);
     return hipGetLastError();
 }
 
@@ -422,7 +422,7 @@ __global__ void delay_kernel(unsigned us) {
     }
 }
 hipError_t delay_us(hipStream_t s, unsigned us) {
-    hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(1), 0, s, us);
+    launch_k(delay_kernel, dim3(1), dim3(1), s, us);
     return hipGetLastError();
 }
 
