@@ -44,6 +44,10 @@ struct OracleNet {
     int32_t conv_cout[4], conv_k[4], conv_stride[4];
     int32_t fc;
     int32_t n_actions;
+    int32_t bf16;      // 0: everything in double.  1: emulate bf16 STORAGE of the configurations that
+                       // name it: conv/fc weights as used by forward and backward, conv activations and
+                       // the gradients handed from layer to layer are rounded to bf16 (round to nearest
+                       // even); sums stay in double, master weights and the optimiser stay unrounded.
 };
 
 struct OracleHParams {
@@ -60,6 +64,7 @@ struct OracleStats {
 namespace {
 
 struct Shapes {
+    int bf16;
     int n_conv;
     int cin[4], cout[4], k[4], s[4], hin[4], win[4], hout[4], wout[4];
     size_t w_off[4], b_off[4];
@@ -71,6 +76,7 @@ struct Shapes {
 
 Shapes make_shapes(const OracleNet& n) {
     Shapes s{};
+    s.bf16 = n.bf16;
     s.n_conv = n.n_conv;
     int c = n.in_c, h = n.in_h, w = n.in_w;
     size_t off = 0, aoff = 0;
@@ -97,6 +103,31 @@ Shapes make_shapes(const OracleNet& n) {
     return s;
 }
 
+// Round a value to the nearest bf16 (8-bit significand, ties to even), returned as double.
+double round_bf16(double v) {
+    float f = (float)v;
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return f;          // inf / nan unchanged
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+inline double q(const Shapes& S, double v) { return S.bf16 ? round_bf16(v) : v; }
+
+// Parameters as the forward and backward passes see them: conv and fc weights rounded to bf16 in the
+// bf16 configurations (biases and the two heads stay as they are).
+std::vector<double> used_params(const Shapes& S, const double* th) {
+    std::vector<double> t(th, th + S.P);
+    if (S.bf16) {
+        for (int l = 0; l < S.n_conv; ++l)
+            for (size_t i = S.w_off[l]; i < S.b_off[l]; ++i) t[i] = round_bf16(t[i]);
+        for (size_t i = S.fcw_off; i < S.fcb_off; ++i) t[i] = round_bf16(t[i]);
+    }
+    return t;
+}
+
 // Forward pass of one sample.  x: uint8 [C][H][W].  act: post-ReLU outputs of every conv layer
 // and of the fc layer, laid out per Shapes::act_off.  logits[A], *value.
 void forward_sample(const Shapes& S, const double* th, const uint8_t* x, double* act,
@@ -118,7 +149,7 @@ void forward_sample(const Shapes& S, const double* th, const uint8_t* x, double*
                             for (int kx = 0; kx < K; ++kx)
                                 acc += W[(((size_t)co * S.cin[l] + ci) * K + ky) * K + kx] *
                                        in[((size_t)ci * Hi + (oy * st + ky)) * Wi + (ox * st + kx)];
-                    out[((size_t)co * S.hout[l] + oy) * S.wout[l] + ox] = acc > 0.0 ? acc : 0.0;
+                    out[((size_t)co * S.hout[l] + oy) * S.wout[l] + ox] = acc > 0.0 ? q(S, acc) : 0.0;
                 }
         in = out;
     }
@@ -175,7 +206,7 @@ void backward_sample(const Shapes& S, const double* th, const uint8_t* x, const 
     std::vector<double> dcur(S.flat, 0.0);
     for (int j = 0; j < S.fc; ++j) {
         if (!(h[j] > 0.0)) continue;            // ReLU'(pre) = 1[pre > 0]; post > 0 iff pre > 0
-        const double d = dh[j];
+        const double d = q(S, dh[j]);
         g[S.fcb_off + j] += d;
         for (int i = 0; i < S.flat; ++i) {
             g[S.fcw_off + (size_t)j * S.flat + i] += d * last[i];
@@ -200,7 +231,7 @@ void backward_sample(const Shapes& S, const double* th, const uint8_t* x, const 
                 for (int ox = 0; ox < S.wout[l]; ++ox) {
                     const size_t o = ((size_t)co * S.hout[l] + oy) * S.wout[l] + ox;
                     if (!(out[o] > 0.0)) continue;
-                    const double d = dcur[o];
+                    const double d = q(S, dcur[o]);
                     g[S.b_off[l] + co] += d;
                     for (int ci = 0; ci < S.cin[l]; ++ci)
                         for (int ky = 0; ky < K; ++ky)
@@ -224,8 +255,10 @@ int n_threads() {
 }
 
 // Forward over N samples; acts may be null (then activations are discarded per sample).
-void forward_batch(const Shapes& S, const double* th, const uint8_t* states, int N,
+void forward_batch(const Shapes& S, const double* th_master, const uint8_t* states, int N,
                    double* acts, double* logits, double* values) {
+    const std::vector<double> used = used_params(S, th_master);
+    const double* th = used.data();
     const size_t in_sz = (size_t)S.cin[0] * S.hin[0] * S.win[0];
 #pragma omp parallel
     {
@@ -280,8 +313,10 @@ void loss_and_grads(const double* logits, const double* values, const double* R,
 }
 
 // Gradient of the loss over B samples given dz/dv; deterministic reduction over per-thread buffers.
-void backward_batch(const Shapes& S, const double* th, const uint8_t* states, const double* acts,
+void backward_batch(const Shapes& S, const double* th_master, const uint8_t* states, const double* acts,
                     const double* dz, const double* dv, int B, double* g) {
+    const std::vector<double> used = used_params(S, th_master);
+    const double* th = used.data();
     const size_t in_sz = (size_t)S.cin[0] * S.hin[0] * S.win[0];
     const int nt = std::max(1, std::min(n_threads(), B));
     std::vector<std::vector<double>> gl(nt, std::vector<double>(S.P, 0.0));
@@ -311,6 +346,8 @@ void oracle_set_threads(int n) {
     (void)n;
 #endif
 }
+
+double oracle_round_bf16(double v) { return round_bf16(v); }
 
 uint64_t oracle_param_count(const OracleNet* net) { return make_shapes(*net).P; }
 uint64_t oracle_act_per_sample(const OracleNet* net) { return make_shapes(*net).act_per_sample; }

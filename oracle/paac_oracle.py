@@ -31,7 +31,8 @@ def build(force: bool = False) -> str:
 class _Net(C.Structure):
     _fields_ = [("in_c", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32),
                 ("n_conv", C.c_int32), ("conv_cout", C.c_int32 * 4), ("conv_k", C.c_int32 * 4),
-                ("conv_stride", C.c_int32 * 4), ("fc", C.c_int32), ("n_actions", C.c_int32)]
+                ("conv_stride", C.c_int32 * 4), ("fc", C.c_int32), ("n_actions", C.c_int32),
+                ("bf16", C.c_int32)]
 
 
 class _HP(C.Structure):
@@ -56,6 +57,8 @@ def _load():
         _lib.oracle_clip_f64.restype = C.c_double
         _lib.oracle_surrogate_loss_f64.restype = C.c_double
         _lib.oracle_threads.restype = C.c_int
+        _lib.oracle_round_bf16.restype = C.c_double
+        _lib.oracle_round_bf16.argtypes = [C.c_double]
     return _lib
 
 
@@ -66,6 +69,7 @@ def _net(net) -> _Net:
     for i, (co, k, s) in enumerate(net.conv):
         n.conv_cout[i], n.conv_k[i], n.conv_stride[i] = co, k, s
     n.fc, n.n_actions = net.fc, net.n_actions
+    n.bf16 = int(getattr(net, "bf16", 0))
     return n
 
 
@@ -75,6 +79,10 @@ def _p(a, t):
 
 def _c(a, dt):
     return np.ascontiguousarray(a, dtype=dt)
+
+
+def round_bf16(v: float) -> float:
+    return float(_load().oracle_round_bf16(float(v)))
 
 
 def threads() -> int:

@@ -77,14 +77,22 @@ struct Plan {
     int head_chunks, n_loss_blocks;
 };
 
-Plan make_plan(const NetDesc& n, int n_e, int T) {
+Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
     Plan p{};
     p.n_e = n_e; p.T = T; p.B = n_e * T; p.Bp = n_e * (T + 1);
-    p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
-    p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
-    for (int l = 0; l < n.n_conv; ++l)
-        p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 64, 256);
-    p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 256);
+    if (bf16) {
+        p.sel_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, n_e), 64, 256);
+        p.trn_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, p.Bp), 64, 256);
+        for (int l = 0; l < n.n_conv; ++l)
+            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, 512);
+        p.fc_wg = plan_split(p.B, fc_wgrad_tiles_bf16(n.arch), 64, 256);
+    } else {
+        p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
+        p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
+        for (int l = 0; l < n.n_conv; ++l)
+            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 64, 256);
+        p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 256);
+    }
     p.head_chunks = p.B / 8 < 1 ? 1 : (p.B / 8 > 128 ? 128 : p.B / 8);
     p.n_loss_blocks = loss_blocks(n_e);
     return p;
@@ -94,14 +102,17 @@ Plan make_plan(const NetDesc& n, int n_e, int T) {
 struct Buffers {
     float *theta, *g2, *grads, *hp, *block_ss, *loss_partials;
     StatsOut* stats;
-    float* act[3];          // conv outputs, NHWC, Bp rows
-    float *fc_partial, *h, *logits, *values, *returns, *dz, *dv, *dh;
-    float* dact[3];         // gradient w.r.t. conv outputs, B rows
+    void* act[3];           // conv outputs, NHWC, Bp rows (fp32, or bf16 in the bf16 configuration)
+    float *fc_partial, *h, *logits, *values, *returns, *dz, *dv;
+    void* dh;               // gradient w.r.t. the fc output (same element type as act)
+    void* dact[3];          // gradient w.r.t. conv outputs, B rows
+    bf16_t *wt[3], *wd[3], *fc_t, *fc_c;   // bf16 weight copies (bf16 configuration only)
+    WeightCopies copies;
     float *pw[3], *pb[3], *fc_pw, *fc_pb, *hd_pw, *hd_pb;
     size_t bytes;
 };
 
-Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, char* base) {
+Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* base) {
     Buffers b{};
     size_t off = 0;
     auto take = [&](size_t floats) {
@@ -114,14 +125,14 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, char* base) {
     b.stats = reinterpret_cast<StatsOut*>(take(16));
     for (int l = 0; l < n.n_conv; ++l) {
         const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout;
-        b.act[l] = take(per * p.Bp);
-        b.dact[l] = take(per * p.B);
+        b.act[l] = take(bf16 ? (per * p.Bp + 1) / 2 : per * p.Bp);
+        b.dact[l] = take(bf16 ? (per * p.B + 1) / 2 : per * p.B);
     }
     const size_t fcp_sel = (size_t)p.sel_fc.n * p.n_e * n.fc, fcp_trn = (size_t)p.trn_fc.n * p.Bp * n.fc;
     b.fc_partial = take(fcp_sel > fcp_trn ? fcp_sel : fcp_trn);
     b.h = take((size_t)p.Bp * n.fc);
     b.logits = take((size_t)p.Bp * n.n_actions); b.values = take(p.Bp); b.returns = take(p.B);
-    b.dz = take((size_t)p.B * n.n_actions); b.dv = take(p.B); b.dh = take((size_t)p.B * n.fc);
+    b.dz = take((size_t)p.B * n.n_actions); b.dv = take(p.B); b.dh = take((size_t)p.B * n.fc);   // sized for fp32
     for (int l = 0; l < n.n_conv; ++l) {
         b.pw[l] = take((size_t)p.wg[l].n * n.conv[l].kk * n.conv[l].cout);
         b.pb[l] = take((size_t)p.wg[l].n * n.conv[l].cout);
@@ -129,6 +140,20 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, char* base) {
     b.fc_pw = take((size_t)p.fc_wg.n * n.flat * n.fc); b.fc_pb = take((size_t)p.fc_wg.n * n.fc);
     b.hd_pw = take((size_t)p.head_chunks * (n.n_actions + 1) * n.fc);
     b.hd_pb = take((size_t)p.head_chunks * (n.n_actions + 1));
+    if (bf16) {
+        WeightCopies& w = b.copies;
+        auto copy = [&](bf16_t*& dst, int src_off, int K, int C, int cin, int mode) {
+            dst = reinterpret_cast<bf16_t*>(take(((size_t)K * C + 1) / 2));
+            w.dst[w.n] = dst; w.start[w.n] = w.total; w.src_off[w.n] = src_off; w.K[w.n] = K; w.C[w.n] = C;
+            w.cin[w.n] = cin; w.mode[w.n] = mode; w.total += K * C; ++w.n;
+        };
+        for (int l = 0; l < n.n_conv; ++l) {
+            copy(b.wt[l], a.conv_w[l], n.conv[l].kk, n.conv[l].cout, n.conv[l].cin, 0);
+            if (l > 0) copy(b.wd[l], a.conv_w[l], n.conv[l].kk, n.conv[l].cout, n.conv[l].cin, 2);
+        }
+        copy(b.fc_t, a.fc_w, n.flat, n.fc, 1, 0);
+        copy(b.fc_c, a.fc_w, n.flat, n.fc, 1, 1);
+    }
     b.bytes = off;
     return b;
 }
@@ -137,14 +162,14 @@ enum KernelId {
     K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
     K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_DH, K_TRN_HEADS_WG,
     K_TRN_FC_WG, K_TRN_FC_DG, K_TRN_CONV3_WG, K_TRN_CONV3_DG, K_TRN_CONV2_WG, K_TRN_CONV2_DG, K_TRN_CONV1_WG,
-    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_COUNT
+    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_COUNT
 };
 const char* const kKernelNames[K_COUNT] = {
     "select.conv1_fwd", "select.conv2_fwd", "select.conv3_fwd", "select.fc_fwd", "select.heads_sample",
     "train.conv1_fwd", "train.conv2_fwd", "train.conv3_fwd", "train.fc_fwd", "train.heads_fwd", "train.returns_loss",
     "train.heads_dh", "train.heads_wgrad", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
     "train.conv3_dgrad", "train.conv2_wgrad", "train.conv2_dgrad", "train.conv1_wgrad", "train.grad_reduce_norm",
-    "train.clip_rmsprop"};
+    "train.clip_rmsprop", "train.bf16_weight_copies"};
 
 struct GraphKey {
     int kind;                 // 0 select, 1 train
@@ -202,7 +227,7 @@ int check_config(const paac_config* cfg, std::string* why) {
     if (cfg->t_max < 1 || cfg->t_max > 4096) { *why = "t_max out of range"; return PAAC_E_BADCONFIG; }
     if (cfg->n_actions < 2 || cfg->n_actions > PAAC_MAX_ACTIONS) { *why = "n_actions must be 2..32"; return PAAC_E_BADCONFIG; }
     if (cfg->in_c != 4 || cfg->in_h != 84 || cfg->in_w != 84) { *why = "input must be 4x84x84"; return PAAC_E_BADCONFIG; }
-    if (cfg->precision != PAAC_PREC_FP32) { *why = "only PAAC_PREC_FP32 is implemented"; return PAAC_E_BADCONFIG; }
+    if (cfg->precision != PAAC_PREC_FP32 && cfg->precision != PAAC_PREC_BF16) { *why = "precision must be 0 (fp32) or 1 (bf16)"; return PAAC_E_BADCONFIG; }
     // row counts are held in int: (t_max+1) n_e 400 output positions must fit
     if ((double)cfg->n_e * (cfg->t_max + 1) * 400.0 * 64.0 > 2.0e9) { *why = "n_e*(t_max+1) too large"; return PAAC_E_BADCONFIG; }
     return PAAC_OK;
@@ -246,11 +271,14 @@ struct TrainArgs { const uint8_t* states; const int32_t* actions; const float* r
 void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0) {
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf;
     const void* in = states;
+    const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
     for (int l = 0; l < n.n_conv; ++l) {
-        L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], b.act[l], ns); });
+        if (bf16) L.run(id0 + l, [&] { return conv_fwd_bf16(L.s, n.arch, l, in, b.wt[l], b.theta + a.conv_b[l], (bf16_t*)b.act[l], ns); });
+        else L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], (float*)b.act[l], ns); });
         in = b.act[l];
     }
-    L.run(id0 + 3, [&] { return fc_fwd(L.s, n.arch, b.act[n.n_conv - 1], b.theta + a.fc_w, b.fc_partial, ns, fc_split); });
+    if (bf16) L.run(id0 + 3, [&] { return fc_fwd_bf16(L.s, n.arch, (const bf16_t*)b.act[n.n_conv - 1], b.fc_t, b.fc_partial, ns, fc_split); });
+    else L.run(id0 + 3, [&] { return fc_fwd(L.s, n.arch, (const float*)b.act[n.n_conv - 1], b.theta + a.fc_w, b.fc_partial, ns, fc_split); });
 }
 
 hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int* err_id) {
@@ -288,19 +316,30 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     la.returns = b.returns; la.dz = b.dz; la.dv = b.dv; la.loss_partials = b.loss_partials;
     L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
     // heads backward
-    L.run(K_TRN_HEADS_DH, [&] { return heads_dh(L.s, F, A, p.B, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, b.dh); });
+    const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
+    L.run(K_TRN_HEADS_DH, [&] {
+        return heads_dh(L.s, F, A, p.B, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, bf16 ? nullptr : (float*)b.dh,
+                        bf16 ? (bf16_t*)b.dh : nullptr);
+    });
     L.run(K_TRN_HEADS_WG, [&] { return heads_wgrad(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.h, b.hd_pw, b.hd_pb); });
     // fc backward
-    L.run(K_TRN_FC_WG, [&] { return fc_wgrad(L.s, n.arch, b.act[last], b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
-    L.run(K_TRN_FC_DG, [&] { return fc_dgrad(L.s, n.arch, b.dh, b.theta + a.fc_w, b.act[last], b.dact[last], p.B); });
+    if (bf16) {
+        L.run(K_TRN_FC_WG, [&] { return fc_wgrad_bf16(L.s, n.arch, (const bf16_t*)b.act[last], (const bf16_t*)b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
+        L.run(K_TRN_FC_DG, [&] { return fc_dgrad_bf16(L.s, n.arch, (const bf16_t*)b.dh, b.fc_c, (const bf16_t*)b.act[last], (bf16_t*)b.dact[last], p.B); });
+    } else {
+        L.run(K_TRN_FC_WG, [&] { return fc_wgrad(L.s, n.arch, (const float*)b.act[last], (const float*)b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
+        L.run(K_TRN_FC_DG, [&] { return fc_dgrad(L.s, n.arch, (const float*)b.dh, b.theta + a.fc_w, (const float*)b.act[last], (float*)b.dact[last], p.B); });
+    }
     // conv backward, last layer first
     for (int l = last; l >= 0; --l) {
         const void* in = l == 0 ? (const void*)x.states : (const void*)b.act[l - 1];
         const int wg_id = l == 2 ? K_TRN_CONV3_WG : l == 1 ? K_TRN_CONV2_WG : K_TRN_CONV1_WG;
-        L.run(wg_id, [&] { return conv_wgrad(L.s, n.arch, l, in, b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
+        if (bf16) L.run(wg_id, [&] { return conv_wgrad_bf16(L.s, n.arch, l, in, (const bf16_t*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
+        else L.run(wg_id, [&] { return conv_wgrad(L.s, n.arch, l, in, (const float*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
         if (l > 0) {
             const int dg_id = l == 2 ? K_TRN_CONV3_DG : K_TRN_CONV2_DG;
-            L.run(dg_id, [&] { return conv_dgrad(L.s, n.arch, l, b.dact[l], b.theta + a.conv_w[l], b.act[l - 1], b.dact[l - 1], p.B); });
+            if (bf16) L.run(dg_id, [&] { return conv_dgrad_bf16(L.s, n.arch, l, (const bf16_t*)b.dact[l], b.wd[l], (const bf16_t*)b.act[l - 1], (bf16_t*)b.dact[l - 1], p.B); });
+            else L.run(dg_id, [&] { return conv_dgrad(L.s, n.arch, l, (const float*)b.dact[l], b.theta + a.conv_w[l], (const float*)b.act[l - 1], (float*)b.dact[l - 1], p.B); });
         }
     }
     // reduce split gradients, global norm, clip + RMSProp
@@ -325,6 +364,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
         return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, b.hp, b.loss_partials, p.n_loss_blocks,
                               b.stats, reinterpret_cast<StatsOut*>(x.stats));
     });
+    if (bf16) L.run(K_TRN_BF16W, [&] { return make_bf16_weights(L.s, b.copies, b.theta); });
     *err_id = L.err_id;
     return L.err;
 }
@@ -401,8 +441,8 @@ int paac_workspace_bytes(const paac_config* cfg, size_t* bytes_out) {
     if (r) return r;
     const NetDesc n = make_net(cfg->arch, cfg->n_actions);
     const Arena a = make_arena(n);
-    const Plan p = make_plan(n, cfg->n_e, cfg->t_max);
-    *bytes_out = carve(n, a, p, nullptr).bytes;
+    const Plan p = make_plan(n, cfg->n_e, cfg->t_max, cfg->precision == PAAC_PREC_BF16);
+    *bytes_out = carve(n, a, p, cfg->precision == PAAC_PREC_BF16, nullptr).bytes;
     return PAAC_OK;
 }
 
@@ -418,8 +458,8 @@ int paac_create(const paac_config* cfg, void* workspace_dev, size_t workspace_by
     c->cfg = *cfg;
     c->net = make_net(cfg->arch, cfg->n_actions);
     c->arena = make_arena(c->net);
-    c->plan = make_plan(c->net, cfg->n_e, cfg->t_max);
-    c->buf = carve(c->net, c->arena, c->plan, static_cast<char*>(workspace_dev));
+    c->plan = make_plan(c->net, cfg->n_e, cfg->t_max, cfg->precision == PAAC_PREC_BF16);
+    c->buf = carve(c->net, c->arena, c->plan, cfg->precision == PAAC_PREC_BF16, static_cast<char*>(workspace_dev));
     if (c->buf.bytes > workspace_bytes) { delete c; return PAAC_E_WORKSPACE; }
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->have_params = false; c->use_graphs = true; c->profiling = false;
@@ -461,6 +501,7 @@ int paac_set_state(paac_ctx* c, const float* params_host, const float* rms_host)
     HIP_TRY(c, hipMemcpy(c->buf.theta, th.data(), a.p_int * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->buf.g2, g2.data(), a.p_int * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemset(c->buf.grads, 0, a.p_int * sizeof(float)));
+    if (c->cfg.precision == PAAC_PREC_BF16) HIP_TRY(c, make_bf16_weights(c->stream, c->buf.copies, c->buf.theta));
     HIP_TRY(c, hipDeviceSynchronize());
     c->have_params = true;
     return PAAC_OK;

@@ -53,6 +53,30 @@ int fc_wgrad_tiles(int arch);
 hipError_t fc_wgrad(hipStream_t s, int arch, const float* x, const float* dh, float* partial_w, float* partial_b,
                     int ns, Split sp);
 
+// ---- the same layers with bf16 operands (layers_bf16.hip): bf16 NHWC activations, bf16 weight copies
+// (forward copy Wt[c_out][K], data-gradient copy Wd[c_in][ky,kx][c_out]; fc: Wt[fc][flat], Wc[flat][fc]),
+// fp32 bias, fp32 partial sums and gradients ----
+typedef unsigned short bf16_t;
+hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* Wt, const float* b,
+                         bf16_t* out, int ns);
+hipError_t conv_dgrad_bf16(hipStream_t s, int arch, int layer, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in,
+                           bf16_t* dx, int ns);
+int conv_wgrad_tiles_bf16(int arch, int layer);
+hipError_t conv_wgrad_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* dy, float* partial_w,
+                           float* partial_b, int ns, Split sp);
+int fc_fwd_tiles_bf16(int arch, int ns);
+hipError_t fc_fwd_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* Wt, float* partial, int ns, Split sp);
+hipError_t fc_dgrad_bf16(hipStream_t s, int arch, const bf16_t* dh, const bf16_t* Wc, const bf16_t* act, bf16_t* dx, int ns);
+int fc_wgrad_tiles_bf16(int arch);
+hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* dh, float* partial_w, float* partial_b,
+                         int ns, Split sp);
+constexpr int kMaxCopies = 8;
+struct WeightCopies {            // see make_bf16_weights_kernel for the modes
+    int n, total;
+    bf16_t* dst[kMaxCopies]; int start[kMaxCopies], src_off[kMaxCopies], K[kMaxCopies], C[kMaxCopies], cin[kMaxCopies], mode[kMaxCopies];
+};
+hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);
+
 // ---- small kernels (small_kernels.hip) ----
 struct HeadsArgs {
     const float* fc_partial; int n_split; size_t split_stride;   // [split][rows][F]
@@ -78,8 +102,9 @@ struct LossArgs {
 int loss_blocks(int n_e);
 hipError_t returns_loss(hipStream_t s, const LossArgs& a);
 
+// dh is written as fp32 (dh) or, when dh_b is non-null, as bf16 (dh_b)
 hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
-                    const float* v_w, const float* h, float* dh);
+                    const float* v_w, const float* h, float* dh, bf16_t* dh_b);
 // partial_w[chunk][A+1][F] (row A = value head), partial_b[chunk][A+1]
 hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
                        const float* h, float* partial_w, float* partial_b);

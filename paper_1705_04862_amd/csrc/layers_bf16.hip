@@ -1,0 +1,178 @@
+// Dense layers of the PAAC network with bf16 operands (bf16 activations and weight copies, fp32
+// accumulation and fp32 gradients): the same six contractions as layers.hip on the bf16 GEMM core.
+#include "gemm_bf16.hip.h"
+#include "internal.h"
+
+namespace paac {
+
+typedef ConvGeom<4, 84, 84, 8, 4, 16> NipsC1;
+typedef ConvGeom<16, 20, 20, 4, 2, 32> NipsC2;
+typedef ConvGeom<4, 84, 84, 8, 4, 32> NatC1;
+typedef ConvGeom<32, 20, 20, 4, 2, 64> NatC2;
+typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
+
+// 128 rows, four waves along m; 32 or 64 columns (a 16-wide output uses the 32-wide tile)
+typedef TileB<128, 32, 64, 4, 1, 3> B128x32;
+typedef TileB<128, 64, 64, 4, 1, 3> B128x64;
+template <int N> struct TileBForN { typedef B128x64 type; };
+template <> struct TileBForN<16> { typedef B128x32 type; };
+template <> struct TileBForN<32> { typedef B128x32 type; };
+
+// ---------------------------------------------------------------------------------- forward
+template <class G, bool U8>
+static hipError_t conv_fwd_t(hipStream_t s, const void* in, const bf16_t* Wt, const float* b, bf16_t* out, int ns) {
+    typedef typename TileBForN<G::COUT>::type T;
+    const int M = ns * G::HO * G::WO;
+    DenseRowsK8 bl{Wt, G::COUT, G::KK};              // B(k, n = co) = Wt[co][k]
+    EpiBiasReluB ep{out, b, G::COUT, U8 ? 1.0f / 255.0f : 1.0f};     // bytes enter unscaled
+    if constexpr (U8) {
+        ConvU8RowsK8<G> al{(const uint8_t*)in, M};
+        return launch_gemm_bf16<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+    } else {
+        ConvNHWCRowsK8<G> al{(const bf16_t*)in, M};
+        return launch_gemm_bf16<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+    }
+}
+
+hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* Wt, const float* b,
+                         bf16_t* out, int ns) {
+    if (arch == 0) {
+        if (layer == 0) return conv_fwd_t<NipsC1, true>(s, in, Wt, b, out, ns);
+        if (layer == 1) return conv_fwd_t<NipsC2, false>(s, in, Wt, b, out, ns);
+    } else {
+        if (layer == 0) return conv_fwd_t<NatC1, true>(s, in, Wt, b, out, ns);
+        if (layer == 1) return conv_fwd_t<NatC2, false>(s, in, Wt, b, out, ns);
+        if (layer == 2) return conv_fwd_t<NatC3, false>(s, in, Wt, b, out, ns);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- data gradient
+template <class G>
+static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in, bf16_t* dx, int ns) {
+    typedef typename TileBForN<G::CIN>::type T;
+    const int M = ns * G::HC * G::WC;
+    DgradGatherRowsK8<G> al{dy, M};
+    DgradWeightRowsK8<G> bl{Wd};
+    EpiDgradMaskB<G> ep{dx, act_in};
+    return launch_gemm_bf16<T>(s, al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0);
+}
+
+hipError_t conv_dgrad_bf16(hipStream_t s, int arch, int layer, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in,
+                           bf16_t* dx, int ns) {
+    if (arch == 0 && layer == 1) return conv_dgrad_t<NipsC2>(s, dy, Wd, act_in, dx, ns);
+    if (arch == 1 && layer == 1) return conv_dgrad_t<NatC2>(s, dy, Wd, act_in, dx, ns);
+    if (arch == 1 && layer == 2) return conv_dgrad_t<NatC3>(s, dy, Wd, act_in, dx, ns);
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- weight gradient
+template <class G> static int wgrad_tiles_t() {
+    typedef typename TileBForN<G::COUT>::type T;
+    return ((G::KK + T::BM - 1) / T::BM) * ((G::COUT + T::BN - 1) / T::BN);
+}
+int conv_wgrad_tiles_bf16(int arch, int layer) {
+    if (arch == 0) return layer == 0 ? wgrad_tiles_t<NipsC1>() : wgrad_tiles_t<NipsC2>();
+    return layer == 0 ? wgrad_tiles_t<NatC1>() : layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
+}
+
+template <class G, bool U8>
+static hipError_t conv_wgrad_t(hipStream_t s, const void* in, const bf16_t* dy, float* pw, float* pb, int ns, Split sp) {
+    typedef typename TileBForN<G::COUT>::type T;
+    const int R = ns * G::HO * G::WO;
+    DenseKCols8 bl{dy, G::COUT, G::COUT};
+    EpiPartial<true> ep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
+    if constexpr (U8) {
+        ConvU8KCols8<G> al{(const uint8_t*)in, R};
+        EpiPartialScaled eps{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT, 1.0f / 255.0f};
+        return launch_gemm_bf16<T>(s, al, bl, eps, G::KK, G::COUT, R, sp.n, sp.k_per);
+    } else {
+        ConvNHWCKCols8<G> al{(const bf16_t*)in, R};
+        return launch_gemm_bf16<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
+    }
+}
+
+hipError_t conv_wgrad_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* dy, float* pw, float* pb,
+                           int ns, Split sp) {
+    if (arch == 0) {
+        if (layer == 0) return conv_wgrad_t<NipsC1, true>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NipsC2, false>(s, in, dy, pw, pb, ns, sp);
+    } else {
+        if (layer == 0) return conv_wgrad_t<NatC1, true>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NatC2, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 2) return conv_wgrad_t<NatC3, false>(s, in, dy, pw, pb, ns, sp);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------- fully connected
+static void fc_dims(int arch, int& flat, int& fc) {
+    if (arch == 0) { flat = 2592; fc = 256; } else { flat = 3136; fc = 512; }
+}
+
+int fc_fwd_tiles_bf16(int arch, int ns) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    return ((ns + 127) / 128) * (fc / 64);
+}
+
+// partial[split][ns][fc] (fp32) = x[ns][flat] . Wt[fc][flat]^T
+hipError_t fc_fwd_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* Wt, float* partial, int ns, Split sp) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseRowsK8 al{x, ns, flat};
+    DenseRowsK8 bl{Wt, fc, flat};
+    EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+}
+
+// dx[ns][flat] = (dh[ns][fc] . W[flat][fc]^T) * 1[act > 0]
+hipError_t fc_dgrad_bf16(hipStream_t s, int arch, const bf16_t* dh, const bf16_t* Wc, const bf16_t* act, bf16_t* dx, int ns) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseRowsK8 al{dh, ns, fc};
+    DenseRowsK8 bl{Wc, flat, fc};
+    EpiDenseMaskB ep{dx, act, flat};
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, flat, fc, 1, 0);
+}
+
+int fc_wgrad_tiles_bf16(int arch) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    return ((flat + 127) / 128) * (fc / 64);
+}
+
+hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* dh, float* pw, float* pb, int ns, Split sp) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseKCols8 al{x, flat, flat};
+    DenseKCols8 bl{dh, fc, fc};
+    EpiPartial<true> ep{pw, (size_t)flat * fc, fc, pb, fc};
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per);
+}
+
+// ---------------------------------------------------------------------------------- bf16 weight copies
+// One launch rewrites every bf16 copy from the fp32 master arena:
+//   mode 0: dst[c*K + k]              = src[k*C + c]           (forward: [c_out][K])
+//   mode 1: dst[i]                    = src[i]                 (fc data gradient: [flat][fc])
+//   mode 2: dst[(ci*T + t)*C + co]    = src[(t*CIN + ci)*C + co]   (conv data gradient: [ci][ky,kx][co])
+__global__ __launch_bounds__(256) void make_bf16_weights_kernel(const WeightCopies w, const float* theta) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= w.total) return;
+    int sidx = 0;
+    for (int q = 1; q < w.n; ++q) if (i >= w.start[q]) sidx = q;
+    const int o = i - w.start[sidx];
+    const int K = w.K[sidx], C = w.C[sidx];
+    const float* src = theta + w.src_off[sidx];
+    int si;
+    if (w.mode[sidx] == 0) { const int c = o / K, k = o % K; si = k * C + c; }
+    else if (w.mode[sidx] == 1) si = o;
+    else {
+        const int T = K / w.cin[sidx];                      // taps
+        const int co = o % C, t = (o / C) % T, ci = o / (C * T);
+        si = (t * w.cin[sidx] + ci) * C + co;
+    }
+    w.dst[sidx][o] = f2bf(src[si]);
+}
+
+hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta) {
+    launch_k(make_bf16_weights_kernel, dim3((w.total + 255) / 256), dim3(256), s, w, theta);
+    return hipGetLastError();
+}
+
+}  // namespace paac

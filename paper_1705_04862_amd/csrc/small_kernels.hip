@@ -216,7 +216,8 @@ hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
 // ------------------------------------------------------------------------------------ head backward
 // dh[row][j] = 1[h > 0] * (sum_a dz[row][a] pi_w[a][j] + dv[row] v_w[j])
 __global__ __launch_bounds__(256) void heads_dh_kernel(int F4, int A, int rows, const float* dz, const float* dv,
-                                                       const float* pi_w, const float* v_w, const float* h, float* dh) {
+                                                       const float* pi_w, const float* v_w, const float* h, float* dh,
+                                                       bf16_t* dh_b) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= rows * F4) return;
     const int row = idx / F4, j = (idx % F4) * 4, F = F4 * 4;
@@ -231,13 +232,18 @@ __global__ __launch_bounds__(256) void heads_dh_kernel(int F4, int A, int rows, 
     const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
     acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
     acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
-    *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+    if (dh_b) {
+        auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
+        *reinterpret_cast<uint2*>(dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
+    } else {
+        *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+    }
 }
 
 hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
-                    const float* v_w, const float* h, float* dh) {
+                    const float* v_w, const float* h, float* dh, bf16_t* dh_b) {
     const int n = rows * (F / 4);
-    launch_k(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh);
+    launch_k(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh, dh_b);
     return hipGetLastError();
 }
 
@@ -362,7 +368,7 @@ hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, con
                           const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b) {
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
+    if (blocks > 512) blocks = 512;       // grid-stride loop: fewer, longer-lived workgroups
     launch_k(rmsprop_update_kernel, dim3(blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
                        (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b);
     return hipGetLastError();

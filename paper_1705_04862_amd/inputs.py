@@ -29,6 +29,7 @@ class Net:
     conv: Tuple[Tuple[int, int, int], ...]   # (c_out, kernel, stride), valid padding
     fc: int
     n_actions: int
+    bf16: int = 0                  # 1: conv/fc weights and conv activations are stored in bf16
 
     def conv_out_shapes(self) -> List[Tuple[int, int, int]]:
         c, h, w = self.in_c, self.in_h, self.in_w

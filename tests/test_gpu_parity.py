@@ -336,3 +336,127 @@ def test_profiling_mode_matches_and_reports(paac):
         np.testing.assert_array_equal(x, y)
     assert "train.clip_rmsprop" in times and times["train.conv1_wgrad"]["calls"] == 1
     assert all(v["ms"] > 0 for v in times.values())
+
+
+# ------------------------------------------------------------------ bf16 MFMA path (precision = 1)
+# bf16 operands (8 significand bits) with fp32 accumulation: see check_train_bf16 for what is held to
+# 2e-2 and why the trunk gradients carry a wider bound.
+TOL_BF16 = 2e-2
+
+
+TOL_BF16_FLIP = 6e-2
+
+
+def check_train_bf16(oracle, net, ctx, params, rms, ro, hp, label=""):
+    """Two references.
+    (a) The plain fp64 oracle: logits, values, returns and losses within 2e-2.
+    (b) The oracle with the same bf16 STORAGE points (conv/fc weights as used, conv activations and the
+    layer-to-layer gradients rounded to bf16; sums in double): forward within 2e-3.
+    Gradients: a ReLU unit whose pre-activation is within accumulation error of zero can take a
+    different side in fp32 accumulation (the kernel) and in double (the oracle); each such flip moves a
+    whole per-sample term, and on this synthetic data (per-sample gradients uncorrelated) a handful of
+    flips per step is worth 2-4 % in relative L2 whatever the batch size.  So: tensors that no mask
+    touches (both heads) within 2e-2; every tensor within 6e-2 relative L2 and with its median
+    element error within 2e-2 of the tensor's largest magnitude."""
+    import dataclasses
+    ctx.set_state(params, rms)
+    ctx.train_step(dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones), hp)
+    torch.cuda.synchronize()
+    st = ctx.read_stats()
+    logits, values, returns = ctx.get_train_outputs()
+    p2, r2, g = ctx.get_state()
+    want = oracle.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    assert relmax(logits, want.logits) < TOL_BF16, label
+    assert relmax(values, want.values) < TOL_BF16, label
+    assert relmax(returns, want.returns) < TOL_BF16, label
+    scale = abs(want.stats["policy_loss"]) + hp.beta * abs(want.stats["entropy"]) + hp.value_coef * want.stats["value_loss"]
+    for k in ("policy_loss", "entropy", "value_loss"):
+        assert abs(st[k] - want.stats[k]) <= TOL_BF16 * max(abs(want.stats[k]), 0.05), (label, k, st[k], want.stats[k])
+    assert abs(st["total_loss"] - want.stats["total_loss"]) <= TOL_BF16 * max(scale, 0.05), label
+    assert st["nonfinite"] == 0
+    assert rel_l2(g, want.grads) < 0.2, (label, rel_l2(g, want.grads))
+    # (b) same storage precision on both sides
+    qnet = dataclasses.replace(net, bf16=1)
+    wq = oracle.train_step(qnet, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    assert relmax(logits, wq.logits) < 2e-3, label
+    assert relmax(values, wq.values) < 2e-3, label
+    for k in ("policy_loss", "entropy", "value_loss"):
+        assert abs(st[k] - wq.stats[k]) <= 2e-3 * max(abs(wq.stats[k]), 0.05), (label, k, st[k], wq.stats[k])
+    assert abs(st["grad_norm"] - wq.stats["grad_norm"]) <= TOL_BF16 * wq.stats["grad_norm"], label
+    assert rel_l2(g, wq.grads) < max(TOL_BF16_FLIP, 0.25 / np.sqrt(ro.actions.size)), (label, rel_l2(g, wq.grads))
+    for name, sl in net.param_slices().items():
+        ref = wq.grads[sl]
+        err = np.abs(g[sl].astype(np.float64) - ref)
+        # one flip weighs more in a tiny batch: 0.25/sqrt(B) per tensor below B = 17
+        tol = TOL_BF16 if name.startswith(("pi.", "v.")) else max(TOL_BF16_FLIP, 0.25 / np.sqrt(ro.actions.size))
+        assert np.linalg.norm(err) <= tol * max(np.linalg.norm(ref), 0.05 * np.linalg.norm(wq.grads)), (label, name)
+        assert np.median(err) <= TOL_BF16 * np.abs(ref).max(), (label, name)
+    assert rel_l2(p2 - params, wq.params.astype(np.float64) - params) < 2 * TOL_BF16_FLIP, label
+    assert rel_l2(r2, wq.rms.astype(np.float64)) < 2 * TOL_BF16_FLIP, label
+    # master weights stay fp32: the update is not rounded to bf16
+    assert np.abs(p2 - params).max() > 0 and rel_l2(p2, wq.params.astype(np.float64)) < 1e-3
+
+
+def check_select_bf16(oracle, net, params, states, uniforms, got):
+    acts, vals, probs = got
+    want = oracle.select_actions(net, params, states, uniforms)
+    assert relmax(vals, want["values"].astype(np.float64)) < TOL_BF16
+    assert relmax(probs, want["probs"].astype(np.float64)) < TOL_BF16
+    np.testing.assert_allclose(probs.sum(1), 1.0, atol=1e-5)
+    # the draw itself is exact given the kernel's own probabilities (same fp32 CDF rule)
+    for e in range(states.shape[0]):
+        cdf = np.cumsum(probs[e].astype(np.float32), dtype=np.float32)
+        k = int(np.searchsorted(cdf, uniforms[e], side="right"))
+        k = min(k, net.n_actions - 1)
+        if np.abs(cdf.astype(np.float64) - float(uniforms[e])).min() > 1e-5:
+            assert acts[e] == k
+        # and it agrees with the oracle's draw unless bf16 error can move u across a boundary
+        if acts[e] != want["actions"][e]:
+            ocdf = np.cumsum(want["probs"][e].astype(np.float64))
+            assert np.abs(ocdf - float(uniforms[e])).min() < TOL_BF16
+
+
+@pytest.mark.parametrize("net,n_e,t_max", [(I.nips_net(6), 4, 5), (I.nature_net(18), 3, 2), (I.nature_net(18), 37, 3)],
+                         ids=["nips_4x5", "nature_3x2", "nature_37x3"])
+def test_bf16_small_shapes(paac, oracle, net, n_e, t_max):
+    ctx = make_ctx(paac, net, n_e, t_max, precision=1)
+    params = I.make_params(41, net, bias_range=0.05)
+    rms = I.make_rms(41, net, hi=0.01)
+    ro = I.make_rollout(41, net, n_e, t_max, 0.1)
+    ctx.set_state(params, rms)
+    for t in range(t_max):
+        check_select_bf16(oracle, net, params, ro.states[t], ro.uniforms[t], run_select(ctx, net, ro.states[t], ro.uniforms[t]))
+    check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16")
+
+
+def test_bf16_config3_full_size(paac, oracle):
+    """Configuration 3 (n_e=256, t_max=5, Nature net) at full size against the whole oracle step."""
+    cfg = I.CONFIGS[3]
+    assert cfg.precision == 1
+    ctx = make_ctx(paac, cfg.net, cfg.n_e, cfg.t_max, precision=1)
+    params = I.config_params(cfg, bias_range=0.05)
+    rms = I.make_rms(1003, cfg.net, hi=0.01)
+    ro = I.config_rollout(cfg)
+    ctx.set_state(params, rms)
+    check_select_bf16(oracle, cfg.net, params, ro.states[0], ro.uniforms[0],
+                      run_select(ctx, cfg.net, ro.states[0], ro.uniforms[0]))
+    check_train_bf16(oracle, cfg.net, ctx, params, rms, ro, cfg.hp, cfg.name)
+
+
+def test_bf16_graph_replay_deterministic(paac):
+    cfg = I.CONFIGS[3]
+    net = cfg.net
+    ro = I.make_rollout(5, net, 16, 5, 0.02)
+    params = I.make_params(5, net)
+    d = [dev(x) for x in (ro.states, ro.actions, ro.rewards, ro.dones)]
+    res = []
+    for graphs in (False, True):
+        ctx = make_ctx(paac, net, 16, 5, precision=1)
+        ctx.set_graphs(graphs)
+        ctx.set_state(params)
+        for _ in range(3):
+            ctx.train_step(*d, cfg.hp)
+            torch.cuda.synchronize()
+        res.append(ctx.get_state())
+    for x, y in zip(res[0], res[1]):
+        np.testing.assert_array_equal(x, y)
