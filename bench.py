@@ -18,6 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -51,6 +52,7 @@ def kernel_work(net, n_e, t_max):
     w["train.returns_loss"] = ("byte", 4.0 * (Bp * (A + 1) + B * (A + 4)))
     w["train.grad_reduce_norm"] = ("byte", 8.0 * P)      # read one gradient copy, write the arena
     w["train.clip_rmsprop"] = ("byte", 20.0 * P)         # read theta, g, g2; write theta, g2
+    w["train.bf16_weight_copies"] = ("byte", 8.0 * P)    # read the fp32 weights, write two bf16 copies
     return w
 
 
@@ -159,10 +161,11 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
+    mfma_peak = PEAK_BF16_MFMA_TFLOPS if cfg.precision == 1 else PEAK_FP32_MFMA_TFLOPS
     if kind == "flop":
         ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e12
-        roof = dict(bound="mfma", kernel=dom, achieved=round(ach, 3), peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                    frac=round(ach / PEAK_FP32_MFMA_TFLOPS, 4), traffic=traffic,
+        roof = dict(bound="mfma", kernel=dom, achieved=round(ach, 3), peak=mfma_peak, unit="TFLOP/s",
+                    frac=round(ach / mfma_peak, 4), traffic=traffic,
                     avg_launch_us=per_kernel[dom]["avg_us"], algorithmic_flop_per_launch=amount)
     else:
         ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e9
@@ -177,12 +180,12 @@ def main():
         "value": round(value, 1), "unit": "env-timesteps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16" if cfg.precision == 1 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "net": net.name, "n_e": n_e, "t_max": T, "n_actions": net.n_actions,
                    "rollouts_rotated": len(R), "launch": "hip-graph replay (t_max select graphs + 1 train graph)"},
         "roofline": roof,
         "step_gflop": round(step_flop / 1e9, 3),
-        "pct_fp32_mfma_peak_whole_step": round(100 * step_flop / elapsed * args.steps / (PEAK_FP32_MFMA_TFLOPS * 1e12), 3),
+        "pct_mfma_peak_whole_step": round(100 * step_flop / elapsed * args.steps / (mfma_peak * 1e12), 3),
         "ms_select_x_tmax": round(ms_select, 4), "ms_train": round(ms_train, 4), "ms_per_step_eager": round(ms_eager, 4),
         "kernels": per_kernel,
         "paper_context": "derived from the paper's Table 1 training times and time split on a GTX 980 Ti: "
