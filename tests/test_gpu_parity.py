@@ -460,3 +460,62 @@ def test_bf16_graph_replay_deterministic(paac):
         res.append(ctx.get_state())
     for x, y in zip(res[0], res[1]):
         np.testing.assert_array_equal(x, y)
+
+
+def test_bf16_config4_full_size_sampled(paac, oracle):
+    """Configuration 4 (n_e=1024, t_max=20: 21504 forward rows, 20480 transitions) in the launch
+    configuration bench.py times.  The whole oracle step would take minutes, so: forward outputs and
+    returns are compared on sampled rows / environments the oracle computes one by one, and the
+    reduction, clip and update are checked through properties that hold at any size."""
+    import dataclasses
+    cfg = I.CONFIGS[4]
+    net, n_e, T = cfg.net, cfg.n_e, cfg.t_max
+    qnet = dataclasses.replace(net, bf16=1)
+    ctx = make_ctx(paac, net, n_e, T, precision=1)
+    params = I.config_params(cfg, bias_range=0.05)
+    rms = I.make_rms(1004, net, hi=0.01)
+    ro = I.config_rollout(cfg)
+    ctx.set_state(params, rms)
+    g = np.random.default_rng(4)
+    # select on one slab, 48 sampled environments
+    acts, vals, probs = run_select(ctx, net, ro.states[3], ro.uniforms[3])
+    es = np.sort(g.choice(n_e, 48, replace=False))
+    wq = oracle.select_actions(qnet, params, ro.states[3][es], ro.uniforms[3][es])
+    w0 = oracle.select_actions(net, params, ro.states[3][es], ro.uniforms[3][es])
+    assert relmax(vals[es], wq["values"].astype(np.float64)) < 2e-3 and relmax(probs[es], wq["probs"].astype(np.float64)) < 2e-3
+    assert relmax(vals[es], w0["values"].astype(np.float64)) < TOL_BF16 and relmax(probs[es], w0["probs"].astype(np.float64)) < TOL_BF16
+    check_select_bf16(oracle, net, params, ro.states[3][es], ro.uniforms[3][es], (acts[es], vals[es], probs[es]))
+    assert ((acts >= 0) & (acts < net.n_actions)).all()
+    # train step at full size
+    ctx.train_step(dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones), cfg.hp)
+    torch.cuda.synchronize()
+    st = ctx.read_stats()
+    logits, values, returns = ctx.get_train_outputs()
+    p2, r2, grads = ctx.get_state()
+    flat_states = ro.states.reshape(-1, 4, 84, 84)
+    rows = np.sort(g.choice((T + 1) * n_e, 64, replace=False))
+    lq, vq, _ = oracle.forward_f64(qnet, params.astype(np.float64), flat_states[rows])
+    l0, v0, _ = oracle.forward_f64(net, params.astype(np.float64), flat_states[rows])
+    assert relmax(logits[rows], lq) < 2e-3 and relmax(values[rows], vq) < 2e-3
+    assert relmax(logits[rows], l0) < TOL_BF16 and relmax(values[rows], v0) < TOL_BF16
+    # returns of 32 sampled environments: bootstrap and V from the oracle, scan by the oracle
+    envs = np.sort(g.choice(n_e, 32, replace=False))
+    _, vboot, _ = oracle.forward_f64(net, params.astype(np.float64), ro.states[T][envs])
+    R = oracle.returns_f64(ro.rewards[:, envs], ro.dones[:, envs], vboot, cfg.hp.gamma)
+    assert ro.dones[:, envs].any()
+    assert np.abs(returns[:, envs] - R).max() < TOL_BF16 * max(np.abs(R).max(), 1.0)
+    # properties of the reduction, the clip and the update at full size
+    assert st["nonfinite"] == 0 and np.isfinite(grads).all()
+    n = np.linalg.norm(grads.astype(np.float64))
+    assert abs(st["grad_norm"] - n) < 1e-4 * n
+    scale = min(1.0, cfg.hp.clip_norm / n)
+    assert abs(st["clip_scale"] - scale) < 1e-4
+    gc = grads.astype(np.float64) * scale
+    g2 = cfg.hp.rms_alpha * rms.astype(np.float64) + (1 - cfg.hp.rms_alpha) * gc * gc
+    th = params.astype(np.float64) - cfg.hp.lr * gc / np.sqrt(g2 + cfg.hp.rms_eps)
+    assert rel_l2(r2, g2) < 1e-5 and rel_l2(p2 - params, th - params) < 1e-4
+    assert abs(st["total_loss"] - (st["policy_loss"] - cfg.hp.beta * st["entropy"] + cfg.hp.value_coef * st["value_loss"])) < 1e-5
+    assert 0 < st["entropy"] <= np.log(net.n_actions) + 1e-5
+    # every tensor received a gradient
+    for name, sl in net.param_slices().items():
+        assert np.abs(grads[sl]).max() > 0, name

@@ -423,3 +423,48 @@ def test_init_params_glorot(oracle):
             assert np.abs(x).max() > 0.99 * lim
             assert abs(x.mean()) < 5 * lim / math.sqrt(3 * x.size)
             assert abs(x.var() - lim * lim / 3) < 0.05 * lim * lim / 3
+
+
+# ---------------------------------------------------------------- bf16 storage emulation
+def test_round_bf16_matches_library_and_known_values(oracle):
+    """Round-to-nearest-even to 8 significand bits: hand values and torch's CPU bfloat16 cast."""
+    assert oracle.round_bf16(1.0) == 1.0
+    assert oracle.round_bf16(1 + 2 ** -8) == 1.0                 # tie -> even
+    assert oracle.round_bf16(1 + 3 * 2 ** -8) == 1 + 2 ** -6     # tie -> even (up)
+    assert oracle.round_bf16(1 + 2 ** -8 + 2 ** -20) == 1 + 2 ** -7
+    assert oracle.round_bf16(-3.14159) == -3.140625
+    for b in range(256):                                          # every byte value is exact in bf16
+        assert oracle.round_bf16(float(b)) == float(b)
+    g = np.random.default_rng(7)
+    x = np.concatenate([g.normal(size=2000), g.normal(size=2000) * 1e-6, g.normal(size=2000) * 1e6]).astype(np.float32)
+    want = torch.tensor(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([oracle.round_bf16(float(v)) for v in x], np.float32)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_bf16_storage_mode_of_the_oracle(oracle):
+    """The storage-emulating mode rounds exactly the documented tensors: conv activations come out
+    on the bf16 grid, the fc output and the heads do not; its forward stays within bf16 error of
+    the plain oracle; and it equals a torch float64 forward with the same roundings."""
+    import dataclasses
+    net = I.nature_net(18)
+    qnet = dataclasses.replace(net, bf16=1)
+    params = I.make_params(12, net, bias_range=0.05).astype(np.float64)
+    st = I.make_states(12, 1, 2, net)[0]
+    lq, vq, aq = oracle.forward_f64(qnet, params, st, want_acts=True)
+    l0, v0, _ = oracle.forward_f64(net, params, st)
+    n_conv_act = 32 * 400 + 64 * 81 + 64 * 49
+    conv_acts = aq[:, :n_conv_act].astype(np.float32)
+    np.testing.assert_array_equal(conv_acts, torch.tensor(conv_acts).to(torch.bfloat16).to(torch.float32).numpy())
+    h = aq[:, n_conv_act:].astype(np.float32)
+    assert (h != torch.tensor(h).to(torch.bfloat16).to(torch.float32).numpy()).any()
+    assert 0 < np.abs(lq - l0).max() < 2e-2 * np.abs(l0).max()
+    # torch float64 with the same rounding points
+    q = lambda t: t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    P = {k: torch.tensor(v) for k, v in _split(net, params).items()}
+    x = torch.tensor(st.astype(np.float64)) / 255.0
+    for i, (co, k, s) in enumerate(net.conv):
+        x = q(F.relu(F.conv2d(x, q(P[f"conv{i + 1}.W"]), P[f"conv{i + 1}.b"], stride=s)))
+    hh = F.relu(F.linear(x.flatten(1), q(P["fc.W"]), P["fc.b"]))
+    lt = F.linear(hh, P["pi.W"], P["pi.b"]).numpy()
+    assert np.abs(lq - lt).max() < 2e-3 * np.abs(lt).max()        # same roundings up to ties met from either side
