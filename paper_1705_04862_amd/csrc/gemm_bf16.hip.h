@@ -8,12 +8,14 @@
 //   RowK (forward, data gradient): both operands are contiguous along k in memory; a tile is
 //        kept in LDS as [row][BK] and a lane reads its eight k with one 16-byte LDS load.
 //   KRow (weight gradient): the reduction runs over output positions, both operands are
-//        contiguous along m / n; a tile is kept as [k][cols] and a lane gathers its eight k with
-//        eight 2-byte LDS loads (a transposition done by addressing, no data movement).
+//        contiguous along m / n in memory; a thread loads 8 columns at 4 consecutive reduction
+//        indices, transposes the 8 x 4 block in registers (byte permutes) and stores it into the
+//        same [row][BK] LDS layout, so the MFMA side is identical in both modes.
 // Global loads are 16 bytes (8 bf16; 8 bytes for the uint8 first layer), branch free and clamped,
 // S register stages ahead; conversion and zeroing happen when the registers are stored to LDS.
 #pragma once
 #include "gemm_core.hip.h"
+#include <algorithm>
 
 namespace paac {
 
@@ -48,133 +50,186 @@ struct TileB {
 //   static constexpr bool kContig;      true: RowK operand (fixed = row, var = k, multiple of 8)
 //                                       false: KRow operand (fixed = first of 8 columns, var = k)
 //   typedef Raw; Raw load(fixed, var, pred, ok&);  static uint4 finish(Raw, ok)  -> 8 bf16
+//
+// LDS layout, both modes: tile[row][BK + 8] with the eight 16-byte chunks of a row permuted by
+// chunk ^ ((row / 8) % 8).  The permutation costs nothing on the MFMA side (a lane reads whole
+// chunks) and lets the transposing store of the KRow mode (four reduction indices of one row =
+// half a chunk per lane, lanes along the rows' groups of 8) hit every bank equally.
+//
+// Persistent workgroups: the grid's x extent may be smaller than the number of output tiles; a
+// workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the hardware starts only ~90
+// workgroups per microsecond, so one workgroup per 128-row tile of a large batch would be bound by
+// that rate).  The load pipeline is refilled per tile on purpose: global stores inside the k loop
+// would share the wave's memory counter with the prefetched loads, and every wait would then have
+// to drain the whole pipeline; the refill latency is covered by the other workgroups of the CU.
+// Epilogue flavours: the fp32 core's epilogues take (row, col); epilogues declared with kEntry take a
+// per-row entry (an element offset) computed by row_entry(row, z), optionally through the LDS table.
+template <class EP, class = void> struct EpiTraits { static constexpr bool kEntry = false, kRowTable = false; };
+template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
+    static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
+};
+
+template <int BK> __device__ __forceinline__ int swz(int row, int chunk) {
+    static_assert(BK == 64, "eight 16-byte chunks per row");
+    return chunk ^ ((row >> 3) & 7);
+}
+
 template <class T, class AL, class BL, class EP>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
-                                                        int k_per_split, int m_tiles) {
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
+                                                        int k_per_split, int m_tiles, int n_tiles) {
     static_assert(AL::kContig == BL::kContig, "both operands use the same staging mode");
     constexpr bool ROWK = AL::kContig;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, TM = T::TM, TN = T::TN, S = T::STAGES;
-    // leading dimensions in bf16 elements: 16 bytes of padding keep the 16-byte rows aligned and
-    // rotate the banks from row to row
-    constexpr int LDA = ROWK ? BK + 8 : BM + 8;
-    constexpr int LDB = ROWK ? BK + 8 : BN + 8;
-    constexpr int A_BUF = (ROWK ? BM : BK) * LDA, B_BUF = (ROWK ? BN : BK) * LDB;
-    constexpr int A_U = BM * BK / 8, B_U = BN * BK / 8;          // 16-byte units per tile
+    constexpr int LD = BK + 8;                                   // bf16 elements per LDS row
+    constexpr int A_BUF = BM * LD, B_BUF = BN * LD;
+    constexpr int NL = ROWK ? 1 : 4;                             // global loads per staging unit
+    // staging unit: RowK = one 16-byte chunk of one row; KRow = 8 rows x 4 reduction indices
+    constexpr int A_U = ROWK ? BM * BK / 8 : (BM / 8) * (BK / 4);
+    constexpr int B_U = ROWK ? BN * BK / 8 : (BN / 8) * (BK / 4);
     constexpr int A_IT = (A_U + 255) / 256, B_IT = (B_U + 255) / 256;
-    static_assert(A_IT + B_IT <= 16, "ok-bit mask");
+    static_assert((A_IT + B_IT) * NL <= 32, "ok-bit mask");
 
     __shared__ __attribute__((aligned(16))) bf16_t smem[2 * A_BUF + 2 * B_BUF];
+    // epilogues whose output address needs divisions per row (scatter of a parity class) get the BM
+    // row entries of a tile computed once, by BM threads, into a table (two copies: a wave may start
+    // the next tile while another still stores the previous one)
+    __shared__ int rowtab[EpiTraits<EP>::kRowTable ? 2 * BM : 1];
     bf16_t* const As = smem;
     bf16_t* const Bs = smem + 2 * A_BUF;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % T::WM, wn = wave / T::WM;
-    const int mt = blockIdx.x % m_tiles, nt = blockIdx.x / m_tiles;
     const int z = blockIdx.y;
-    const int m0 = mt * BM, n0 = nt * BN;
     const int k_begin = k_per_split > 0 ? z * k_per_split : 0;
     const int k_end = k_per_split > 0 ? min(K, k_begin + k_per_split) : K;
     const int nk = (k_end - k_begin + BK - 1) / BK;
+    const int tiles = m_tiles * n_tiles;
+    if (nk <= 0 || (int)blockIdx.x >= tiles) return;
+
+    // ---- staging units of this thread: tile-independent part
+    int a_var[A_IT], a_lds[A_IT], a_fix0[A_IT], b_var[B_IT], b_lds[B_IT], b_fix0[B_IT];
+    auto unit = [&](int f, int rows, bool rowfast, int& fix0, int& var, int& lds) __attribute__((always_inline)) {
+        if (ROWK) {
+            int c = rowfast ? f / rows : f % (BK / 8);
+            const int row = rowfast ? f % rows : f / (BK / 8);
+            // lanes along the rows: the 64 lanes of a wave share the chunk, so everything that depends
+            // on k (kernel tap, channel offset, range test) is computed once per wave on the scalar unit
+            if (rowfast && rows % 64 == 0) c = __builtin_amdgcn_readfirstlane(c);
+            fix0 = row; var = c * 8; lds = row * LD + swz<BK>(row, c) * 8;
+        } else {
+            const int cq = f % (rows / 8), kq = f / (rows / 8);      // lanes along the contiguous columns
+            fix0 = cq * 8; var = kq * 4; lds = cq * 8 * LD + swz<BK>(cq * 8, kq >> 1) * 8 + (kq & 1) * 4;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) unit(tid + i * 256, BM, row_fast<AL>(), a_fix0[i], a_var[i], a_lds[i]);
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) unit(tid + i * 256, BN, row_fast<BL>(), b_fix0[i], b_var[i], b_lds[i]);
 
     typename AL::Fixed afix[A_IT];
     typename BL::Fixed bfix[B_IT];
-    int a_var[A_IT], a_lds[A_IT], b_var[B_IT], b_lds[B_IT];
+    auto set_load_tile = [&](int tile) __attribute__((always_inline)) {
+        const int m0 = (tile % m_tiles) * BM, n0 = (tile / m_tiles) * BN;
 #pragma unroll
-    for (int i = 0; i < A_IT; ++i) {
-        const int f = tid + i * 256;
-        if (ROWK) {
-            const int kq = f % (BK / 8), row = f / (BK / 8);
-            afix[i] = al.prep(m0 + row, z); a_var[i] = kq * 8; a_lds[i] = row * LDA + kq * 8;
-        } else {
-            const int cq = f % (BM / 8), k = f / (BM / 8);
-            afix[i] = al.prep(m0 + cq * 8, z); a_var[i] = k; a_lds[i] = k * LDA + cq * 8;
-        }
-    }
+        for (int i = 0; i < A_IT; ++i) afix[i] = al.prep(m0 + a_fix0[i], z);
 #pragma unroll
-    for (int i = 0; i < B_IT; ++i) {
-        const int f = tid + i * 256;
-        if (ROWK) {
-            const int kq = f % (BK / 8), row = f / (BK / 8);
-            bfix[i] = bl.prep(n0 + row, z); b_var[i] = kq * 8; b_lds[i] = row * LDB + kq * 8;
-        } else {
-            const int cq = f % (BN / 8), k = f / (BN / 8);
-            bfix[i] = bl.prep(n0 + cq * 8, z); b_var[i] = k; b_lds[i] = k * LDB + cq * 8;
-        }
-    }
+        for (int i = 0; i < B_IT; ++i) bfix[i] = bl.prep(n0 + b_fix0[i], z);
+    };
 
-    typename AL::Raw areg[S][A_IT];
-    typename BL::Raw breg[S][B_IT];
+    typename AL::Raw areg[S][A_IT][NL];
+    typename BL::Raw breg[S][B_IT][NL];
     unsigned okbits[S];
-    auto gload = [&](int kt, auto stage) {
+    auto gload = [&](int kt, auto stage) __attribute__((always_inline)) {     // kt past the end: predicated off
         constexpr int G = decltype(stage)::value;
         const int kb = k_begin + kt * BK;
         unsigned bits = 0;
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
-            const int kk = kb + a_var[i];
-            bool ok;
-            areg[G][i] = al.load(afix[i], kk, (A_U % 256 == 0 || tid + i * 256 < A_U) && kk < k_end, ok);
-            bits |= ok ? (1u << i) : 0u;
-        }
+        for (int i = 0; i < A_IT; ++i)
 #pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
-            const int kk = kb + b_var[i];
-            bool ok;
-            breg[G][i] = bl.load(bfix[i], kk, (B_U % 256 == 0 || tid + i * 256 < B_U) && kk < k_end, ok);
-            bits |= ok ? (1u << (16 + i)) : 0u;
-        }
+            for (int q = 0; q < NL; ++q) {
+                const int kk = kb + a_var[i] + q;
+                bool ok;
+                areg[G][i][q] = al.load(afix[i], kk, (A_U % 256 == 0 || tid + i * 256 < A_U) && kk < k_end, ok);
+                bits |= ok ? (1u << (i * NL + q)) : 0u;
+            }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i)
+#pragma unroll
+            for (int q = 0; q < NL; ++q) {
+                const int kk = kb + b_var[i] + q;
+                bool ok;
+                breg[G][i][q] = bl.load(bfix[i], kk, (B_U % 256 == 0 || tid + i * 256 < B_U) && kk < k_end, ok);
+                bits |= ok ? (1u << ((A_IT + i) * NL + q)) : 0u;
+            }
         okbits[G] = bits;
     };
-    auto lstore = [&](auto stage, int buf) {
+    // registers of one unit -> LDS.  KRow: r[q] holds columns c..c+7 at reduction index k+q; column j
+    // gets the four values {r[0][j], r[1][j], r[2][j], r[3][j]} as one 8-byte store.
+    auto put = [&](bf16_t* dst, const uint4 (&r)[NL]) {
+        if constexpr (ROWK) {
+            *reinterpret_cast<uint4*>(dst) = r[0];
+        } else {
+            const unsigned w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
+                                      {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                uint2 o;
+                o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
+                o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
+                *reinterpret_cast<uint2*>(dst + j * LD) = o;
+            }
+        }
+    };
+    auto lstore = [&](auto stage, int buf) __attribute__((always_inline)) {
         constexpr int G = decltype(stage)::value;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i)
-            if (tid + i * 256 < A_U)
-                *reinterpret_cast<uint4*>(As + buf * A_BUF + a_lds[i]) = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
+            if (A_U % 256 == 0 || tid + i * 256 < A_U) {
+                uint4 r[NL];
+#pragma unroll
+                for (int q = 0; q < NL; ++q) r[q] = AL::finish(areg[G][i][q], (okbits[G] >> (i * NL + q)) & 1u);
+                put(As + buf * A_BUF + a_lds[i], r);
+            }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i)
-            if (tid + i * 256 < B_U)
-                *reinterpret_cast<uint4*>(Bs + buf * B_BUF + b_lds[i]) = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
+            if (B_U % 256 == 0 || tid + i * 256 < B_U) {
+                uint4 r[NL];
+#pragma unroll
+                for (int q = 0; q < NL; ++q) r[q] = BL::finish(breg[G][i][q], (okbits[G] >> ((A_IT + i) * NL + q)) & 1u);
+                put(Bs + buf * B_BUF + b_lds[i], r);
+            }
     };
 
     f32x16 acc[TM][TN];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+    zero_acc();
     float colsum = 0.f;
 
     const int fidx = lane & 31, kg = lane >> 5;
-    auto compute = [&](int buf) {
+    int c_tile = blockIdx.x, tile_par = 0;
+    auto compute = [&](int buf) __attribute__((always_inline)) {
         const bf16_t* as = As + buf * A_BUF;
         const bf16_t* bs = Bs + buf * B_BUF;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 a[TM], b[TN];
-            if constexpr (ROWK) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    a[i] = *reinterpret_cast<const bf16x8*>(as + (wm * TM * 32 + i * 32 + fidx) * LDA + ks * 16 + kg * 8);
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * TM * 32 + i * 32 + fidx;
+                a[i] = *reinterpret_cast<const bf16x8*>(as + row * LD + swz<BK>(row, ks * 2 + kg) * 8);
+            }
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    b[j] = *reinterpret_cast<const bf16x8*>(bs + (wn * TN * 32 + j * 32 + fidx) * LDB + ks * 16 + kg * 8);
-            } else {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    unsigned short t[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) t[q] = as[(ks * 16 + kg * 8 + q) * LDA + wm * TM * 32 + i * 32 + fidx];
-                    a[i] = __builtin_bit_cast(bf16x8, t);
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    unsigned short t[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) t[q] = bs[(ks * 16 + kg * 8 + q) * LDB + wn * TN * 32 + j * 32 + fidx];
-                    b[j] = __builtin_bit_cast(bf16x8, t);
-                }
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * TN * 32 + j * 32 + fidx;
+                b[j] = *reinterpret_cast<const bf16x8*>(bs + row * LD + swz<BK>(row, ks * 2 + kg) * 8);
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -182,14 +237,69 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const AL al, const BL bl
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
-        if constexpr (EP::kColSum) {          // KRow mode: Bs is [k][n], column sums of dY give the bias gradient
-            if (mt == 0 && tid < BN) {
-#pragma unroll 8
-                for (int k = 0; k < BK; ++k) colsum += bf2f(bs[k * LDB + tid]);
+        if constexpr (EP::kColSum) {          // bias gradient: sums of the B tile's rows (a row holds one column's k)
+            if (c_tile % m_tiles == 0 && tid < BN) {
+#pragma unroll
+                for (int c = 0; c < BK / 8; ++c) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(bs + tid * LD + c * 8);
+                    colsum += bf2f((bf16_t)(v.x & 0xffffu)) + bf2f((bf16_t)(v.x >> 16)) + bf2f((bf16_t)(v.y & 0xffffu)) +
+                              bf2f((bf16_t)(v.y >> 16)) + bf2f((bf16_t)(v.z & 0xffffu)) + bf2f((bf16_t)(v.z >> 16)) +
+                              bf2f((bf16_t)(v.w & 0xffffu)) + bf2f((bf16_t)(v.w >> 16));
+                }
             }
         }
     };
-    auto step = [&](int kt, auto stage) {
+    auto epilogue = [&]() __attribute__((always_inline)) {
+        const int mt = c_tile % m_tiles, nt = c_tile / m_tiles;
+        const int m0 = mt * BM, n0 = nt * BN;
+        if constexpr (EP::kColSum) {
+            if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
+            colsum = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
+                const bool full = m0 + BM <= M && n0 + BN <= N;     // interior tile (workgroup-uniform): no per-store test
+                if constexpr (EpiTraits<EP>::kEntry) {
+                    int ent[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int lr = wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                        if constexpr (EpiTraits<EP>::kRowTable) ent[r] = rowtab[tile_par * BM + lr];
+                        else ent[r] = ep.row_entry(m0 + lr < M ? m0 + lr : 0, z);
+                    }
+                    typename EP::Aux aux[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) aux[r] = ep.aux(ent[r], col < N ? col : 0);
+                    if (full) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) ep.store(ent[r], col, acc[i][j][r], aux[r]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                            if (row < M && col < N) ep.store(ent[r], col, acc[i][j][r], aux[r]);
+                        }
+                    }
+                } else {
+                    typename EP::Aux aux[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                        aux[r] = ep.aux(row, col, z, row < M && col < N);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                        if (full || (row < M && col < N)) ep.store(row, col, acc[i][j][r], z, aux[r]);
+                    }
+                }
+            }
+        zero_acc();
+    };
+    auto step = [&](int kt, auto stage) __attribute__((always_inline)) {
         constexpr int G = decltype(stage)::value;
         constexpr int GN = (G + 1) % S;
         gload(kt + S, stage);
@@ -197,65 +307,61 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const AL al, const BL bl
         if (kt + 1 < nk) lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);
         __syncthreads();
     };
-    gload(0, std::integral_constant<int, 0>());
-    gload(1, std::integral_constant<int, 1>());
-    if constexpr (S > 2) gload(2, std::integral_constant<int, 2>());
-    if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
-    lstore(std::integral_constant<int, 0>(), 0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += S) {
-        step(kt, std::integral_constant<int, 0>());
-        if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>());
-        if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
-        if constexpr (S > 3) { if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>()); }
-    }
-
-    if constexpr (EP::kColSum) {
-        if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
-            typename EP::Aux aux[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                aux[r] = ep.aux(row, col, z, row < M && col < N);
-            }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                if (row < M && col < N) ep.store(row, col, acc[i][j][r], z, aux[r]);
-            }
+    for (; c_tile < tiles; c_tile += gridDim.x, tile_par ^= 1) {
+        set_load_tile(c_tile);
+        if constexpr (EpiTraits<EP>::kRowTable) {
+            static_assert(BM <= 256, "one thread per row of the tile");
+            const int row = (c_tile % m_tiles) * BM + tid;
+            if (tid < BM) rowtab[tile_par * BM + tid] = ep.row_entry(row < M ? row : 0, z);
         }
+        gload(0, std::integral_constant<int, 0>());
+        gload(1, std::integral_constant<int, 1>());
+        if constexpr (S > 2) gload(2, std::integral_constant<int, 2>());
+        if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
+        lstore(std::integral_constant<int, 0>(), 0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; kt += S) {
+            step(kt, std::integral_constant<int, 0>());
+            if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>());
+            if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
+            if constexpr (S > 3) { if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>()); }
+        }
+        epilogue();          // the k loop ended with a barrier: the next tile may overwrite both LDS buffers
+    }
 }
 
 // ----------------------------------------------------------------------------------------------
 // RowK operands (contiguous along k)
+
+// Addresses are split into a per-row byte offset (divisions, once per tile: Fixed) and a per-k byte
+// offset; with lanes along the rows the latter is wave-uniform.  Out-of-range rows are clamped to row 0
+// in Fixed and out-of-range k to 0, so every load is in bounds without per-lane address selects.
+__device__ __forceinline__ const char* at(const void* base, int byte_off) {
+    return static_cast<const char*>(base) + (unsigned)byte_off;      // tensors are far below 4 GiB
+}
 
 // im2col rows of uint8 NCHW states, k = (c, ky, kx): one kernel row of 8 bytes per load; values are
 // the bytes themselves (not yet divided by 255).
 template <class G> struct ConvU8RowsK8 {
     static_assert(G::KS == 8, "one 8-byte load covers one kernel row");
     static constexpr bool kContig = true;
+    static constexpr bool kRowFast = true;      // lanes walk output positions (stride ST bytes), not kernel rows
     typedef uint2 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, u8x8_to_bf16(r)); }
     const uint8_t* x; int rows;
-    struct Fixed { const uint8_t* p; bool ok; };
+    struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
         Fixed f; f.ok = row < rows;
         row = f.ok ? row : 0;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        f.p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
+        f.off = n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
         return f;
     }
     __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
         ok = pred && f.ok;
-        k = ok ? k : 0;
+        k = pred ? k : 0;
         const int c = k / 64, ky = (k % 64) / 8;
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(f.p + c * (G::H * G::W) + ky * G::W);
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(at(x, f.off + c * (G::H * G::W) + ky * G::W));
         return make_uint2(p[0], p[1]);
     }
 };
@@ -263,23 +369,26 @@ template <class G> struct ConvU8RowsK8 {
 // im2col rows of a bf16 NHWC activation, k = (ky, kx, c), c in groups of 8.
 template <class G> struct ConvNHWCRowsK8 {
     static_assert(G::CIN % 8 == 0, "channels in groups of 8");
-    static constexpr bool kContig = true;
+    static_assert((G::KS * G::CIN) % 64 == 0 && G::KK % 64 == 0, "a 64-wide k tile stays inside one kernel row");
+    static constexpr bool kContig = true;      // lanes along k: eight lanes read 128 contiguous bytes
     typedef uint4 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
     const bf16_t* x; int rows;
-    struct Fixed { const bf16_t* p; bool ok; };
+    struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
         Fixed f; f.ok = row < rows;
         row = f.ok ? row : 0;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        f.p = x + ((size_t)(n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN;
+        f.off = (((n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN) * 2;
         return f;
     }
     __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
         ok = pred && f.ok;
-        k = ok ? k : 0;
-        const int ky = k / (G::KS * G::CIN), rem = k % (G::KS * G::CIN);
-        return *reinterpret_cast<const uint4*>(f.p + ky * (G::W * G::CIN) + rem);
+        // all lanes work on the same 64-wide k tile: its kernel row and offset are wave-uniform
+        int kb = __builtin_amdgcn_readfirstlane(k & ~63);
+        kb = kb < G::KK ? kb : 0;
+        const int ky = kb / (G::KS * G::CIN), rem = kb % (G::KS * G::CIN);
+        return *reinterpret_cast<const uint4*>(at(x, f.off + (ky * (G::W * G::CIN) + rem) * 2 + (k & 63) * 2));
     }
 };
 
@@ -298,29 +407,38 @@ struct DenseRowsK8 {            // element (row, k) = base[row*ld + k]
     }
 };
 
-// Data gradient, gather form (see DgradGatherRowsK): k = (ty, tx, co), co in groups of 8.
+// Data gradient, gather form (see DgradGatherRowsK): k = (ty, tx, co), co in groups of 8.  The row
+// part is the offset of dy[n][yy][xx][0] (a position that need not exist), the k part moves it back
+// by the tap; which taps fall inside the output map is a per-row bit mask.
 template <class G> struct DgradGatherRowsK8 {
     static constexpr bool kContig = true;
+    static constexpr bool kRowFast = true;
+    static_assert(G::TAPS * G::TAPS <= 31, "tap mask");
     typedef uint4 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
     const bf16_t* dy; int rows;
-    struct Fixed { const bf16_t* p; int yy, xx; bool ok; };
+    struct Fixed { int off; unsigned taps; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.ok = row < rows;
-        row = f.ok ? row : 0;
-        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC);
-        f.yy = r / G::WC; f.xx = r % G::WC;
-        f.p = dy + (size_t)n * (G::HO * G::WO * G::COUT);
+        Fixed f;
+        const bool rok = row < rows;
+        row = rok ? row : 0;
+        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
+        f.off = ((n * (G::HO * G::WO) + yy * G::WO + xx) * G::COUT) * 2;
+        unsigned m = 0;
+#pragma unroll
+        for (int t = 0; t < G::TAPS * G::TAPS; ++t) {
+            const int oy = yy - t / G::TAPS, ox = xx - t % G::TAPS;
+            m |= (oy >= 0 && oy < G::HO && ox >= 0 && ox < G::WO) ? (1u << t) : 0u;
+        }
+        f.taps = rok ? m : 0u;
         return f;
     }
     __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        ok = pred && f.ok;
-        k = ok ? k : 0;
+        k = pred ? k : 0;
         const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
-        int oy = f.yy - ty, ox = f.xx - tx;
-        ok = ok && oy >= 0 && oy < G::HO && ox >= 0 && ox < G::WO;
-        oy = ok ? oy : 0; ox = ok ? ox : 0;
-        return *reinterpret_cast<const uint4*>(f.p + (oy * G::WO + ox) * G::COUT + co);
+        ok = pred && ((f.taps >> tap) & 1u);
+        const int off = f.off + (co - (ty * G::WO + tx) * G::COUT) * 2;
+        return *reinterpret_cast<const uint4*>(at(dy, ok ? off : 0));
     }
 };
 
@@ -331,18 +449,22 @@ template <class G> struct DgradWeightRowsK8 {
     typedef uint4 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
     const bf16_t* w;
-    struct Fixed { const bf16_t* p; int py, px; bool ok; };
+    struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int ci, int z) const {
-        Fixed f; f.py = z / G::ST; f.px = z % G::ST; f.ok = ci < G::CIN;
-        f.p = w + (size_t)(f.ok ? ci : 0) * (G::KS * G::KS * G::COUT);
+        Fixed f; f.ok = ci < G::CIN;
+        const int py = z / G::ST, px = z % G::ST;
+        f.off = ((f.ok ? ci : 0) * (G::KS * G::KS) + py * G::KS + px) * G::COUT * 2;
         return f;
     }
     __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
         ok = pred && f.ok;
-        k = ok ? k : 0;
-        const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
-        const int ky = f.py + G::ST * ty, kx = f.px + G::ST * tx;
-        return *reinterpret_cast<const uint4*>(f.p + (ky * G::KS + kx) * G::COUT + co);
+        k = pred ? k : 0;
+        // a 64-wide k tile lies inside one tap when COUT is a multiple of 64: the tap is then the same
+        // for every lane of the wave
+        int tap = k / G::COUT;
+        if (G::COUT % 64 == 0) tap = __builtin_amdgcn_readfirstlane(tap);
+        const int co = k - tap * G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
+        return *reinterpret_cast<const uint4*>(at(w, f.off + ((G::ST * ty * G::KS + G::ST * tx) * G::COUT + co) * 2));
     }
 };
 
@@ -411,12 +533,13 @@ struct DenseKCols8 {            // element (k, col) = base[k*ld + col]
 // ----------------------------------------------------------------------------------------------
 // Epilogues with bf16 outputs (EpiPartial of the fp32 core is reused for fp32 partial sums)
 struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col], 0))
-    static constexpr bool kColSum = false;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false;
     typedef float Aux;
     bf16_t* out; const float* bias; int ldo; float scale;
-    __device__ __forceinline__ Aux aux(int, int col, int, bool ok) const { return bias[ok ? col : 0]; }
-    __device__ __forceinline__ void store(int row, int col, float v, int, Aux b) const {
-        out[(size_t)row * ldo + col] = f2bf(fmaxf(v * scale + b, 0.f));
+    __device__ __forceinline__ int row_entry(int row, int) const { return row * ldo; }
+    __device__ __forceinline__ Aux aux(int, int col) const { return bias[col]; }
+    __device__ __forceinline__ void store(int ent, int col, float v, Aux b) const {
+        out[(size_t)(unsigned)(ent + col)] = f2bf(fmaxf(v * scale + b, 0.f));
     }
 };
 
@@ -433,38 +556,53 @@ struct EpiPartialScaled {       // out[z][row][col] = scale * v, column sums of 
     }
 };
 
-template <class G> struct EpiDgradMaskB {
-    static constexpr bool kColSum = false;
+__device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) != 0 && !(a & 0x8000u); }
+
+template <class G> struct EpiDgradMaskB {      // scatter a parity class back to NHWC, times ReLU'
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = true;
     typedef bf16_t Aux;
     bf16_t* dx; const bf16_t* act;
-    __device__ __forceinline__ size_t addr(int row, int col, int z) const {
+    __device__ __forceinline__ int row_entry(int row, int z) const {
         const int py = z / G::ST, px = z % G::ST;
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
-        return ((size_t)(n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN + col;
+        return ((n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN;
     }
-    __device__ __forceinline__ Aux aux(int row, int col, int z, bool ok) const { return act[ok ? addr(row, col, z) : 0]; }
-    __device__ __forceinline__ void store(int row, int col, float v, int z, Aux a) const {
-        dx[addr(row, col, z)] = (a & 0x7fffu) != 0 && !(a & 0x8000u) ? f2bf(v) : (bf16_t)0;     // act > 0
+    __device__ __forceinline__ Aux aux(int ent, int col) const { return act[(size_t)(unsigned)(ent + col)]; }
+    __device__ __forceinline__ void store(int ent, int col, float v, Aux a) const {
+        dx[(size_t)(unsigned)(ent + col)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
     }
 };
 
 struct EpiDenseMaskB {
-    static constexpr bool kColSum = false;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false;
     typedef bf16_t Aux;
     bf16_t* out; const bf16_t* act; int ld;
-    __device__ __forceinline__ Aux aux(int row, int col, int, bool ok) const { return act[ok ? (size_t)row * ld + col : 0]; }
-    __device__ __forceinline__ void store(int row, int col, float v, int, Aux a) const {
-        out[(size_t)row * ld + col] = (a & 0x7fffu) != 0 && !(a & 0x8000u) ? f2bf(v) : (bf16_t)0;
+    __device__ __forceinline__ int row_entry(int row, int) const { return row * ld; }
+    __device__ __forceinline__ Aux aux(int ent, int col) const { return act[(size_t)(unsigned)(ent + col)]; }
+    __device__ __forceinline__ void store(int ent, int col, float v, Aux a) const {
+        out[(size_t)(unsigned)(ent + col)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
     }
 };
 
+// Grid: every k-split (grid y) gets min(tiles, resident workgroups of the whole chip) workgroups.
 template <class T, class AL, class BL, class EP>
 inline hipError_t launch_gemm_bf16(hipStream_t s, const AL& al, const BL& bl, const EP& ep, int M, int N, int K,
                                    int z_count, int k_per_split) {
     const int m_tiles = (M + T::BM - 1) / T::BM, n_tiles = (N + T::BN - 1) / T::BN;
     if (M <= 0 || N <= 0 || z_count <= 0) return hipErrorInvalidValue;
-    launch_k((gemm_bf16_kernel<T, AL, BL, EP>), dim3(m_tiles * n_tiles, z_count, 1), dim3(256), s, al, bl, ep, M, N, K,
-             k_per_split, m_tiles);
+    static int resident = 0;           // workgroups of this kernel the device holds at once
+    if (resident == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemm_bf16_kernel<T, AL, BL, EP>, 256, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        resident = per_cu * cus;
+    }
+    const int tiles = m_tiles * n_tiles;
+    // a grid up to a few times the resident set is started whole (its tail balances better than a
+    // second full round of a persistent grid); beyond that the grid is the resident set
+    const int gx = (tiles * z_count <= 4 * resident) ? tiles : std::max(1, resident / z_count);
+    launch_k((gemm_bf16_kernel<T, AL, BL, EP>), dim3(gx, z_count, 1), dim3(256), s, al, bl, ep, M, N, K,
+             k_per_split, m_tiles, n_tiles);
     return hipGetLastError();
 }
 

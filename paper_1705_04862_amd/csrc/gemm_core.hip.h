@@ -84,6 +84,10 @@ struct Tile {
 //           void store(int row, int col, float v, int z, Aux) const;
 //           void store_colsum(int col, float v, int z) const      (only if kColSum)
 
+template <class L, class = void> struct RowFast { static constexpr bool value = false; };
+template <class L> struct RowFast<L, std::enable_if_t<L::kRowFast>> { static constexpr bool value = true; };
+template <class L> __host__ __device__ constexpr bool row_fast() { return RowFast<L>::value; }
+
 template <class T, class AL, class BL, class EP>
 __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
                                                    int K, int k_per_split, int m_tiles) {
@@ -119,7 +123,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, con
     for (int i = 0; i < A_IT; ++i) {
         const int f = tid + i * 256;
         if (AL::kContig) {
-            const int kq = f % (BK / 4), row = f / (BK / 4);
+            // consecutive lanes take consecutive k of a row, or (kRowFast) consecutive rows at one k:
+            // whichever walks contiguous memory for this operand
+            const int kq = row_fast<AL>() ? f / BM : f % (BK / 4), row = row_fast<AL>() ? f % BM : f / (BK / 4);
             afix[i] = al.prep(m0 + row, z);
             a_var[i] = kq * 4;
             a_lds[i] = (kq * 4) * LDA + row;
