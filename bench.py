@@ -45,6 +45,9 @@ def kernel_work(net, n_e, t_max):
     w["train.fc_fwd"] = ("flop", fc * Bp)
     w["train.fc_wgrad"] = ("flop", fc * B)
     w["train.fc_dgrad"] = ("flop", fc * B)
+    w["train.fc_bwd"] = ("flop", 2 * fc * B)
+    for l in range(1, len(conv)):
+        w[f"train.conv{l + 1}_bwd"] = ("flop", 2 * conv[l] * B)
     w["select.heads_sample"] = ("flop", hd * n_e)
     w["train.heads_fwd"] = ("flop", hd * Bp)
     w["train.heads_dh"] = ("flop", hd * B)

@@ -162,14 +162,14 @@ enum KernelId {
     K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
     K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_DH, K_TRN_HEADS_WG,
     K_TRN_FC_WG, K_TRN_FC_DG, K_TRN_CONV3_WG, K_TRN_CONV3_DG, K_TRN_CONV2_WG, K_TRN_CONV2_DG, K_TRN_CONV1_WG,
-    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_COUNT
+    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_TRN_FC_BWD, K_TRN_CONV3_BWD, K_TRN_CONV2_BWD, K_COUNT
 };
 const char* const kKernelNames[K_COUNT] = {
     "select.conv1_fwd", "select.conv2_fwd", "select.conv3_fwd", "select.fc_fwd", "select.heads_sample",
     "train.conv1_fwd", "train.conv2_fwd", "train.conv3_fwd", "train.fc_fwd", "train.heads_fwd", "train.returns_loss",
     "train.heads_dh", "train.heads_wgrad", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
     "train.conv3_dgrad", "train.conv2_wgrad", "train.conv2_dgrad", "train.conv1_wgrad", "train.grad_reduce_norm",
-    "train.clip_rmsprop", "train.bf16_weight_copies"};
+    "train.clip_rmsprop", "train.bf16_weight_copies", "train.fc_bwd", "train.conv3_bwd", "train.conv2_bwd"};
 
 struct GraphKey {
     int kind;                 // 0 select, 1 train
@@ -327,13 +327,22 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
         L.run(K_TRN_FC_WG, [&] { return fc_wgrad_bf16(L.s, n.arch, (const bf16_t*)b.act[last], (const bf16_t*)b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
         L.run(K_TRN_FC_DG, [&] { return fc_dgrad_bf16(L.s, n.arch, (const bf16_t*)b.dh, b.fc_c, (const bf16_t*)b.act[last], (bf16_t*)b.dact[last], p.B); });
     } else {
-        L.run(K_TRN_FC_WG, [&] { return fc_wgrad(L.s, n.arch, (const float*)b.act[last], (const float*)b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
-        L.run(K_TRN_FC_DG, [&] { return fc_dgrad(L.s, n.arch, (const float*)b.dh, b.theta + a.fc_w, (const float*)b.act[last], (float*)b.dact[last], p.B); });
+        L.run(K_TRN_FC_BWD, [&] {
+            return fc_bwd(L.s, n.arch, (const float*)b.act[last], (const float*)b.dh, b.theta + a.fc_w, (float*)b.dact[last],
+                          b.fc_pw, b.fc_pb, p.B, p.fc_wg);
+        });
     }
     // conv backward, last layer first
     for (int l = last; l >= 0; --l) {
         const void* in = l == 0 ? (const void*)x.states : (const void*)b.act[l - 1];
         const int wg_id = l == 2 ? K_TRN_CONV3_WG : l == 1 ? K_TRN_CONV2_WG : K_TRN_CONV1_WG;
+        if (!bf16 && l > 0) {       // fp32: data and weight gradient of the layer share one launch
+            L.run(l == 2 ? K_TRN_CONV3_BWD : K_TRN_CONV2_BWD, [&] {
+                return conv_bwd(L.s, n.arch, l, (const float*)b.act[l - 1], (const float*)b.dact[l], b.theta + a.conv_w[l],
+                                (float*)b.dact[l - 1], b.pw[l], b.pb[l], p.B, p.wg[l]);
+            });
+            continue;
+        }
         if (bf16) L.run(wg_id, [&] { return conv_wgrad_bf16(L.s, n.arch, l, in, (const bf16_t*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
         else L.run(wg_id, [&] { return conv_wgrad(L.s, n.arch, l, in, (const float*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
         if (l > 0) {

@@ -88,9 +88,15 @@ template <class L, class = void> struct RowFast { static constexpr bool value = 
 template <class L> struct RowFast<L, std::enable_if_t<L::kRowFast>> { static constexpr bool value = true; };
 template <class L> __host__ __device__ constexpr bool row_fast() { return RowFast<L>::value; }
 
+// LDS floats of one workgroup: two buffers per operand
+template <class T, class AL, class BL> constexpr int gemm_smem_floats() {
+    return 2 * T::BK * (AL::kContig ? T::BM + 1 : T::BM + 4) + 2 * T::BK * (BL::kContig ? T::BN + 1 : T::BN + 4);
+}
+
+// One workgroup's share of a GEMM: output tile `tile_idx` (m tiles fastest), k-split `z`.
 template <class T, class AL, class BL, class EP>
-__global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
-                                                   int K, int k_per_split, int m_tiles) {
+__device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int k_per_split,
+                                          int m_tiles, int tile_idx, int z, float* smem) {
     typedef Mma<T::MF> MM;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MF = T::MF, TM = T::TM, TN = T::TN;
     // leading dimensions: odd-ish for transposed scalar stores, multiple of 4 for 16-byte stores
@@ -100,14 +106,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, con
     constexpr int A_IT = (A_F4 + 255) / 256, B_IT = (B_F4 + 255) / 256;
 
     constexpr int A_BUF = BK * LDA, B_BUF = BK * LDB;      // floats per LDS buffer (multiples of 4)
-    __shared__ __attribute__((aligned(16))) float smem[2 * A_BUF + 2 * B_BUF];
+    static_assert(2 * A_BUF + 2 * B_BUF == gemm_smem_floats<T, AL, BL>(), "LDS size");
     float* const As = smem;                 // As[buf] = As + buf * A_BUF
     float* const Bs = smem + 2 * A_BUF;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % T::WM, wn = (wave / T::WM) % T::WN, wk = wave / (T::WM * T::WN);
-    const int mt = blockIdx.x % m_tiles, nt = blockIdx.x / m_tiles;
-    const int z = blockIdx.y;
+    const int mt = tile_idx % m_tiles, nt = tile_idx / m_tiles;
     const int m0 = mt * BM, n0 = nt * BN;
     const int k_begin = k_per_split > 0 ? z * k_per_split : 0;
     const int k_end = k_per_split > 0 ? min(K, k_begin + k_per_split) : K;
@@ -590,6 +595,54 @@ struct EpiDenseMask {           // out[row][col] = act[row][col] > 0 ? v : 0
 };
 
 // ----------------------------------------------------------------------------------------------
+template <class T, class AL, class BL, class EP>
+__global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
+                                                   int K, int k_per_split, int m_tiles) {
+    __shared__ __attribute__((aligned(16))) float smem[gemm_smem_floats<T, AL, BL>()];
+    gemm_body<T, AL, BL, EP>(al, bl, ep, M, N, K, k_per_split, m_tiles, blockIdx.x, blockIdx.y, smem);
+}
+
+// A GEMM with its launch shape, as a value: lets two independent GEMMs share one launch.
+template <class T_, class AL_, class BL_, class EP_> struct GemmCall {
+    typedef T_ T; typedef AL_ AL; typedef BL_ BL; typedef EP_ EP;
+    AL al; BL bl; EP ep;
+    int M, N, K, z_count, k_per_split;
+    __host__ __device__ int m_tiles() const { return (M + T::BM - 1) / T::BM; }
+    __host__ __device__ int tiles() const { return m_tiles() * ((N + T::BN - 1) / T::BN); }
+    __host__ __device__ int blocks() const { return tiles() * z_count; }
+};
+template <class T, class AL, class BL, class EP>
+inline GemmCall<T, AL, BL, EP> make_call(const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int z, int k_per) {
+    return GemmCall<T, AL, BL, EP>{al, bl, ep, M, N, K, z, k_per};
+}
+
+// Two independent GEMMs in one grid: workgroups [0, a.blocks()) run `a`, the rest run `b`.  At small
+// batch each GEMM alone leaves most compute units idle and is bound by its own start-up and drain
+// latencies; side by side they overlap them.
+template <class C1, class C2>
+__global__ __launch_bounds__(256) void gemm_pair_kernel(const C1 a, const C2 b) {
+    constexpr int S1 = gemm_smem_floats<typename C1::T, typename C1::AL, typename C1::BL>();
+    constexpr int S2 = gemm_smem_floats<typename C2::T, typename C2::AL, typename C2::BL>();
+    __shared__ __attribute__((aligned(16))) float smem[S1 > S2 ? S1 : S2];
+    const int n1 = a.blocks();
+    if ((int)blockIdx.x < n1) {
+        const int t = a.tiles();
+        gemm_body<typename C1::T, typename C1::AL, typename C1::BL, typename C1::EP>(
+            a.al, a.bl, a.ep, a.M, a.N, a.K, a.k_per_split, a.m_tiles(), blockIdx.x % t, blockIdx.x / t, smem);
+    } else {
+        const int r = blockIdx.x - n1, t = b.tiles();
+        gemm_body<typename C2::T, typename C2::AL, typename C2::BL, typename C2::EP>(
+            b.al, b.bl, b.ep, b.M, b.N, b.K, b.k_per_split, b.m_tiles(), r % t, r / t, smem);
+    }
+}
+
+template <class C1, class C2>
+inline hipError_t launch_pair(hipStream_t s, const C1& a, const C2& b) {
+    if (a.blocks() <= 0 || b.blocks() <= 0) return hipErrorInvalidValue;
+    launch_k((gemm_pair_kernel<C1, C2>), dim3(a.blocks() + b.blocks(), 1, 1), dim3(256), s, a, b);
+    return hipGetLastError();
+}
+
 template <class T, class AL, class BL, class EP>
 inline hipError_t launch_gemm(hipStream_t s, const AL& al, const BL& bl, const EP& ep, int M, int N, int K,
                               int z_count, int k_per_split) {

@@ -52,6 +52,11 @@ hipError_t fc_dgrad(hipStream_t s, int arch, const float* dh, const float* W, co
 int fc_wgrad_tiles(int arch);
 hipError_t fc_wgrad(hipStream_t s, int arch, const float* x, const float* dh, float* partial_w, float* partial_b,
                     int ns, Split sp);
+// fused data + weight gradient of one layer (one launch)
+hipError_t conv_bwd(hipStream_t s, int arch, int layer, const float* act_in, const float* dy, const float* W, float* dx,
+                    float* pw, float* pb, int ns, Split sp);
+hipError_t fc_bwd(hipStream_t s, int arch, const float* x, const float* dh, const float* W, float* dx, float* pw, float* pb,
+                  int ns, Split sp);
 
 // ---- the same layers with bf16 operands (layers_bf16.hip): bf16 NHWC activations, bf16 weight copies
 // (forward copy Wt[c_out][K], data-gradient copy Wd[c_in][ky,kx][c_out]; fc: Wt[fc][flat], Wc[flat][fc]),

@@ -167,6 +167,43 @@ hipError_t conv_wgrad(hipStream_t s, int arch, int layer, const void* in, const 
     return hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------------- fused backward of one layer
+// The data gradient and the weight gradient of a layer both start from dY and are independent of
+// each other: one launch runs both (the chain conv3 -> conv2 of data gradients is the critical path
+// of the backward pass, the weight gradients ride along).
+template <class TD, class G, class CW>
+static hipError_t conv_bwd_pair(hipStream_t s, const float* dy, const float* W, const float* act_in, float* dx, int ns,
+                                const CW& wcall) {
+    const int M = ns * G::HC * G::WC;
+    DgradGatherRowsK<G> al{dy, M};
+    DgradWeightColsK<G> bl{W};
+    EpiDgradMask<G> ep{dx, act_in};
+    return launch_pair(s, make_call<TD>(al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0), wcall);
+}
+
+template <class G>
+static hipError_t conv_bwd_t(hipStream_t s, const float* act_in, const float* dy, const float* W, float* dx, float* pw,
+                             float* pb, int ns, Split sp) {
+    typedef TileForN<G::CIN> TS;
+    const int R = ns * G::HO * G::WO, M = ns * G::HC * G::WC, z = G::ST * G::ST;
+    ConvNHWCKCols<G> wal{act_in, R};
+    DenseKCols wbl{dy, G::COUT, G::COUT};
+    EpiPartial<true> wep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
+    const auto wcall = make_call<typename TileForN<G::COUT>::wg>(wal, wbl, wep, G::KK, G::COUT, R, sp.n, sp.k_per);
+    auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((G::CIN + bn - 1) / bn) * z; };
+    if (wgs(TS::big::BM, TS::big::BN) >= 192) return conv_bwd_pair<typename TS::big, G>(s, dy, W, act_in, dx, ns, wcall);
+    if (wgs(TS::mid::BM, TS::mid::BN) >= 192) return conv_bwd_pair<typename TS::mid, G>(s, dy, W, act_in, dx, ns, wcall);
+    return conv_bwd_pair<typename TS::small, G>(s, dy, W, act_in, dx, ns, wcall);
+}
+
+hipError_t conv_bwd(hipStream_t s, int arch, int layer, const float* act_in, const float* dy, const float* W, float* dx,
+                    float* pw, float* pb, int ns, Split sp) {
+    if (arch == 0 && layer == 1) return conv_bwd_t<NipsC2>(s, act_in, dy, W, dx, pw, pb, ns, sp);
+    if (arch == 1 && layer == 1) return conv_bwd_t<NatC2>(s, act_in, dy, W, dx, pw, pb, ns, sp);
+    if (arch == 1 && layer == 2) return conv_bwd_t<NatC3>(s, act_in, dy, W, dx, pw, pb, ns, sp);
+    return hipErrorInvalidValue;
+}
+
 // ---------------------------------------------------------------------------------- fully connected
 static void fc_dims(int arch, int& flat, int& fc) {
     if (arch == 0) { flat = 2592; fc = 256; } else { flat = 3136; fc = 512; }
@@ -207,6 +244,21 @@ hipError_t fc_wgrad(hipStream_t s, int arch, const float* x, const float* dh, fl
     DenseKCols bl{dh, fc, fc};
     EpiPartial<true> ep{pw, (size_t)flat * fc, fc, pb, fc};
     return launch_gemm<T64x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per);
+}
+
+// data gradient and weight gradient of the fully connected layer in one launch
+hipError_t fc_bwd(hipStream_t s, int arch, const float* x, const float* dh, const float* W, float* dx, float* pw, float* pb,
+                  int ns, Split sp) {
+    int flat, fc; fc_dims(arch, flat, fc);
+    DenseKCols wal{x, flat, flat};
+    DenseKCols wbl{dh, fc, fc};
+    EpiPartial<true> wep{pw, (size_t)flat * fc, fc, pb, fc};
+    const auto wcall = make_call<T64x64>(wal, wbl, wep, flat, fc, ns, sp.n, sp.k_per);
+    DenseRowsK al{dh, ns, fc};
+    DenseRowsK bl{W, flat, fc};
+    EpiDenseMask ep{dx, x, flat};
+    if ((long)((ns + 63) / 64) * (flat / 64) >= 192) return launch_pair(s, make_call<T64x64>(al, bl, ep, ns, flat, fc, 1, 0), wcall);
+    return launch_pair(s, make_call<T32x64>(al, bl, ep, ns, flat, fc, 1, 0), wcall);
 }
 
 }  // namespace paac
