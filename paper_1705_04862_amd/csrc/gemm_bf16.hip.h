@@ -30,11 +30,18 @@ __device__ __forceinline__ uint4 keep_if_u4(bool ok, uint4 v) {
 }
 // eight bytes -> eight bf16 holding the byte values 0..255 exactly (8 significand bits suffice);
 // the 1/255 of the input scaling is applied to the fp32 accumulators in the epilogue instead, so the
-// first layer's input carries no rounding error at all
+// first layer's input carries no rounding error at all.  An integer below 256 has zero low fp32
+// mantissa bits: its bf16 is the upper half of the fp32, so two conversions pack with one byte permute.
+__device__ __forceinline__ unsigned u8pair_to_bf16(float lo, float hi) {
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
 __device__ __forceinline__ uint4 u8x8_to_bf16(uint2 w) {
     auto cv = [&](unsigned x, int sh) { return (float)((x >> sh) & 255u); };
-    return make_uint4(pack2(cv(w.x, 0), cv(w.x, 8)), pack2(cv(w.x, 16), cv(w.x, 24)),
-                      pack2(cv(w.y, 0), cv(w.y, 8)), pack2(cv(w.y, 16), cv(w.y, 24)));
+    return make_uint4(u8pair_to_bf16(cv(w.x, 0), cv(w.x, 8)), u8pair_to_bf16(cv(w.x, 16), cv(w.x, 24)),
+                      u8pair_to_bf16(cv(w.y, 0), cv(w.y, 8)), u8pair_to_bf16(cv(w.y, 16), cv(w.y, 24)));
+}
+__device__ __forceinline__ uint4 u8x8_to_bf16_if(bool ok, uint2 w) {      // zeroing on the two raw words
+    return u8x8_to_bf16(make_uint2(ok ? w.x : 0u, ok ? w.y : 0u));
 }
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_ = 3>
@@ -51,10 +58,12 @@ struct TileB {
 //                                       false: KRow operand (fixed = first of 8 columns, var = k)
 //   typedef Raw; Raw load(fixed, var, pred, ok&);  static uint4 finish(Raw, ok)  -> 8 bf16
 //
-// LDS layout, both modes: tile[row][BK + 8] with the eight 16-byte chunks of a row permuted by
-// chunk ^ ((row / 8) % 8).  The permutation costs nothing on the MFMA side (a lane reads whole
-// chunks) and lets the transposing store of the KRow mode (four reduction indices of one row =
-// half a chunk per lane, lanes along the rows' groups of 8) hit every bank equally.
+// LDS layout, both modes: tile[row][BK + 8].  The 16 bytes of padding per row make 16 consecutive
+// rows start in 16 different groups of four banks (row pitch 36 words, 64 banks): the 16-byte reads
+// of the MFMA side (lanes along rows) are conflict free, as measured with SQ_LDS_BANK_CONFLICT; an
+// XOR permutation of the chunks on top of the padding was measured to cause conflicts (45-55% of the
+// LDS cycles) and is not used.  The transposing store of the KRow mode (8-byte stores, lanes along
+// k) touches 2 words x 16 lanes x 2 row groups = all 64 banks once.
 //
 // Persistent workgroups: the grid's x extent may be smaller than the number of output tiles; a
 // workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the hardware starts only ~90
@@ -68,11 +77,6 @@ template <class EP, class = void> struct EpiTraits { static constexpr bool kEntr
 template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
     static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
 };
-
-template <int BK> __device__ __forceinline__ int swz(int row, int chunk) {
-    static_assert(BK == 64, "eight 16-byte chunks per row");
-    return chunk ^ ((row >> 3) & 7);
-}
 
 template <class T, class AL, class BL, class EP>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
@@ -115,10 +119,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             // lanes along the rows: the 64 lanes of a wave share the chunk, so everything that depends
             // on k (kernel tap, channel offset, range test) is computed once per wave on the scalar unit
             if (rowfast && rows % 64 == 0) c = __builtin_amdgcn_readfirstlane(c);
-            fix0 = row; var = c * 8; lds = row * LD + swz<BK>(row, c) * 8;
+            fix0 = row; var = c * 8; lds = row * LD + c * 8;
         } else {
-            const int cq = f % (rows / 8), kq = f / (rows / 8);      // lanes along the contiguous columns
-            fix0 = cq * 8; var = kq * 4; lds = cq * 8 * LD + swz<BK>(cq * 8, kq >> 1) * 8 + (kq & 1) * 4;
+            const int kq = f % (BK / 4), cq = f / (BK / 4);          // lanes along k: conflict-free 8-byte LDS stores
+            fix0 = cq * 8; var = kq * 4; lds = cq * 8 * LD + kq * 4;
         }
     };
 #pragma unroll
@@ -224,12 +228,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * TM * 32 + i * 32 + fidx;
-                a[i] = *reinterpret_cast<const bf16x8*>(as + row * LD + swz<BK>(row, ks * 2 + kg) * 8);
+                a[i] = *reinterpret_cast<const bf16x8*>(as + row * LD + ks * 16 + kg * 8);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = wn * TN * 32 + j * 32 + fidx;
-                b[j] = *reinterpret_cast<const bf16x8*>(bs + row * LD + swz<BK>(row, ks * 2 + kg) * 8);
+                b[j] = *reinterpret_cast<const bf16x8*>(bs + row * LD + ks * 16 + kg * 8);
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         constexpr int GN = (G + 1) % S;
         gload(kt + S, stage);
         compute(kt & 1);
-        if (kt + 1 < nk) lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);
+        lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last k tile: zeros nobody reads
         __syncthreads();
     };
     for (; c_tile < tiles; c_tile += gridDim.x, tile_par ^= 1) {
@@ -320,11 +324,20 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
         lstore(std::integral_constant<int, 0>(), 0);
         __syncthreads();
-        for (int kt = 0; kt < nk; kt += S) {
+        // whole rounds of S steps without a branch, the remainder after the loop (see gemm_body)
+        int kt = 0;
+        for (int q = nk / S; q > 0; --q, kt += S) {
             step(kt, std::integral_constant<int, 0>());
-            if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>());
-            if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
-            if constexpr (S > 3) { if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>()); }
+            step(kt + 1, std::integral_constant<int, 1>());
+            if constexpr (S > 2) step(kt + 2, std::integral_constant<int, 2>());
+            if constexpr (S > 3) step(kt + 3, std::integral_constant<int, 3>());
+        }
+        if (kt < nk) {
+            step(kt, std::integral_constant<int, 0>());
+            if (kt + 1 < nk) {
+                step(kt + 1, std::integral_constant<int, 1>());
+                if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
+            }
         }
         epilogue();          // the k loop ended with a barrier: the next tile may overwrite both LDS buffers
     }
@@ -347,7 +360,7 @@ template <class G> struct ConvU8RowsK8 {
     static constexpr bool kContig = true;
     static constexpr bool kRowFast = true;      // lanes walk output positions (stride ST bytes), not kernel rows
     typedef uint2 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, u8x8_to_bf16(r)); }
+    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return u8x8_to_bf16_if(ok, r); }
     const uint8_t* x; int rows;
     struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int row, int) const {
@@ -475,7 +488,7 @@ template <class G> struct ConvU8KCols8 {       // A(m = (c,ky,kx), k = output po
     static_assert(G::KS == 8, "one 8-byte load covers one kernel row");
     static constexpr bool kContig = false;
     typedef uint2 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, u8x8_to_bf16(r)); }
+    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return u8x8_to_bf16_if(ok, r); }
     const uint8_t* x; int rows;
     struct Fixed { int off; bool ok; };
     __device__ __forceinline__ Fixed prep(int col, int) const {

@@ -267,7 +267,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         PAAC_PHASE_END(0);
         compute(kt & 1);
         PAAC_PHASE_END(1);
-        if (kt + 1 < nk) lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);
+        lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last tile: zeros nobody reads
         PAAC_PHASE_END(2);
         __syncthreads();
         PAAC_PHASE_END(3);
@@ -280,11 +280,23 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     lstore(std::integral_constant<int, 0>(), 0);
     __syncthreads();
     PAAC_STAMP(2);
-    for (int kt = 0; kt < nk; kt += S) {
+    // Whole rounds of S steps run without any branch, the remainder after the loop.  With a step that
+    // can be skipped inside the loop the compiler sees a path on which a register stage is loaded
+    // again while its previous load is still outstanding, and waits for ALL loads at the loop head:
+    // that would drain the prefetch pipeline once per round.
+    int kt = 0;
+    for (int q = nk / S; q > 0; --q, kt += S) {
         step(kt, std::integral_constant<int, 0>());
-        if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>());
-        if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
-        if constexpr (S > 3) { if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>()); }
+        step(kt + 1, std::integral_constant<int, 1>());
+        if constexpr (S > 2) step(kt + 2, std::integral_constant<int, 2>());
+        if constexpr (S > 3) step(kt + 3, std::integral_constant<int, 3>());
+    }
+    if (kt < nk) {
+        step(kt, std::integral_constant<int, 0>());
+        if (kt + 1 < nk) {
+            step(kt + 1, std::integral_constant<int, 1>());
+            if constexpr (S > 2) { if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>()); }
+        }
     }
 
     PAAC_STAMP(3);
