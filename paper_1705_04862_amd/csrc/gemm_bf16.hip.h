@@ -77,6 +77,12 @@ template <class EP, class = void> struct EpiTraits { static constexpr bool kEntr
 template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
     static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
 };
+template <class EP, class = void> struct EpiColMap {          // column index -> offset added to the row entry
+    static __device__ __forceinline__ int off(const EP&, int col) { return col; }
+};
+template <class EP> struct EpiColMap<EP, std::enable_if_t<EP::kColMap>> {
+    static __device__ __forceinline__ int off(const EP& ep, int col) { return ep.col_off(col); }
+};
 
 template <class T, class AL, class BL, class EP>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
@@ -274,17 +280,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
                         if constexpr (EpiTraits<EP>::kRowTable) ent[r] = rowtab[tile_par * BM + lr];
                         else ent[r] = ep.row_entry(m0 + lr < M ? m0 + lr : 0, z);
                     }
+                    const int coff = EpiColMap<EP>::off(ep, col < N ? col : 0);
                     typename EP::Aux aux[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) aux[r] = ep.aux(ent[r], col < N ? col : 0);
+                    for (int r = 0; r < 16; ++r) aux[r] = ep.aux(ent[r], coff);
                     if (full) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) ep.store(ent[r], col, acc[i][j][r], aux[r]);
+                        for (int r = 0; r < 16; ++r) ep.store(ent[r], coff, acc[i][j][r], aux[r]);
                     } else {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                            if (row < M && col < N) ep.store(ent[r], col, acc[i][j][r], aux[r]);
+                            if (row < M && col < N) ep.store(ent[r], coff, acc[i][j][r], aux[r]);
                         }
                     }
                 } else {
@@ -455,18 +462,22 @@ template <class G> struct DgradGatherRowsK8 {
     }
 };
 
-// Weights seen by the data gradient, from the bf16 copy laid out [ci][ky][kx][co]:
-// B(k = (ty,tx,co), n = ci), ky = py + ST*ty, kx = px + ST*tx for parity class z = py*ST + px.
+// Weights seen by the data gradient, from the bf16 copy laid out [ci][ky][kx][co].  All ST*ST parity
+// classes of input positions share the gathered dY rows (the taps (ty, tx) reach the same output
+// positions whatever the class), so the classes are columns of ONE GEMM:
+//   B(k = (ty,tx,co), n = (py,px,ci)) = W[ci][py + ST*ty][px + ST*tx][co].
 template <class G> struct DgradWeightRowsK8 {
     static constexpr bool kContig = true;
+    static constexpr int NCOL = G::ST * G::ST * G::CIN;
     typedef uint4 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
     const bf16_t* w;
     struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int ci, int z) const {
-        Fixed f; f.ok = ci < G::CIN;
-        const int py = z / G::ST, px = z % G::ST;
-        f.off = ((f.ok ? ci : 0) * (G::KS * G::KS) + py * G::KS + px) * G::COUT * 2;
+    __device__ __forceinline__ Fixed prep(int col, int) const {
+        Fixed f; f.ok = col < NCOL;
+        col = f.ok ? col : 0;
+        const int cls = col / G::CIN, ci = col % G::CIN, py = cls / G::ST, px = cls % G::ST;
+        f.off = (ci * (G::KS * G::KS) + py * G::KS + px) * G::COUT * 2;
         return f;
     }
     __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
@@ -571,18 +582,23 @@ struct EpiPartialScaled {       // out[z][row][col] = scale * v, column sums of 
 
 __device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) != 0 && !(a & 0x8000u); }
 
-template <class G> struct EpiDgradMaskB {      // scatter a parity class back to NHWC, times ReLU'
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = true;
+// Data gradient output: row = (n, yy, xx) block of ST x ST input positions, column = (py, px, ci);
+// element goes to dx[n][yy*ST + py][xx*ST + px][ci], times ReLU'(act) at the same place.
+template <class G> struct EpiDgradMaskB {
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true;
     typedef bf16_t Aux;
     bf16_t* dx; const bf16_t* act;
-    __device__ __forceinline__ int row_entry(int row, int z) const {
-        const int py = z / G::ST, px = z % G::ST;
+    __device__ __forceinline__ int row_entry(int row, int) const {
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
-        return ((n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN;
+        return ((n * G::H + yy * G::ST) * G::W + xx * G::ST) * G::CIN;
     }
-    __device__ __forceinline__ Aux aux(int ent, int col) const { return act[(size_t)(unsigned)(ent + col)]; }
-    __device__ __forceinline__ void store(int ent, int col, float v, Aux a) const {
-        dx[(size_t)(unsigned)(ent + col)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
+    __device__ __forceinline__ int col_off(int col) const {
+        const int cls = col / G::CIN, ci = col % G::CIN;
+        return ((cls / G::ST) * G::W + cls % G::ST) * G::CIN + ci;
+    }
+    __device__ __forceinline__ Aux aux(int ent, int coff) const { return act[(size_t)(unsigned)(ent + coff)]; }
+    __device__ __forceinline__ void store(int ent, int coff, float v, Aux a) const {
+        dx[(size_t)(unsigned)(ent + coff)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
     }
 };
 

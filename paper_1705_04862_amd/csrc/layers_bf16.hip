@@ -50,12 +50,11 @@ hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, con
 // ---------------------------------------------------------------------------------- data gradient
 template <class G>
 static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in, bf16_t* dx, int ns) {
-    typedef typename TileBForN<G::CIN>::type T;
-    const int M = ns * G::HC * G::WC;
+    const int M = ns * G::HC * G::WC;                // blocks of ST x ST input positions
     DgradGatherRowsK8<G> al{dy, M};
     DgradWeightRowsK8<G> bl{Wd};
     EpiDgradMaskB<G> ep{dx, act_in};
-    return launch_gemm_bf16<T>(s, al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0);
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, M, G::ST * G::ST * G::CIN, G::KD, 1, 0);
 }
 
 hipError_t conv_dgrad_bf16(hipStream_t s, int arch, int layer, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in,
