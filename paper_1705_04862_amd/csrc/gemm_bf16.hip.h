@@ -24,6 +24,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ bf16_t f2bf(float f) { __bf16 b = (__bf16)f; return __builtin_bit_cast(unsigned short, b); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
 __device__ __forceinline__ unsigned pack2(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// acc + lo + hi of a packed bf16 pair: one v_dot2 against (1, 1)
+__device__ __forceinline__ float dot2_ones(unsigned pair, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
 __device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
 __device__ __forceinline__ uint4 keep_if_u4(bool ok, uint4 v) {
     return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
@@ -77,6 +82,13 @@ template <class EP, class = void> struct EpiTraits { static constexpr bool kEntr
 template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
     static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
 };
+// KRow loaders whose address needs divisions per reduction index (im2col of an output position)
+// declare kRowTab: the kernel then keeps the per-index offsets of the coming k tiles in a small LDS
+// table, filled by 64 threads one pipeline step ahead, and a staging unit fetches its four offsets
+// with one 16-byte LDS read instead of four chains of integer divisions.
+template <class L, class = void> struct RowTab { static constexpr bool value = false; };
+template <class L> struct RowTab<L, std::enable_if_t<L::kRowTab>> { static constexpr bool value = true; };
+
 template <class EP, class = void> struct EpiColMap {          // column index -> offset added to the row entry
     static __device__ __forceinline__ int off(const EP&, int col) { return col; }
 };
@@ -106,6 +118,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
     __shared__ int rowtab[EpiTraits<EP>::kRowTable ? 2 * BM : 1];
     bf16_t* const As = smem;
     bf16_t* const Bs = smem + 2 * A_BUF;
+    constexpr bool ATAB = !ROWK && RowTab<AL>::value;
+    constexpr int RS = S + 1;                                     // table slots: k tile j lives in slot j % RS
+    __shared__ __attribute__((aligned(16))) int ktab[ATAB ? RS * BK : 4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % T::WM, wn = wave / T::WM;
@@ -146,6 +161,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         for (int i = 0; i < B_IT; ++i) bfix[i] = bl.prep(n0 + b_fix0[i], z);
     };
 
+    // offsets of the reduction indices of k tile `kt` (also past the end: -1 = load nothing)
+    auto fill_tab = [&](int kt, int idx) __attribute__((always_inline)) {
+        if constexpr (ATAB) {
+            const int r = k_begin + kt * BK + idx;
+            ktab[(kt % RS) * BK + idx] = r < k_end ? al.row_entry(r) : -1;
+        }
+    };
     typename AL::Raw areg[S][A_IT][NL];
     typename BL::Raw breg[S][B_IT][NL];
     unsigned okbits[S];
@@ -154,14 +176,26 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         const int kb = k_begin + kt * BK;
         unsigned bits = 0;
 #pragma unroll
-        for (int i = 0; i < A_IT; ++i)
+        for (int i = 0; i < A_IT; ++i) {
+            if constexpr (ATAB) {
+                const int4 e = *reinterpret_cast<const int4*>(&ktab[(kt % RS) * BK + a_var[i]]);
+                const int ent[4] = {e.x, e.y, e.z, e.w};
 #pragma unroll
-            for (int q = 0; q < NL; ++q) {
-                const int kk = kb + a_var[i] + q;
-                bool ok;
-                areg[G][i][q] = al.load(afix[i], kk, (A_U % 256 == 0 || tid + i * 256 < A_U) && kk < k_end, ok);
-                bits |= ok ? (1u << (i * NL + q)) : 0u;
+                for (int q = 0; q < NL; ++q) {
+                    bool ok;
+                    areg[G][i][q] = al.load_at(afix[i], ent[q], A_U % 256 == 0 || tid + i * 256 < A_U, ok);
+                    bits |= ok ? (1u << (i * NL + q)) : 0u;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < NL; ++q) {
+                    const int kk = kb + a_var[i] + q;
+                    bool ok;
+                    areg[G][i][q] = al.load(afix[i], kk, (A_U % 256 == 0 || tid + i * 256 < A_U) && kk < k_end, ok);
+                    bits |= ok ? (1u << (i * NL + q)) : 0u;
+                }
             }
+        }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i)
 #pragma unroll
@@ -252,9 +286,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
 #pragma unroll
                 for (int c = 0; c < BK / 8; ++c) {
                     const uint4 v = *reinterpret_cast<const uint4*>(bs + tid * LD + c * 8);
-                    colsum += bf2f((bf16_t)(v.x & 0xffffu)) + bf2f((bf16_t)(v.x >> 16)) + bf2f((bf16_t)(v.y & 0xffffu)) +
-                              bf2f((bf16_t)(v.y >> 16)) + bf2f((bf16_t)(v.z & 0xffffu)) + bf2f((bf16_t)(v.z >> 16)) +
-                              bf2f((bf16_t)(v.w & 0xffffu)) + bf2f((bf16_t)(v.w >> 16));
+                    colsum = dot2_ones(v.w, dot2_ones(v.z, dot2_ones(v.y, dot2_ones(v.x, colsum))));
                 }
             }
         }
@@ -314,6 +346,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         constexpr int G = decltype(stage)::value;
         constexpr int GN = (G + 1) % S;
         gload(kt + S, stage);
+        if (ATAB && tid < BK) fill_tab(kt + S + 1, tid);          // read by the next step's gload, after this step's barrier
         compute(kt & 1);
         lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last k tile: zeros nobody reads
         __syncthreads();
@@ -324,6 +357,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             static_assert(BM <= 256, "one thread per row of the tile");
             const int row = (c_tile % m_tiles) * BM + tid;
             if (tid < BM) rowtab[tile_par * BM + tid] = ep.row_entry(row < M ? row : 0, z);
+        }
+        if constexpr (ATAB) {
+            for (int e = tid; e < RS * BK; e += 256) fill_tab(e / BK, e % BK);      // k tiles 0 .. S
+            __syncthreads();
         }
         gload(0, std::integral_constant<int, 0>());
         gload(1, std::integral_constant<int, 1>());
@@ -497,7 +534,7 @@ template <class G> struct DgradWeightRowsK8 {
 
 template <class G> struct ConvU8KCols8 {       // A(m = (c,ky,kx), k = output position), 8 kx per load
     static_assert(G::KS == 8, "one 8-byte load covers one kernel row");
-    static constexpr bool kContig = false;
+    static constexpr bool kContig = false, kRowTab = true;
     typedef uint2 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return u8x8_to_bf16_if(ok, r); }
     const uint8_t* x; int rows;
@@ -509,17 +546,20 @@ template <class G> struct ConvU8KCols8 {       // A(m = (c,ky,kx), k = output po
         f.off = c * (G::H * G::W) + ky * G::W;
         return f;
     }
-    __device__ __forceinline__ Raw load(const Fixed& f, int row, bool pred, bool& ok) const {
-        ok = pred && f.ok && row < rows;
-        row = ok ? row : 0;
+    __device__ __forceinline__ int row_entry(int row) const {       // byte offset of the window's corner, -1 past the end
+        if (row >= rows) return -1;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST + f.off);
+        return n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
+    }
+    __device__ __forceinline__ Raw load_at(const Fixed& f, int ent, bool pred, bool& ok) const {
+        ok = pred && f.ok && ent >= 0;
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(at(x, ok ? ent + f.off : 0));
         return make_uint2(p[0], p[1]);
     }
 };
 
 template <class G> struct ConvNHWCKCols8 {     // A(m = (ky,kx,c), k = output position) from bf16 NHWC
-    static constexpr bool kContig = false;
+    static constexpr bool kContig = false, kRowTab = true;
     typedef uint4 Raw;
     static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
     const bf16_t* x; int rows;
@@ -528,14 +568,17 @@ template <class G> struct ConvNHWCKCols8 {     // A(m = (ky,kx,c), k = output po
         Fixed f; f.ok = col < G::KK;
         col = f.ok ? col : 0;
         const int ky = col / (G::KS * G::CIN), rem = col % (G::KS * G::CIN);
-        f.off = ky * (G::W * G::CIN) + rem;
+        f.off = (ky * (G::W * G::CIN) + rem) * 2;
         return f;
     }
-    __device__ __forceinline__ Raw load(const Fixed& f, int row, bool pred, bool& ok) const {
-        ok = pred && f.ok && row < rows;
-        row = ok ? row : 0;
+    __device__ __forceinline__ int row_entry(int row) const {
+        if (row >= rows) return -1;
         const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        return *reinterpret_cast<const uint4*>(x + ((size_t)(n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN + f.off);
+        return (((n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN) * 2;
+    }
+    __device__ __forceinline__ Raw load_at(const Fixed& f, int ent, bool pred, bool& ok) const {
+        ok = pred && f.ok && ent >= 0;
+        return *reinterpret_cast<const uint4*>(at(x, ok ? ent + f.off : 0));
     }
 };
 
