@@ -120,7 +120,7 @@ hipError_t fc_fwd_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* W
     DenseRowsK8 al{x, ns, flat};
     DenseRowsK8 bl{Wt, fc, flat};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
-    return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
 }
 
 // dx[ns][flat] = (dh[ns][fc] . W[flat][fc]^T) * 1[act > 0]
@@ -142,7 +142,7 @@ hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t*
     DenseKCols8 al{x, flat, flat};
     DenseKCols8 bl{dh, fc, fc};
     EpiPartial<true> ep{pw, (size_t)flat * fc, fc, pb, fc};
-    return launch_gemm_bf16<B128x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per);
+    return launch_gemm_bf16<B128x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per, 1);
 }
 
 // ---------------------------------------------------------------------------------- bf16 weight copies
