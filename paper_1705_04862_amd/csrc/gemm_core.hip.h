@@ -84,6 +84,8 @@ struct Tile {
 //           void store(int row, int col, float v, int z, Aux) const;
 //           void store_colsum(int col, float v, int z) const      (only if kColSum)
 
+template <class E, class = void> struct AuxEarly { static constexpr bool value = false; };
+template <class E> struct AuxEarly<E, std::enable_if_t<E::kAuxEarly>> { static constexpr bool value = true; };
 template <class L, class = void> struct RowFast { static constexpr bool value = false; };
 template <class L> struct RowFast<L, std::enable_if_t<L::kRowFast>> { static constexpr bool value = true; };
 template <class L> __host__ __device__ constexpr bool row_fast() { return RowFast<L>::value; }
@@ -189,7 +191,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         constexpr int G = decltype(stage)::value;
 #pragma unroll
         for (int i = 0; i < A_IT; ++i) {
-            if (tid + i * 256 < A_F4) {
+            if (A_F4 % 256 == 0 || tid + i * 256 < A_F4) {
                 float* p = As + buf * A_BUF + a_lds[i];
                 const float4 v = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
                 if (AL::kContig) { p[0] = v.x; p[LDA] = v.y; p[2 * LDA] = v.z; p[3 * LDA] = v.w; }
@@ -198,7 +200,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
-            if (tid + i * 256 < B_F4) {
+            if (B_F4 % 256 == 0 || tid + i * 256 < B_F4) {
                 float* p = Bs + buf * B_BUF + b_lds[i];
                 const float4 v = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
                 if (BL::kContig) { p[0] = v.x; p[LDB] = v.y; p[2 * LDB] = v.z; p[3 * LDB] = v.w; }
@@ -272,6 +274,24 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         __syncthreads();
         PAAC_PHASE_END(3);
     };
+    // Auxiliary epilogue operands (bias, ReLU mask) do not depend on the accumulators: their loads are
+    // issued before the first operand load, so the epilogue does not start with a memory round trip
+    // (about a microsecond, a tenth of a small-batch kernel).
+    typename EP::Aux aux[TM][TN][MM::NACC];
+    auto load_aux = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (TN * MF) + j * MF + MM::col(lane);
+#pragma unroll
+                for (int r = 0; r < MM::NACC; ++r) {
+                    const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
+                    aux[i][j][r] = ep.aux(row, col, z, wk == 0 && row < M && col < N);
+                }
+            }
+    };
+    if constexpr (AuxEarly<EP>::value) load_aux();      // one register per column (a bias); masks would cost 16
     PAAC_STAMP(1);
     gload(0, std::integral_constant<int, 0>());
     gload(1, std::integral_constant<int, 1>());
@@ -335,22 +355,16 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
                     for (int r = 0; r < MM::NACC; ++r) acc[0][i][j][r] += src[((i * TN + j) * MM::NACC + r) * 64];
         }
     }
+    if constexpr (!AuxEarly<EP>::value) load_aux();     // every auxiliary load of the tile, then the stores
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * (TN * MF) + j * MF + MM::col(lane);
-            // first every auxiliary load of the fragment (bias, ReLU mask), then the stores
-            typename EP::Aux aux[MM::NACC];
 #pragma unroll
             for (int r = 0; r < MM::NACC; ++r) {
                 const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
-                aux[r] = ep.aux(row, col, z, row < M && col < N);
-            }
-#pragma unroll
-            for (int r = 0; r < MM::NACC; ++r) {
-                const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
-                if (row < M && col < N) ep.store(row, col, acc[0][i][j][r], z, aux[r]);
+                if (row < M && col < N) ep.store(row, col, acc[0][i][j][r], z, aux[i][j][r]);
             }
         }
     PAAC_STAMP(4);
@@ -559,7 +573,7 @@ template <class G> struct ConvNHWCKCols {
 // ----------------------------------------------------------------------------------------------
 // Epilogues
 struct EpiBiasRelu {            // out[row][col] = max(v + bias[col], 0)
-    static constexpr bool kColSum = false;
+    static constexpr bool kColSum = false, kAuxEarly = true;
     typedef float Aux;
     float* out; const float* bias; int ldo;
     __device__ __forceinline__ Aux aux(int, int col, int, bool ok) const { return bias[ok ? col : 0]; }
