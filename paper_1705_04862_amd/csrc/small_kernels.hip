@@ -108,18 +108,109 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
     }
 }
 
+// Small batches (every select call of the paper's configurations, the train forward up to a few
+// thousand rows): one workgroup per state row, so that the chain of dependent memory round trips is
+// as short as possible.  All loads that do not depend on h (the split partial sums of the row, the
+// head weights of this wave's outputs) are issued at once; thread t owns F/256 hidden units, wave w
+// the outputs w, w+4, ...; the element-to-lane assignment and the reduction order of a dot product
+// are those of heads_fwd_kernel, so both kernels produce the same bits.
+template <int F, int KMAX>
+__global__ __launch_bounds__(256) void heads_fwd_row_kernel(const HeadsArgs a) {
+    constexpr int C = F / 256, U = F / 256, KW = (KMAX + 3) / 4;      // chunks per lane, units per thread, outputs per wave
+    constexpr int SMAX = 32;                                          // splits held in registers at once
+    __shared__ __attribute__((aligned(16))) float hs[F];
+    __shared__ float outs[KMAX + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = blockIdx.x;
+    // head weights of this wave's outputs (branch-free: outputs beyond A re-read the value row)
+    float4 w4[KW][C];
+#pragma unroll
+    for (int q = 0; q < KW; ++q) {
+        const int k = wave + 4 * q;
+        const float* w = k < a.A ? a.pi_w + (size_t)k * F : a.v_w;
+#pragma unroll
+        for (int c = 0; c < C; ++c) w4[q][c] = *reinterpret_cast<const float4*>(w + c * 256 + lane * 4);
+    }
+    // hidden units tid*U .. tid*U+U-1: split partial sums added in ascending split order
+    const float* src = a.fc_partial + (size_t)row * F + tid * U;
+    float acc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc[u] = 0.f;
+    for (int s0 = 0; s0 < a.n_split; s0 += SMAX) {
+        float p[SMAX][U];
+#pragma unroll
+        for (int q = 0; q < SMAX; ++q) {
+            const int sidx = min(s0 + q, a.n_split - 1);              // clamped: a valid address, ignored below
+            if constexpr (U == 2) {
+                const float2 v = *reinterpret_cast<const float2*>(src + (size_t)sidx * a.split_stride);
+                p[q][0] = v.x; p[q][1] = v.y;
+            } else {
+                p[q][0] = src[(size_t)sidx * a.split_stride];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < SMAX; ++q)
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u] += (s0 + q < a.n_split) ? p[q][u] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        acc[u] = fmaxf(acc[u] + a.fc_b[tid * U + u], 0.f);
+        hs[tid * U + u] = acc[u];
+        if (a.h_out) a.h_out[(size_t)row * F + tid * U + u] = acc[u];
+    }
+    __syncthreads();
+    float4 h[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) h[c] = *reinterpret_cast<const float4*>(hs + c * 256 + lane * 4);
+#pragma unroll
+    for (int q = 0; q < KW; ++q) {
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) d += h[c].x * w4[q][c].x + h[c].y * w4[q][c].y + h[c].z * w4[q][c].z + h[c].w * w4[q][c].w;
+        const float t = wave_sum(d);
+        const int k = wave + 4 * q;
+        if (lane == 0 && k <= a.A && k < KMAX) outs[k] = t;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const float z = lane < a.A ? outs[lane] + a.pi_b[lane] : -INFINITY;
+    const float v = outs[a.A] + a.v_b[0];
+    if (a.values_out && lane == 0) a.values_out[row] = v;
+    if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
+    if (a.uniforms) {
+        const float m = wave_max(z);
+        const float e = lane < a.A ? expf(z - m) : 0.f;
+        const float p = e / wave_sum(e);
+        if (a.probs_out && lane < a.A) a.probs_out[(size_t)row * a.A + lane] = p;
+        const float u = a.uniforms[row];
+        float cdf = 0.f;
+        int act = a.A - 1;
+        bool found = false;
+        for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
+            cdf = cdf + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), k));
+            if (!found && u < cdf) { act = k; found = true; }
+        }
+        if (lane == 0) a.actions_out[row] = act;
+    }
+}
+
+template <int F, int KMAX> static void launch_heads(hipStream_t s, const HeadsArgs& a) {
+    if (a.rows <= 512) launch_k((heads_fwd_row_kernel<F, KMAX>), dim3(a.rows), dim3(256), s, a);
+    else launch_k((heads_fwd_kernel<F, KMAX>), dim3((a.rows + 3) / 4), dim3(256), s, a);
+}
+
 hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a) {
     if (a.rows <= 0) return hipErrorInvalidValue;
-    dim3 grid((a.rows + 3) / 4);
     const int outs = a.A + 1;
     if (F == 256) {
-        if (outs <= 8) launch_k((heads_fwd_kernel<256, 8>), grid, dim3(256), s, a);
-        else if (outs <= 19) launch_k((heads_fwd_kernel<256, 19>), grid, dim3(256), s, a);
-        else launch_k((heads_fwd_kernel<256, 33>), grid, dim3(256), s, a);
+        if (outs <= 8) launch_heads<256, 8>(s, a);
+        else if (outs <= 19) launch_heads<256, 19>(s, a);
+        else launch_heads<256, 33>(s, a);
     } else if (F == 512) {
-        if (outs <= 8) launch_k((heads_fwd_kernel<512, 8>), grid, dim3(256), s, a);
-        else if (outs <= 19) launch_k((heads_fwd_kernel<512, 19>), grid, dim3(256), s, a);
-        else launch_k((heads_fwd_kernel<512, 33>), grid, dim3(256), s, a);
+        if (outs <= 8) launch_heads<512, 8>(s, a);
+        else if (outs <= 19) launch_heads<512, 19>(s, a);
+        else launch_heads<512, 33>(s, a);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
 }
