@@ -1,0 +1,117 @@
+// First convolution (8x8, stride 4, uint8 NCHW input) with bf16 operands, straight from the image.
+//
+// The im2col view repeats every input byte in four output windows, and turning bytes into bf16 is
+// the dominant cost of this layer in the generic GEMM kernel.  Here a workgroup takes NS consecutive
+// samples at a time: their NS x 4 x 84 x 84 bytes are one contiguous block of global memory,
+// loaded with 16-byte loads, converted ONCE and kept in LDS as bf16 in the same (c, y, x) order.
+// The MFMA A fragment of an output position (oy, ox) and k-group (c, ky) is then the 16 bytes at
+//   img[c][4*oy + ky][4*ox .. 4*ox + 7],
+// i.e. one base address per fragment plus compile-time offsets; the weights (COUT x 256) stay in
+// registers for the lifetime of the workgroup.  An image row is 84 elements = 42 words: the rows of
+// consecutive output rows continue each other's bank sequence, no padding is needed.
+// NS = 1 (56 KB of LDS) lets two workgroups share a compute unit, so that one converts and waits
+// while the other multiplies; its 400 output rows are 12.5 fragments of 32 (the last is half empty).
+#pragma once
+#include "gemm_bf16.hip.h"
+
+namespace paac {
+
+template <class G, int NS>
+__global__ __launch_bounds__(256, 2) void conv1_direct_kernel(const uint8_t* __restrict__ x, const bf16_t* __restrict__ Wt,
+                                                           const float* __restrict__ bias, bf16_t* __restrict__ out, int ns,
+                                                           float scale) {
+    static_assert(G::CIN == 4 && G::H == 84 && G::W == 84 && G::KS == 8 && G::ST == 4 && G::COUT <= 32, "first layer");
+    constexpr int SAMPLE = G::CIN * G::H * G::W;            // 28224 bytes, a multiple of 16
+    constexpr int CHUNKS = NS * SAMPLE / 16, IT = (CHUNKS + 255) / 256;
+    constexpr int ROWS = G::HO * G::WO;                     // 400 output positions per sample
+    constexpr int FRAGS = (NS * ROWS + 31) / 32;
+    static_assert(SAMPLE % 16 == 0, "whole 16-byte chunks");
+    __shared__ __attribute__((aligned(16))) bf16_t img[NS * SAMPLE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fidx = lane & 31, kg = lane >> 5;
+    const int pairs = (ns + NS - 1) / NS;                   // groups of NS samples
+    const long total_bytes = (long)ns * SAMPLE;
+
+    // weights of output channel fidx: sixteen k-steps of 16, this lane's eight k of each
+    bf16x8 breg[16];
+#pragma unroll
+    for (int kt = 0; kt < 16; ++kt) {
+        uint4 w = zero_u4();
+        if (fidx < G::COUT) w = *reinterpret_cast<const uint4*>(Wt + fidx * 256 + kt * 16 + kg * 8);
+        breg[kt] = __builtin_bit_cast(bf16x8, w);
+    }
+    const float bias_r = fidx < G::COUT ? bias[fidx] : 0.f;
+
+    uint4 pre[IT];
+    auto prefetch = [&](int p) __attribute__((always_inline)) {
+        const long base = (long)p * (NS * SAMPLE);
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            const int ch = tid + i * 256;
+            const long off = base + (long)ch * 16;
+            const bool ok = ch < CHUNKS && off < total_bytes;           // sample sizes are multiples of 16
+            pre[i] = *reinterpret_cast<const uint4*>(x + (ok ? off : 0));
+            if (!ok) pre[i] = zero_u4();
+        }
+    };
+    int p = blockIdx.x;
+    if (p >= pairs) return;
+    prefetch(p);
+    for (; p < pairs; p += gridDim.x) {
+        // bytes -> bf16, same linear order
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            const int ch = tid + i * 256;
+            if (ch < CHUNKS) {
+                uint4* dst = reinterpret_cast<uint4*>(img + ch * 16);
+                dst[0] = u8x8_to_bf16(make_uint2(pre[i].x, pre[i].y));
+                dst[1] = u8x8_to_bf16(make_uint2(pre[i].z, pre[i].w));
+            }
+        }
+        __syncthreads();
+        if (p + (int)gridDim.x < pairs) prefetch(p + gridDim.x);       // in flight during the MFMA phase
+        const int row0 = p * (NS * ROWS), M = ns * ROWS;
+        for (int f = wave; f < FRAGS; f += 4) {
+            const int row = min(f * 32 + fidx, NS * ROWS - 1);        // rows past the group: a valid address, never stored
+            const int s = row / ROWS, r = row % ROWS, oy = r / G::WO, ox = r % G::WO;
+            const bf16_t* a0 = img + s * SAMPLE + (oy * G::ST + kg) * G::W + ox * G::ST;
+            f32x16 acc;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const uint2* ap = reinterpret_cast<const uint2*>(a0 + c * (G::H * G::W) + ks * 2 * G::W);   // 8-byte aligned
+                    const uint2 lo = ap[0], hi = ap[1];
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, breg[c * 4 + ks], acc, 0, 0, 0);
+                }
+            if (fidx < G::COUT) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int lr = f * 32 + Mma<32>::row(q, lane);
+                    const int orow = row0 + lr;
+                    if (lr < NS * ROWS && orow < M) out[(size_t)orow * G::COUT + fidx] = f2bf(fmaxf(acc[q] * scale + bias_r, 0.f));
+                }
+            }
+        }
+        __syncthreads();                                              // the image is rewritten next
+    }
+}
+
+template <class G, int NS = 1>
+inline hipError_t launch_conv1_direct(hipStream_t s, const uint8_t* x, const bf16_t* Wt, const float* bias, bf16_t* out, int ns) {
+    if (ns <= 0) return hipErrorInvalidValue;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    }
+    const int groups = (ns + NS - 1) / NS;
+    launch_k((conv1_direct_kernel<G, NS>), dim3(std::min(groups, 2 * cus)), dim3(256), s, x, Wt, bias, out, ns, 1.0f / 255.0f);
+    return hipGetLastError();
+}
+
+}  // namespace paac

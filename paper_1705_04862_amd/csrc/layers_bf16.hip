@@ -1,6 +1,6 @@
 // Dense layers of the PAAC network with bf16 operands (bf16 activations and weight copies, fp32
 // accumulation and fp32 gradients): the same six contractions as layers.hip on the bf16 GEMM core.
-#include "gemm_bf16.hip.h"
+#include "conv1_direct.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -26,8 +26,7 @@ static hipError_t conv_fwd_t(hipStream_t s, const void* in, const bf16_t* Wt, co
     DenseRowsK8 bl{Wt, G::COUT, G::KK};              // B(k, n = co) = Wt[co][k]
     EpiBiasReluB ep{out, b, G::COUT, U8 ? 1.0f / 255.0f : 1.0f};     // bytes enter unscaled
     if constexpr (U8) {
-        ConvU8RowsK8<G> al{(const uint8_t*)in, M};
-        return launch_gemm_bf16<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
+        return launch_conv1_direct<G>(s, (const uint8_t*)in, Wt, b, out, ns);
     } else {
         ConvNHWCRowsK8<G> al{(const bf16_t*)in, M};
         return launch_gemm_bf16<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
