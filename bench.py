@@ -72,6 +72,8 @@ def main():
                     help="only run a 256 MiB device-to-device copy 10 times (calibrates the HBM byte counters)")
     ap.add_argument("--n_e", type=int, default=0, help="override the configuration's environment count (n_e sweep)")
     ap.add_argument("--t_max", type=int, default=0, help="override the configuration's rollout length")
+    ap.add_argument("--lr", type=float, default=0.0, help="override the configuration's learning rate")
+    ap.add_argument("--sweep-ne", default="", help="comma separated n_e values: one line with the throughput at each (lr = 0.0007 n_e)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -89,10 +91,26 @@ def main():
     from paper_1705_04862_amd import inputs as I
     from paper_1705_04862_amd import paac as P
 
+    import dataclasses
     cfg = I.CONFIGS[args.config]
-    if args.n_e or args.t_max:
-        import dataclasses
-        cfg = dataclasses.replace(cfg, n_e=args.n_e or cfg.n_e, t_max=args.t_max or cfg.t_max)
+    if args.sweep_ne:
+        # the paper's n_e study: the same network at several n_e with lr = 0.0007 n_e (throughput only)
+        rows = []
+        for ne in [int(x) for x in args.sweep_ne.split(",")]:
+            sub = [sys.executable, os.path.abspath(__file__), "--config", str(args.config), "--n_e", str(ne), "--lr", repr(0.0007 * ne),
+                   "--steps", str(args.steps), "--warmup", str(args.warmup), "--no-cpu-baseline", "--profile-steps", "5"]
+            import subprocess
+            line = subprocess.run(sub, check=True, capture_output=True, text=True).stdout.strip().splitlines()[-1]
+            d = json.loads(line)
+            rows.append({"n_e": ne, "lr": 0.0007 * ne, "value": d["value"], "ms_per_step": d["ms_per_step"],
+                         "pct_mfma_peak_whole_step": d["pct_mfma_peak_whole_step"], "launch": d["config"]["launch"]})
+        print(json.dumps({"metric": "env-timesteps/sec (select+train) over n_e, lr = 0.0007 n_e", "unit": "env-timesteps/s",
+                          "n_gpus": 1, "data": "synthetic", "config": {"workload": cfg.name + " with n_e swept", "t_max": cfg.t_max},
+                          "sweep": rows}))
+        return
+    if args.n_e or args.t_max or args.lr:
+        cfg = dataclasses.replace(cfg, n_e=args.n_e or cfg.n_e, t_max=args.t_max or cfg.t_max,
+                                  hp=dataclasses.replace(cfg.hp, lr=args.lr or cfg.hp.lr))
     net, n_e, T = cfg.net, cfg.n_e, cfg.t_max
     torch.cuda.set_device(0)
     ctx = P.Paac(net.arch, n_e, T, net.n_actions, cfg.precision)

@@ -519,3 +519,38 @@ def test_bf16_config4_full_size_sampled(paac, oracle):
     # every tensor received a gradient
     for name, sl in net.param_slices().items():
         assert np.abs(grads[sl]).max() > 0, name
+
+
+@pytest.mark.parametrize("n_e", [16, 64, 128])
+def test_ne_sweep_sizes_with_scaled_learning_rate(paac, oracle, n_e):
+    """Sizes of the paper's n_e study (Experiments, the n_e / learning-rate figure): lr = 0.0007 n_e,
+    one select slab and one train step each, on the smaller network so the oracle stays quick."""
+    net, t_max = I.nips_net(6), 5
+    ctx = make_ctx(paac, net, n_e, t_max)
+    params = I.make_params(300 + n_e, net, bias_range=0.05)
+    rms = I.make_rms(300 + n_e, net, hi=0.01)
+    ro = I.make_rollout(300 + n_e, net, n_e, t_max, 0.01)
+    ctx.set_state(params, rms)
+    check_select(oracle, net, params, ro.states[0], ro.uniforms[0], run_select(ctx, net, ro.states[0], ro.uniforms[0]))
+    check_train(oracle, net, ctx, params, rms, ro, I.HParams(lr=0.0007 * n_e), f"ne{n_e}")
+
+
+def test_heads_kernels_agree_across_the_batch_threshold(paac, oracle):
+    """Up to 512 rows the heads run one workgroup per row, above that one wavefront per row; both must
+    give the oracle's answer, and the same bits for the same state."""
+    net = I.nips_net(6)
+    params = I.make_params(41, net, bias_range=0.1)
+    st = I.make_states(41, 1, 520, net)[0]
+    u = I.make_uniforms(41, 1, 520)[0]
+    big = make_ctx(paac, net, 520, 1)
+    big.set_state(params)
+    got_big = run_select(big, net, st, u)
+    check_select(oracle, net, params, st, u, got_big)
+    small = make_ctx(paac, net, 40, 1)
+    small.set_state(params)
+    got_small = run_select(small, net, st[:40], u[:40])
+    assert np.array_equal(got_small[0], got_big[0][:40])
+    # the conv/fc GEMMs pick other tiles and k-splits at the other batch size, so values agree to
+    # rounding, not to the bit
+    assert relmax(got_small[1], got_big[1][:40].astype(np.float64)) < 1e-5
+    assert relmax(got_small[2], got_big[2][:40].astype(np.float64)) < 1e-5
