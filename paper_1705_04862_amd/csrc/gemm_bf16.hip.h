@@ -413,32 +413,6 @@ __device__ __forceinline__ const char* at(const void* base, int byte_off) {
     return static_cast<const char*>(base) + (unsigned)byte_off;      // tensors are far below 4 GiB
 }
 
-// im2col rows of uint8 NCHW states, k = (c, ky, kx): one kernel row of 8 bytes per load; values are
-// the bytes themselves (not yet divided by 255).
-template <class G> struct ConvU8RowsK8 {
-    static_assert(G::KS == 8, "one 8-byte load covers one kernel row");
-    static constexpr bool kContig = true;
-    static constexpr bool kRowFast = true;      // lanes walk output positions (stride ST bytes), not kernel rows
-    typedef uint2 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return u8x8_to_bf16_if(ok, r); }
-    const uint8_t* x; int rows;
-    struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.ok = row < rows;
-        row = f.ok ? row : 0;
-        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        f.off = n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        ok = pred && f.ok;
-        k = pred ? k : 0;
-        const int c = k / 64, ky = (k % 64) / 8;
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(at(x, f.off + c * (G::H * G::W) + ky * G::W));
-        return make_uint2(p[0], p[1]);
-    }
-};
-
 // im2col rows of a bf16 NHWC activation, k = (ky, kx, c), c in groups of 8.
 template <class G> struct ConvNHWCRowsK8 {
     static_assert(G::CIN % 8 == 0, "channels in groups of 8");
