@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpaac.so")
 SOURCES = ["layers.hip", "layers_bf16.hip", "small_kernels.hip", "api.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC",
          # packed-fp32 VALU forms are kept off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -17,6 +17,7 @@
 #include <stdint.h>
 #include "internal.h"
 #include <type_traits>
+#include <utility>
 
 namespace paac {
 
@@ -187,19 +188,20 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         }
         okbits[G] = bits;
     };
-    auto lstore = [&](auto stage, int buf) {      // register stage -> LDS buffer
+    // register stage -> LDS buffer, one staging unit (u < A_IT: operand A, else operand B)
+    auto lstore_unit = [&](auto stage, int buf, auto unit) {
         constexpr int G = decltype(stage)::value;
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
+        constexpr int u = decltype(unit)::value;
+        if constexpr (u < A_IT) {
+            constexpr int i = u;
             if (A_F4 % 256 == 0 || tid + i * 256 < A_F4) {
                 float* p = As + buf * A_BUF + a_lds[i];
                 const float4 v = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
                 if (AL::kContig) { p[0] = v.x; p[LDA] = v.y; p[2 * LDA] = v.z; p[3 * LDA] = v.w; }
                 else *reinterpret_cast<float4*>(p) = v;
             }
-        }
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i) {
+        } else {
+            constexpr int i = u - A_IT;
             if (B_F4 % 256 == 0 || tid + i * 256 < B_F4) {
                 float* p = Bs + buf * B_BUF + b_lds[i];
                 const float4 v = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
@@ -207,6 +209,11 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
                 else *reinterpret_cast<float4*>(p) = v;
             }
         }
+    };
+    auto lstore = [&](auto stage, int buf) {
+        [&]<int... U>(std::integer_sequence<int, U...>) {
+            (lstore_unit(stage, buf, std::integral_constant<int, U>()), ...);
+        }(std::make_integer_sequence<int, A_IT + B_IT>());
     };
 
     // a wave with a single output fragment alternates between two accumulators so that consecutive
@@ -227,12 +234,19 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     const int fidx = lane % MF, fk = lane / MF;
     const int a_base = wm * (TM * MF) + fidx, b_base = wn * (TN * MF) + fidx;
 
-    auto compute = [&](int buf) {
+    // The MFMAs of the current tile with the LDS stores of the next tile in between.  An fp32 MFMA
+    // holds the matrix pipe for 64 cycles and a wave issues in order: the conversion and store work
+    // of one staging unit placed after an MFMA runs in its shadow instead of after the last MFMA
+    // (at small batch a wave has its SIMD to itself, nothing else would fill the gap).  The
+    // scheduling barriers keep the compiler from regrouping it.
+    constexpr int NS = BK / MM::KSTEP / T::WK;      // k-steps of this wave: wk, wk + WK, ...
+    constexpr int UNITS = A_IT + B_IT;
+    static_assert(UNITS <= NS, "at most one staging unit per k-step");
+    auto compute_and_store = [&](int buf, auto stage_next, int buf_next) {
         const float* as = As + buf * A_BUF;
         const float* bs = Bs + buf * B_BUF;
         // every LDS read of the tile is issued before the first MFMA: one LDS latency per tile
-        // instead of one per group of MFMAs (a workgroup often has its compute unit to itself)
-        constexpr int NS = BK / MM::KSTEP / T::WK;      // k-steps of this wave: wk, wk + WK, ...
+        // instead of one per group of MFMAs
         float a[NS][TM], b[NS][TN];
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
@@ -242,16 +256,25 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[st][j] = bs[krow * LDB + b_base + j * MF];
         }
+        [&]<int... ST>(std::integer_sequence<int, ST...>) {
+            ([&] {
+                constexpr int st = ST;
 #pragma unroll
-        for (int st = 0; st < NS; ++st) {
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int q = st % KACC;
-                    acc[q][i][j] = MM::mma(a[st][i], b[st][j], acc[q][i][j]);
+                    for (int j = 0; j < TN; ++j) {
+                        const int q = st % KACC;
+                        acc[q][i][j] = MM::mma(a[st][i], b[st][j], acc[q][i][j]);
+                    }
+                // staging unit u goes after k-step u * NS / UNITS (spread evenly, the first right away)
+                constexpr int u = (st * UNITS + NS - 1) / NS;
+                if constexpr (u < UNITS && (u * NS) / UNITS == st) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    lstore_unit(stage_next, buf_next, std::integral_constant<int, u>());
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-        }
+            }(), ...);
+        }(std::make_integer_sequence<int, NS>());
         if constexpr (EP::kColSum) {
             if (mt == 0 && tid < BN) {
 #pragma unroll 8
@@ -267,10 +290,8 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         PAAC_PHASE_BEGIN();
         gload(kt + S, stage);      // stage G was stored to LDS one step ago; past the end: clamped, zeroed
         PAAC_PHASE_END(0);
-        compute(kt & 1);
+        compute_and_store(kt & 1, std::integral_constant<int, GN>(), (kt + 1) & 1);   // after the last tile: zeros nobody reads
         PAAC_PHASE_END(1);
-        lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last tile: zeros nobody reads
-        PAAC_PHASE_END(2);
         __syncthreads();
         PAAC_PHASE_END(3);
     };
@@ -576,7 +597,7 @@ struct EpiBiasRelu {            // out[row][col] = max(v + bias[col], 0)
     static constexpr bool kColSum = false, kAuxEarly = true;
     typedef float Aux;
     float* out; const float* bias; int ldo;
-    __device__ __forceinline__ Aux aux(int, int col, int, bool ok) const { return bias[ok ? col : 0]; }
+    __device__ __forceinline__ Aux aux(int, int col, int, bool) const { return bias[col < ldo ? col : 0]; }   // one load per column
     __device__ __forceinline__ void store(int row, int col, float v, int, Aux b) const {
         out[(size_t)row * ldo + col] = fmaxf(v + b, 0.f);
     }

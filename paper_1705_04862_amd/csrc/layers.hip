@@ -31,11 +31,13 @@ template <> struct TileForN<64> { typedef T64x64 big; typedef T32x64 mid; typede
 // Workgroups are dispatched at a finite rate (on the order of 100 per microsecond), so a launch of
 // thousands of small workgroups is bound by dispatch: take the largest tile that still gives about
 // one workgroup per compute unit (256 of them).
+#include <cstdlib>
+static const int kMinWgs = getenv("PAAC_MIN_WGS") ? atoi(getenv("PAAC_MIN_WGS")) : 192;   // experiment knob
 template <class TBig, class TMid, class TSmall, class AL, class BL, class EP>
 static hipError_t launch_auto(hipStream_t s, const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int z) {
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * z; };
-    if (wgs(TBig::BM, TBig::BN) >= 192) return launch_gemm<TBig>(s, al, bl, ep, M, N, K, z, 0);
-    if (wgs(TMid::BM, TMid::BN) >= 192) return launch_gemm<TMid>(s, al, bl, ep, M, N, K, z, 0);
+    if (wgs(TBig::BM, TBig::BN) >= kMinWgs) return launch_gemm<TBig>(s, al, bl, ep, M, N, K, z, 0);
+    if (wgs(TMid::BM, TMid::BN) >= kMinWgs) return launch_gemm<TMid>(s, al, bl, ep, M, N, K, z, 0);
     return launch_gemm<TSmall>(s, al, bl, ep, M, N, K, z, 0);
 }
 
@@ -191,8 +193,8 @@ static hipError_t conv_bwd_t(hipStream_t s, const float* act_in, const float* dy
     EpiPartial<true> wep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
     const auto wcall = make_call<typename TileForN<G::COUT>::wg>(wal, wbl, wep, G::KK, G::COUT, R, sp.n, sp.k_per);
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((G::CIN + bn - 1) / bn) * z; };
-    if (wgs(TS::big::BM, TS::big::BN) >= 192) return conv_bwd_pair<typename TS::big, G>(s, dy, W, act_in, dx, ns, wcall);
-    if (wgs(TS::mid::BM, TS::mid::BN) >= 192) return conv_bwd_pair<typename TS::mid, G>(s, dy, W, act_in, dx, ns, wcall);
+    if (wgs(TS::big::BM, TS::big::BN) >= kMinWgs) return conv_bwd_pair<typename TS::big, G>(s, dy, W, act_in, dx, ns, wcall);
+    if (wgs(TS::mid::BM, TS::mid::BN) >= kMinWgs) return conv_bwd_pair<typename TS::mid, G>(s, dy, W, act_in, dx, ns, wcall);
     return conv_bwd_pair<typename TS::small, G>(s, dy, W, act_in, dx, ns, wcall);
 }
 
@@ -257,7 +259,7 @@ hipError_t fc_bwd(hipStream_t s, int arch, const float* x, const float* dh, cons
     DenseRowsK al{dh, ns, fc};
     DenseRowsK bl{W, flat, fc};
     EpiDenseMask ep{dx, x, flat};
-    if ((long)((ns + 63) / 64) * (flat / 64) >= 192) return launch_pair(s, make_call<T64x64>(al, bl, ep, ns, flat, fc, 1, 0), wcall);
+    if ((long)((ns + 63) / 64) * (flat / 64) >= kMinWgs) return launch_pair(s, make_call<T64x64>(al, bl, ep, ns, flat, fc, 1, 0), wcall);
     return launch_pair(s, make_call<T32x64>(al, bl, ep, ns, flat, fc, 1, 0), wcall);
 }
 
