@@ -5,7 +5,7 @@
 //
 //   C[m][n] = sum_k A(m,k) * B(k,n)          m < M, n < N, k in this workgroup's k-range
 //
-// A workgroup of 256 threads (4 wavefronts of 64) owns a BM x BN tile.  Both operands are staged
+// A workgroup of 4 (or 8) wavefronts of 64 owns a BM x BN tile.  Both operands are staged
 // through LDS in k-major order (As[k][m], Bs[k][n]) so that the 32 lanes that feed one
 // MFMA operand read consecutive words: bank-conflict free without swizzling.  An operand whose
 // global layout is contiguous along k ("kContig") is transposed on its way into LDS; an operand
@@ -59,9 +59,10 @@ template <> struct Mma<32> {
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int WK_, int MF_, int STAGES_ = 3>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, WK = WK_, MF = MF_, STAGES = STAGES_;
+    static constexpr int NT = WM * WN * WK * 64;             // threads of the workgroup
     static_assert(STAGES >= 2 && STAGES <= 4, "register prefetch depth");
     static constexpr int TM = BM / (WM * MF), TN = BN / (WN * MF);
-    static_assert(WM * WN * WK == 4, "four wavefronts per workgroup");
+    static_assert(WM * WN * WK == 4 || WM * WN * WK == 8, "four or eight wavefronts per workgroup");
     static_assert((BK / Mma<MF>::KSTEP) % WK == 0, "k-steps must divide among the k-waves");
     static_assert(TM * WM * MF == BM && TN * WN * MF == BN, "tile must be whole fragments");
     static_assert(BK % 4 == 0 && BK % Mma<MF>::KSTEP == 0, "BK granularity");
@@ -106,7 +107,8 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     constexpr int LDA = AL::kContig ? BM + 1 : BM + 4;
     constexpr int LDB = BL::kContig ? BN + 1 : BN + 4;
     constexpr int A_F4 = BM * BK / 4, B_F4 = BN * BK / 4;
-    constexpr int A_IT = (A_F4 + 255) / 256, B_IT = (B_F4 + 255) / 256;
+    constexpr int NT = T::NT;
+    constexpr int A_IT = (A_F4 + NT - 1) / NT, B_IT = (B_F4 + NT - 1) / NT;
 
     constexpr int A_BUF = BK * LDA, B_BUF = BK * LDB;      // floats per LDS buffer (multiples of 4)
     static_assert(2 * A_BUF + 2 * B_BUF == gemm_smem_floats<T, AL, BL>(), "LDS size");
@@ -129,7 +131,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     int a_var[A_IT], a_lds[A_IT], b_var[B_IT], b_lds[B_IT];
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-        const int f = tid + i * 256;
+        const int f = tid + i * NT;
         if (AL::kContig) {
             // consecutive lanes take consecutive k of a row, or (kRowFast) consecutive rows at one k:
             // whichever walks contiguous memory for this operand
@@ -146,7 +148,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
-        const int f = tid + i * 256;
+        const int f = tid + i * NT;
         if (BL::kContig) {
             const int kq = f % (BK / 4), col = f / (BK / 4);
             bfix[i] = bl.prep(n0 + col, z);
@@ -176,14 +178,14 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         for (int i = 0; i < A_IT; ++i) {
             const int kk = kb + a_var[i];
             bool ok;
-            areg[G][i] = al.load(afix[i], kk, (A_F4 % 256 == 0 || tid + i * 256 < A_F4) && kk < k_end, ok);
+            areg[G][i] = al.load(afix[i], kk, (A_F4 % NT == 0 || tid + i * NT < A_F4) && kk < k_end, ok);
             bits |= ok ? (1u << i) : 0u;
         }
 #pragma unroll
         for (int i = 0; i < B_IT; ++i) {
             const int kk = kb + b_var[i];
             bool ok;
-            breg[G][i] = bl.load(bfix[i], kk, (B_F4 % 256 == 0 || tid + i * 256 < B_F4) && kk < k_end, ok);
+            breg[G][i] = bl.load(bfix[i], kk, (B_F4 % NT == 0 || tid + i * NT < B_F4) && kk < k_end, ok);
             bits |= ok ? (1u << (16 + i)) : 0u;
         }
         okbits[G] = bits;
@@ -194,7 +196,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         constexpr int u = decltype(unit)::value;
         if constexpr (u < A_IT) {
             constexpr int i = u;
-            if (A_F4 % 256 == 0 || tid + i * 256 < A_F4) {
+            if (A_F4 % NT == 0 || tid + i * NT < A_F4) {
                 float* p = As + buf * A_BUF + a_lds[i];
                 const float4 v = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
                 if (AL::kContig) { p[0] = v.x; p[LDA] = v.y; p[2 * LDA] = v.z; p[3 * LDA] = v.w; }
@@ -202,7 +204,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
             }
         } else {
             constexpr int i = u - A_IT;
-            if (B_F4 % 256 == 0 || tid + i * 256 < B_F4) {
+            if (B_F4 % NT == 0 || tid + i * NT < B_F4) {
                 float* p = Bs + buf * B_BUF + b_lds[i];
                 const float4 v = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
                 if (BL::kContig) { p[0] = v.x; p[LDB] = v.y; p[2 * LDB] = v.z; p[3 * LDB] = v.w; }
@@ -643,7 +645,7 @@ struct EpiDenseMask {           // out[row][col] = act[row][col] > 0 ? v : 0
 
 // ----------------------------------------------------------------------------------------------
 template <class T, class AL, class BL, class EP>
-__global__ __launch_bounds__(256) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
+__global__ __launch_bounds__(T::NT) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
                                                    int K, int k_per_split, int m_tiles) {
     __shared__ __attribute__((aligned(16))) float smem[gemm_smem_floats<T, AL, BL>()];
     gemm_body<T, AL, BL, EP>(al, bl, ep, M, N, K, k_per_split, m_tiles, blockIdx.x, blockIdx.y, smem);
@@ -668,6 +670,7 @@ inline GemmCall<T, AL, BL, EP> make_call(const AL& al, const BL& bl, const EP& e
 // latencies; side by side they overlap them.
 template <class C1, class C2>
 __global__ __launch_bounds__(256) void gemm_pair_kernel(const C1 a, const C2 b) {
+    static_assert(C1::T::NT == 256 && C2::T::NT == 256, "both halves run on four wavefronts");
     constexpr int S1 = gemm_smem_floats<typename C1::T, typename C1::AL, typename C1::BL>();
     constexpr int S2 = gemm_smem_floats<typename C2::T, typename C2::AL, typename C2::BL>();
     __shared__ __attribute__((aligned(16))) float smem[S1 > S2 ? S1 : S2];
@@ -696,7 +699,7 @@ inline hipError_t launch_gemm(hipStream_t s, const AL& al, const BL& bl, const E
     const int m_tiles = (M + T::BM - 1) / T::BM, n_tiles = (N + T::BN - 1) / T::BN;
     if (M <= 0 || N <= 0 || z_count <= 0) return hipErrorInvalidValue;
     dim3 grid(m_tiles * n_tiles, z_count, 1);
-    launch_k((gemm_kernel<T, AL, BL, EP>), grid, dim3(256), s, al, bl, ep, M, N, K, k_per_split, m_tiles);
+    launch_k((gemm_kernel<T, AL, BL, EP>), grid, dim3(T::NT), s, al, bl, ep, M, N, K, k_per_split, m_tiles);
     return hipGetLastError();
 }
 

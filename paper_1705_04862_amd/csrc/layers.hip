@@ -19,20 +19,35 @@ typedef Tile<64, 32, 64, 2, 1, 2, 32, 4> T64x32;
 typedef Tile<32, 32, 64, 1, 1, 4, 32, 4> T32x32;
 typedef Tile<64, 64, 32, 2, 2, 1, 32, 3> T64x64;
 typedef Tile<32, 64, 64, 1, 2, 2, 32, 4> T32x64;
+// eight wavefronts: the k-steps of a tile are split four ways, so a wave's chain of 64-cycle fp32
+// MFMAs is half as long as in the four-wave tile of the same shape, without doubling the number of
+// workgroups the dispatcher has to start (the batch-of-32 launches are bound by exactly these two).
+// Measured at n_e = 32: first layer 10.3 -> 9.2 us; a 32x64 eight-wave tile for the 64-wide layers
+// (half the workgroups of the 32x32 tile) was slower, 8.2 -> 9.7 us, and is not used.
+typedef Tile<64, 32, 64, 2, 1, 4, 32, 4> T64x32w8;
 
-// big / middle / small tile per output width; wg = tile of the weight-gradient GEMMs.  A 16-wide
+// big / middle / small tile per output width for single launches, pbig / pmid / psmall for launches
+// that pair two GEMMs (four waves each); wg = tile of the weight-gradient GEMMs.  A 16-wide
 // output (first layer of arch_nips) runs on the 32-wide tiles: the upper 16 columns load zeros and
 // are not stored (these launches are bound by latency, not by the matrix pipes).
 template <int N> struct TileForN;
-template <> struct TileForN<16> { typedef T128x32 big; typedef T64x32 mid; typedef T32x32 small; typedef T64x32 wg; };
-template <> struct TileForN<32> { typedef T128x32 big; typedef T64x32 mid; typedef T32x32 small; typedef T64x32 wg; };
-template <> struct TileForN<64> { typedef T64x64 big; typedef T32x64 mid; typedef T32x32 small; typedef T64x64 wg; };
+template <> struct TileForN<16> {
+    typedef T128x32 big; typedef T64x32w8 mid; typedef T32x32 small; typedef T64x32 wg;
+    typedef T128x32 pbig; typedef T64x32 pmid; typedef T32x32 psmall;
+};
+template <> struct TileForN<32> {
+    typedef T128x32 big; typedef T64x32w8 mid; typedef T32x32 small; typedef T64x32 wg;
+    typedef T128x32 pbig; typedef T64x32 pmid; typedef T32x32 psmall;
+};
+template <> struct TileForN<64> {
+    typedef T64x64 big; typedef T32x64 mid; typedef T32x32 small; typedef T64x64 wg;
+    typedef T64x64 pbig; typedef T32x64 pmid; typedef T32x32 psmall;
+};
 
 // Workgroups are dispatched at a finite rate (on the order of 100 per microsecond), so a launch of
 // thousands of small workgroups is bound by dispatch: take the largest tile that still gives about
 // one workgroup per compute unit (256 of them).
-#include <cstdlib>
-static const int kMinWgs = getenv("PAAC_MIN_WGS") ? atoi(getenv("PAAC_MIN_WGS")) : 192;   // experiment knob
+static const int kMinWgs = 192;
 template <class TBig, class TMid, class TSmall, class AL, class BL, class EP>
 static hipError_t launch_auto(hipStream_t s, const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int z) {
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * z; };
@@ -193,9 +208,9 @@ static hipError_t conv_bwd_t(hipStream_t s, const float* act_in, const float* dy
     EpiPartial<true> wep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
     const auto wcall = make_call<typename TileForN<G::COUT>::wg>(wal, wbl, wep, G::KK, G::COUT, R, sp.n, sp.k_per);
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((G::CIN + bn - 1) / bn) * z; };
-    if (wgs(TS::big::BM, TS::big::BN) >= kMinWgs) return conv_bwd_pair<typename TS::big, G>(s, dy, W, act_in, dx, ns, wcall);
-    if (wgs(TS::mid::BM, TS::mid::BN) >= kMinWgs) return conv_bwd_pair<typename TS::mid, G>(s, dy, W, act_in, dx, ns, wcall);
-    return conv_bwd_pair<typename TS::small, G>(s, dy, W, act_in, dx, ns, wcall);
+    if (wgs(TS::pbig::BM, TS::pbig::BN) >= kMinWgs) return conv_bwd_pair<typename TS::pbig, G>(s, dy, W, act_in, dx, ns, wcall);
+    if (wgs(TS::pmid::BM, TS::pmid::BN) >= kMinWgs) return conv_bwd_pair<typename TS::pmid, G>(s, dy, W, act_in, dx, ns, wcall);
+    return conv_bwd_pair<typename TS::psmall, G>(s, dy, W, act_in, dx, ns, wcall);
 }
 
 hipError_t conv_bwd(hipStream_t s, int arch, int layer, const float* act_in, const float* dy, const float* W, float* dx,
