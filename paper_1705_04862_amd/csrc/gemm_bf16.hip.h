@@ -241,24 +241,32 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             }
         }
     };
-    auto lstore = [&](auto stage, int buf) __attribute__((always_inline)) {
+    // register stage -> LDS buffer, one staging unit (u < A_IT: operand A, else operand B)
+    auto lstore_unit = [&](auto stage, int buf, auto unit) __attribute__((always_inline)) {
         constexpr int G = decltype(stage)::value;
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i)
+        constexpr int u = decltype(unit)::value;
+        if constexpr (u < A_IT) {
+            constexpr int i = u;
             if (A_U % 256 == 0 || tid + i * 256 < A_U) {
                 uint4 r[NL];
 #pragma unroll
                 for (int q = 0; q < NL; ++q) r[q] = AL::finish(areg[G][i][q], (okbits[G] >> (i * NL + q)) & 1u);
                 put(As + buf * A_BUF + a_lds[i], r);
             }
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i)
+        } else {
+            constexpr int i = u - A_IT;
             if (B_U % 256 == 0 || tid + i * 256 < B_U) {
                 uint4 r[NL];
 #pragma unroll
                 for (int q = 0; q < NL; ++q) r[q] = BL::finish(breg[G][i][q], (okbits[G] >> ((A_IT + i) * NL + q)) & 1u);
                 put(Bs + buf * B_BUF + b_lds[i], r);
             }
+        }
+    };
+    auto lstore = [&](auto stage, int buf) __attribute__((always_inline)) {
+        [&]<int... U>(std::integer_sequence<int, U...>) {
+            (lstore_unit(stage, buf, std::integral_constant<int, U>()), ...);
+        }(std::make_integer_sequence<int, A_IT + B_IT>());
     };
 
     f32x16 acc[TM][TN];
@@ -275,28 +283,44 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
 
     const int fidx = lane & 31, kg = lane >> 5;
     int tile_par = 0;
-    auto compute = [&](int buf) __attribute__((always_inline)) {
+    // MFMAs of the current k tile with the LDS stores of the next one spread between the four
+    // 16-deep sub-steps (the stores' conversion / permute work runs in the shadow of the MFMAs)
+    constexpr int UNITS = A_IT + B_IT, KS = BK / 16;
+    auto compute = [&](int buf, auto stage_next, int buf_next) __attribute__((always_inline)) {
         const bf16_t* as = As + buf * A_BUF;
         const bf16_t* bs = Bs + buf * B_BUF;
+        bf16x8 a[KS][TM], b[KS][TN];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[TM], b[TN];
+        for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * TM * 32 + i * 32 + fidx;
-                a[i] = *reinterpret_cast<const bf16x8*>(as + row * LD + ks * 16 + kg * 8);
+                a[ks][i] = *reinterpret_cast<const bf16x8*>(as + row * LD + ks * 16 + kg * 8);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = wn * TN * 32 + j * 32 + fidx;
-                b[j] = *reinterpret_cast<const bf16x8*>(bs + row * LD + ks * 16 + kg * 8);
+                b[ks][j] = *reinterpret_cast<const bf16x8*>(bs + row * LD + ks * 16 + kg * 8);
             }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+        [&]<int... KSI>(std::integer_sequence<int, KSI...>) {
+            ([&] {
+                constexpr int ks = KSI;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+                constexpr int u0 = ks * UNITS / KS, u1 = (ks + 1) * UNITS / KS;
+                if constexpr (u1 > u0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    [&]<int... U>(std::integer_sequence<int, U...>) {
+                        (lstore_unit(stage_next, buf_next, std::integral_constant<int, u0 + U>()), ...);
+                    }(std::make_integer_sequence<int, u1 - u0>());
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }(), ...);
+        }(std::make_integer_sequence<int, KS>());
         if constexpr (EP::kColSum) {          // bias gradient: sums of the B tile's rows (a row holds one column's k)
             if (c_tile % m_tiles == 0 && tid < BN) {
 #pragma unroll
@@ -363,8 +387,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         constexpr int GN = (G + 1) % S;
         gload(kt + S, stage);
         if (ATAB && tid < BK) fill_tab(kt + S + 1, tid);          // read by the next step's gload, after this step's barrier
-        compute(kt & 1);
-        lstore(std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last k tile: zeros nobody reads
+        compute(kt & 1, std::integral_constant<int, GN>(), (kt + 1) & 1);      // after the last k tile: zeros nobody reads
         __syncthreads();
     };
     for (; c_tile < tiles; c_tile += tile_stride, tile_par ^= 1) {
