@@ -78,9 +78,9 @@ struct TileB {
 // to drain the whole pipeline; the refill latency is covered by the other workgroups of the CU.
 // Epilogue flavours: the fp32 core's epilogues take (row, col); epilogues declared with kEntry take a
 // per-row entry (an element offset) computed by row_entry(row, z), optionally through the LDS table.
-template <class EP, class = void> struct EpiTraits { static constexpr bool kEntry = false, kRowTable = false; };
+template <class EP, class = void> struct EpiTraits { static constexpr bool kEntry = false, kRowTable = false, kEarly = false; };
 template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
-    static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
+    static constexpr bool kEntry = true, kRowTable = EP::kRowTable, kEarly = EP::kEarly;
 };
 // KRow loaders whose address needs divisions per reduction index (im2col of an output position)
 // declare kRowTab: the kernel then keeps the per-index offsets of the coming k tiles in a small LDS
@@ -331,9 +331,48 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             }
         }
     };
+    // Entry-type epilogues: row entries and auxiliary operands (bias, ReLU mask) of the tile are loaded
+    // right after the tile's first barrier (the row table is complete then) and arrive while the k loop
+    // runs, so the epilogue does not begin with a memory round trip.
+    constexpr bool ENTRY = EpiTraits<EP>::kEntry;
+    constexpr bool EARLY = EpiTraits<EP>::kEarly;                 // per epilogue: 16 live registers per fragment
+    typename EP::Aux eaux[ENTRY ? TM : 1][ENTRY ? TN : 1][ENTRY ? 16 : 1];
+    int ecoff[ENTRY ? TN : 1];
+    auto row_entries = [&](int i, int (&ent)[16]) __attribute__((always_inline)) {
+        if constexpr (ENTRY) {
+            const int m0 = (c_tile % m_tiles) * BM;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                if constexpr (EpiTraits<EP>::kRowTable) ent[r] = rowtab[tile_par * BM + lr];
+                else ent[r] = ep.row_entry(m0 + lr < M ? m0 + lr : 0, z);
+            }
+        }
+    };
+    auto load_aux = [&]() __attribute__((always_inline)) {
+        if constexpr (ENTRY) {
+            const int nt = c_tile / m_tiles;
+            const int n0 = nt * BN;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
+                ecoff[j] = EpiColMap<EP>::off(ep, col < N ? col : 0);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                int ent[16];
+                row_entries(i, ent);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) eaux[i][j][r] = ep.aux(ent[r], ecoff[j]);
+            }
+        }
+    };
     auto epilogue = [&]() __attribute__((always_inline)) {
         const int mt = c_tile % m_tiles, nt = c_tile / m_tiles;
         const int m0 = mt * BM, n0 = nt * BN;
+        if constexpr (ENTRY && !EARLY) load_aux();
         if constexpr (EP::kColSum) {
             if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
             colsum = 0.f;
@@ -346,24 +385,15 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
                 const bool full = m0 + BM <= M && n0 + BN <= N;     // interior tile (workgroup-uniform): no per-store test
                 if constexpr (EpiTraits<EP>::kEntry) {
                     int ent[16];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int lr = wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                        if constexpr (EpiTraits<EP>::kRowTable) ent[r] = rowtab[tile_par * BM + lr];
-                        else ent[r] = ep.row_entry(m0 + lr < M ? m0 + lr : 0, z);
-                    }
-                    const int coff = EpiColMap<EP>::off(ep, col < N ? col : 0);
-                    typename EP::Aux aux[16];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) aux[r] = ep.aux(ent[r], coff);
+                    row_entries(i, ent);                 // again (a table read or a multiply): cheaper than 16 live registers
                     if (full) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) ep.store(ent[r], coff, acc[i][j][r], aux[r]);
+                        for (int r = 0; r < 16; ++r) ep.store(ent[r], ecoff[j], acc[i][j][r], eaux[i][j][r]);
                     } else {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                            if (row < M && col < N) ep.store(ent[r], coff, acc[i][j][r], aux[r]);
+                            if (row < M && col < N) ep.store(ent[r], ecoff[j], acc[i][j][r], eaux[i][j][r]);
                         }
                     }
                 } else {
@@ -407,6 +437,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
         lstore(std::integral_constant<int, 0>(), 0);
         __syncthreads();
+        if constexpr (EARLY) load_aux();
         // whole rounds of S steps without a branch, the remainder after the loop (see gemm_body)
         int kt = 0;
         for (int q = nk / S; q > 0; --q, kt += S) {
@@ -613,7 +644,7 @@ struct DenseKCols8 {            // element (k, col) = base[k*ld + col]
 // ----------------------------------------------------------------------------------------------
 // Epilogues with bf16 outputs (EpiPartial of the fp32 core is reused for fp32 partial sums)
 struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col], 0))
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = false;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kEarly = true;
     typedef float Aux;
     bf16_t* out; const float* bias; int ldo; float scale;
     __device__ __forceinline__ int row_entry(int row, int) const { return row * ldo; }
@@ -641,7 +672,7 @@ __device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) !
 // Data gradient output: row = (n, yy, xx) block of ST x ST input positions, column = (py, px, ci);
 // element goes to dx[n][yy*ST + py][xx*ST + px][ci], times ReLU'(act) at the same place.
 template <class G> struct EpiDgradMaskB {
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true, kEarly = true;
     typedef bf16_t Aux;
     bf16_t* dx; const bf16_t* act;
     __device__ __forceinline__ int row_entry(int row, int) const {
@@ -659,7 +690,7 @@ template <class G> struct EpiDgradMaskB {
 };
 
 struct EpiDenseMaskB {
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = false;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kEarly = false;      // register budget
     typedef bf16_t Aux;
     bf16_t* out; const bf16_t* act; int ld;
     __device__ __forceinline__ int row_entry(int row, int) const { return row * ld; }
