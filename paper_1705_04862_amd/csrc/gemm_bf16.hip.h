@@ -29,6 +29,14 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float dot2_ones(unsigned pair, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
 }
+__device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) != 0 && !(a & 0x8000u); }
+// keep the bf16 halves of v whose counterpart in a is a positive number
+__device__ __forceinline__ unsigned mask2(unsigned v, unsigned a) {
+    const unsigned lo = bf16_positive((bf16_t)(a & 0xffffu)) ? 0x0000ffffu : 0u;
+    const unsigned hi = bf16_positive((bf16_t)(a >> 16)) ? 0xffff0000u : 0u;
+    return v & (lo | hi);
+}
+
 __device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
 __device__ __forceinline__ uint4 keep_if_u4(bool ok, uint4 v) {
     return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
@@ -76,11 +84,12 @@ struct TileB {
 // that rate).  The load pipeline is refilled per tile on purpose: global stores inside the k loop
 // would share the wave's memory counter with the prefetched loads, and every wait would then have
 // to drain the whole pipeline; the refill latency is covered by the other workgroups of the CU.
-// Epilogue flavours: the fp32 core's epilogues take (row, col); epilogues declared with kEntry take a
-// per-row entry (an element offset) computed by row_entry(row, z), optionally through the LDS table.
-template <class EP, class = void> struct EpiTraits { static constexpr bool kEntry = false, kRowTable = false, kEarly = false; };
+// Epilogue flavours: the fp32 core's epilogues take (row, col) and store from the accumulator layout;
+// epilogues declared with kEntry produce a bf16 tile that is addressed by a per-row entry (an element
+// offset from row_entry(row, z), optionally through the LDS row table) plus a column offset.
+template <class EP, class = void> struct EpiTraits { static constexpr bool kEntry = false, kRowTable = false; };
 template <class EP> struct EpiTraits<EP, std::enable_if_t<EP::kEntry>> {
-    static constexpr bool kEntry = true, kRowTable = EP::kRowTable, kEarly = EP::kEarly;
+    static constexpr bool kEntry = true, kRowTable = EP::kRowTable;
 };
 // KRow loaders whose address needs divisions per reduction index (im2col of an output position)
 // declare kRowTab: the kernel then keeps the per-index offsets of the coming k tiles in a small LDS
@@ -331,48 +340,44 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             }
         }
     };
-    // Entry-type epilogues: row entries and auxiliary operands (bias, ReLU mask) of the tile are loaded
-    // right after the tile's first barrier (the row table is complete then) and arrive while the k loop
-    // runs, so the epilogue does not begin with a memory round trip.
-    constexpr bool ENTRY = EpiTraits<EP>::kEntry;
-    constexpr bool EARLY = EpiTraits<EP>::kEarly;                 // per epilogue: 16 live registers per fragment
-    typename EP::Aux eaux[ENTRY ? TM : 1][ENTRY ? TN : 1][ENTRY ? 16 : 1];
-    int ecoff[ENTRY ? TN : 1];
-    auto row_entries = [&](int i, int (&ent)[16]) __attribute__((always_inline)) {
-        if constexpr (ENTRY) {
-            const int m0 = (c_tile % m_tiles) * BM;
+    // Epilogues with a bf16 output tile (kEntry): the finished tile goes through LDS and leaves as
+    // 16-byte stores, 8 consecutive columns per thread, instead of 2-byte stores straight from the
+    // accumulator layout (one eighth of the global memory instructions; the ReLU mask is read with
+    // 16-byte loads as well).  Addresses and mask are fetched right after the tile's first barrier
+    // (the row table is complete then) and arrive while the k loop runs.
+    constexpr bool LOUT = EpiTraits<EP>::kEntry;
+    constexpr int LDO = BN + 8, CPR = BN / 8, C_IT = LOUT ? BM * CPR / 256 : 1;
+    static_assert(!LOUT || (BM * CPR) % 256 == 0, "whole chunks per thread");
+    __shared__ __attribute__((aligned(16))) bf16_t outT[LOUT ? BM * LDO : 8];
+    int cent[C_IT];
+    uint4 caux[C_IT];
+    float ebias[TN];
+    auto tile_begin = [&]() __attribute__((always_inline)) {
+        if constexpr (LOUT) {
+            const int m0 = (c_tile % m_tiles) * BM, n0 = (c_tile / m_tiles) * BN;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                if constexpr (EpiTraits<EP>::kRowTable) ent[r] = rowtab[tile_par * BM + lr];
-                else ent[r] = ep.row_entry(m0 + lr < M ? m0 + lr : 0, z);
+            for (int c = 0; c < C_IT; ++c) {
+                const int ch = tid + c * 256, lr = ch / CPR, c8 = ch % CPR;
+                const int row = m0 + lr, col = n0 + c8 * 8;
+                const bool ok = row < M && col < N;
+                int base;
+                if constexpr (EpiTraits<EP>::kRowTable) base = rowtab[tile_par * BM + lr];
+                else base = ep.row_entry(ok ? row : 0, z);
+                cent[c] = ok ? base + EpiColMap<EP>::off(ep, col) : -1;
+                if constexpr (EP::kMask) caux[c] = *reinterpret_cast<const uint4*>(ep.mask() + (cent[c] >= 0 ? cent[c] : 0));
             }
-        }
-    };
-    auto load_aux = [&]() __attribute__((always_inline)) {
-        if constexpr (ENTRY) {
-            const int nt = c_tile / m_tiles;
-            const int n0 = nt * BN;
+            if constexpr (EP::kBias) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
-                ecoff[j] = EpiColMap<EP>::off(ep, col < N ? col : 0);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int ent[16];
-                row_entries(i, ent);
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) eaux[i][j][r] = ep.aux(ent[r], ecoff[j]);
+                for (int j = 0; j < TN; ++j) {
+                    const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
+                    ebias[j] = ep.bias[col < N ? col : 0];
+                }
             }
         }
     };
     auto epilogue = [&]() __attribute__((always_inline)) {
         const int mt = c_tile % m_tiles, nt = c_tile / m_tiles;
         const int m0 = mt * BM, n0 = nt * BN;
-        if constexpr (ENTRY && !EARLY) load_aux();
         if constexpr (EP::kColSum) {
             if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
             colsum = 0.f;
@@ -383,18 +388,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
                 const bool full = m0 + BM <= M && n0 + BN <= N;     // interior tile (workgroup-uniform): no per-store test
-                if constexpr (EpiTraits<EP>::kEntry) {
-                    int ent[16];
-                    row_entries(i, ent);                 // again (a table read or a multiply): cheaper than 16 live registers
-                    if (full) {
+                if constexpr (LOUT) {
+                    const int lc = wn * (TN * 32) + j * 32 + Mma<32>::col(lane);
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) ep.store(ent[r], ecoff[j], acc[i][j][r], eaux[i][j][r]);
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = m0 + wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
-                            if (row < M && col < N) ep.store(ent[r], ecoff[j], acc[i][j][r], eaux[i][j][r]);
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        const int lr = wm * (TM * 32) + i * 32 + Mma<32>::row(r, lane);
+                        outT[lr * LDO + lc] = ep.value(acc[i][j][r], EP::kBias ? ebias[j] : 0.f);
                     }
                 } else {
                     typename EP::Aux aux[16];
@@ -410,6 +409,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
                     }
                 }
             }
+        if constexpr (LOUT) {
+            __syncthreads();
+#pragma unroll
+            for (int c = 0; c < C_IT; ++c) {
+                const int ch = tid + c * 256, lr = ch / CPR, c8 = ch % CPR;
+                uint4 v = *reinterpret_cast<const uint4*>(outT + lr * LDO + c8 * 8);
+                if constexpr (EP::kMask) {
+                    v.x = mask2(v.x, caux[c].x); v.y = mask2(v.y, caux[c].y); v.z = mask2(v.z, caux[c].z); v.w = mask2(v.w, caux[c].w);
+                }
+                if (cent[c] >= 0) *reinterpret_cast<uint4*>(ep.dst() + cent[c]) = v;
+            }
+        }
         zero_acc();
     };
     auto step = [&](int kt, auto stage) __attribute__((always_inline)) {
@@ -437,7 +448,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
         lstore(std::integral_constant<int, 0>(), 0);
         __syncthreads();
-        if constexpr (EARLY) load_aux();
+        tile_begin();
         // whole rounds of S steps without a branch, the remainder after the loop (see gemm_body)
         int kt = 0;
         for (int q = nk / S; q > 0; --q, kt += S) {
@@ -644,14 +655,12 @@ struct DenseKCols8 {            // element (k, col) = base[k*ld + col]
 // ----------------------------------------------------------------------------------------------
 // Epilogues with bf16 outputs (EpiPartial of the fp32 core is reused for fp32 partial sums)
 struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col], 0))
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kEarly = true;
-    typedef float Aux;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kMask = false, kBias = true;
     bf16_t* out; const float* bias; int ldo; float scale;
     __device__ __forceinline__ int row_entry(int row, int) const { return row * ldo; }
-    __device__ __forceinline__ Aux aux(int, int col) const { return bias[col]; }
-    __device__ __forceinline__ void store(int ent, int col, float v, Aux b) const {
-        out[(size_t)(unsigned)(ent + col)] = f2bf(fmaxf(v * scale + b, 0.f));
-    }
+    __device__ __forceinline__ bf16_t value(float v, float b) const { return f2bf(fmaxf(v * scale + b, 0.f)); }
+    __device__ __forceinline__ bf16_t* dst() const { return out; }
+    __device__ __forceinline__ const bf16_t* mask() const { return nullptr; }
 };
 
 struct EpiPartialScaled {       // out[z][row][col] = scale * v, column sums of B unscaled
@@ -667,14 +676,12 @@ struct EpiPartialScaled {       // out[z][row][col] = scale * v, column sums of 
     }
 };
 
-__device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) != 0 && !(a & 0x8000u); }
-
 // Data gradient output: row = (n, yy, xx) block of ST x ST input positions, column = (py, px, ci);
 // element goes to dx[n][yy*ST + py][xx*ST + px][ci], times ReLU'(act) at the same place.
 template <class G> struct EpiDgradMaskB {
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true, kEarly = true;
-    typedef bf16_t Aux;
-    bf16_t* dx; const bf16_t* act;
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true, kMask = true, kBias = false;
+    static_assert(G::CIN % 8 == 0, "eight consecutive columns stay inside one parity class");
+    bf16_t* dx; const bf16_t* act; const float* bias;
     __device__ __forceinline__ int row_entry(int row, int) const {
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
         return ((n * G::H + yy * G::ST) * G::W + xx * G::ST) * G::CIN;
@@ -683,21 +690,18 @@ template <class G> struct EpiDgradMaskB {
         const int cls = col / G::CIN, ci = col % G::CIN;
         return ((cls / G::ST) * G::W + cls % G::ST) * G::CIN + ci;
     }
-    __device__ __forceinline__ Aux aux(int ent, int coff) const { return act[(size_t)(unsigned)(ent + coff)]; }
-    __device__ __forceinline__ void store(int ent, int coff, float v, Aux a) const {
-        dx[(size_t)(unsigned)(ent + coff)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
-    }
+    __device__ __forceinline__ bf16_t value(float v, float) const { return f2bf(v); }
+    __device__ __forceinline__ bf16_t* dst() const { return dx; }
+    __device__ __forceinline__ const bf16_t* mask() const { return act; }
 };
 
-struct EpiDenseMaskB {
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kEarly = false;      // register budget
-    typedef bf16_t Aux;
-    bf16_t* out; const bf16_t* act; int ld;
+struct EpiDenseMaskB {          // out[row][col] = v * 1[act[row][col] > 0]
+    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kMask = true, kBias = false;
+    bf16_t* out; const bf16_t* act; int ld; const float* bias;
     __device__ __forceinline__ int row_entry(int row, int) const { return row * ld; }
-    __device__ __forceinline__ Aux aux(int ent, int col) const { return act[(size_t)(unsigned)(ent + col)]; }
-    __device__ __forceinline__ void store(int ent, int col, float v, Aux a) const {
-        out[(size_t)(unsigned)(ent + col)] = bf16_positive(a) ? f2bf(v) : (bf16_t)0;
-    }
+    __device__ __forceinline__ bf16_t value(float v, float) const { return f2bf(v); }
+    __device__ __forceinline__ bf16_t* dst() const { return out; }
+    __device__ __forceinline__ const bf16_t* mask() const { return act; }
 };
 
 // Grid: every k-split (grid y) gets min(tiles, resident workgroups of the whole chip) workgroups.

@@ -52,7 +52,7 @@ static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd
     const int M = ns * G::HC * G::WC;                // blocks of ST x ST input positions
     DgradGatherRowsK8<G> al{dy, M};
     DgradWeightRowsK8<G> bl{Wd};
-    EpiDgradMaskB<G> ep{dx, act_in};
+    EpiDgradMaskB<G> ep{dx, act_in, nullptr};
     return launch_gemm_bf16<B128x64>(s, al, bl, ep, M, G::ST * G::ST * G::CIN, G::KD, 1, 0);
 }
 
@@ -127,7 +127,7 @@ hipError_t fc_dgrad_bf16(hipStream_t s, int arch, const bf16_t* dh, const bf16_t
     int flat, fc; fc_dims(arch, flat, fc);
     DenseRowsK8 al{dh, ns, fc};
     DenseRowsK8 bl{Wc, flat, fc};
-    EpiDenseMaskB ep{dx, act, flat};
+    EpiDenseMaskB ep{dx, act, flat, nullptr};
     return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, flat, fc, 1, 0);
 }
 
