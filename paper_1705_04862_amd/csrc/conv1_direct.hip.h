@@ -27,6 +27,8 @@ __global__ __launch_bounds__(256, 2) void conv1_direct_kernel(const uint8_t* __r
     constexpr int FRAGS = (NS * ROWS + 31) / 32;
     static_assert(SAMPLE % 16 == 0, "whole 16-byte chunks");
     __shared__ __attribute__((aligned(16))) bf16_t img[NS * SAMPLE];
+    constexpr int LDS_O = G::COUT + 8, CPR = G::COUT / 8;     // staging row pitch (bf16), 16-byte chunks per output row
+    __shared__ __attribute__((aligned(16))) bf16_t stage[4 * 32 * LDS_O];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fidx = lane & 31, kg = lane >> 5;
@@ -88,14 +90,25 @@ __global__ __launch_bounds__(256, 2) void conv1_direct_kernel(const uint8_t* __r
                     const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, breg[c * 4 + ks], acc, 0, 0, 0);
                 }
+            // the fragment's 32 rows are one contiguous piece of the output: through a wave-private LDS
+            // staging area it leaves as 16-byte stores instead of sixteen 2-byte stores per lane
+            bf16_t* st = stage + wave * (32 * LDS_O);
             if (fidx < G::COUT) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const int lr = f * 32 + Mma<32>::row(q, lane);
-                    const int orow = row0 + lr;
-                    if (lr < NS * ROWS && orow < M) out[(size_t)orow * G::COUT + fidx] = f2bf(fmaxf(acc[q] * scale + bias_r, 0.f));
-                }
+                for (int q = 0; q < 16; ++q)
+                    st[Mma<32>::row(q, lane) * LDS_O + fidx] = f2bf(fmaxf(acc[q] * scale + bias_r, 0.f));
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int c = 0; c < (32 * CPR + 63) / 64; ++c) {
+                const int ch = lane + c * 64, lrow = ch / CPR, c8 = ch % CPR;
+                const int lr = f * 32 + lrow, orow = row0 + lr;
+                if (ch < 32 * CPR && lr < NS * ROWS && orow < M)
+                    *reinterpret_cast<uint4*>(out + (size_t)orow * G::COUT + c8 * 8) = *reinterpret_cast<const uint4*>(st + lrow * LDS_O + c8 * 8);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();                                              // the image is rewritten next
     }
