@@ -120,6 +120,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
     constexpr int B_U = ROWK ? BN * BK / 8 : (BN / 8) * (BK / 4);
     constexpr int A_IT = (A_U + 255) / 256, B_IT = (B_U + 255) / 256;
     static_assert((A_IT + B_IT) * NL <= 32, "ok-bit mask");
+    // Side jobs of the weight-gradient mode are spread over the waves so that no wave is the
+    // straggler of every step: the B staging units (fewer than 256) go to the last waves, the
+    // row-offset table is filled by wave 0, the bias-gradient column sums by wave 1.
+    constexpr int B_SHIFT = (!ROWK && B_U % 256 != 0) ? 256 - B_U % 256 : 0;
+    constexpr int CS0 = ROWK ? 0 : 64;
 
     __shared__ __attribute__((aligned(16))) bf16_t smem[2 * A_BUF + 2 * B_BUF];
     // epilogues whose output address needs divisions per row (scatter of a parity class) get the BM
@@ -174,7 +179,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) unit(tid + i * 256, BM, row_fast<AL>(), a_fix0[i], a_var[i], a_lds[i]);
 #pragma unroll
-    for (int i = 0; i < B_IT; ++i) unit(tid + i * 256, BN, row_fast<BL>(), b_fix0[i], b_var[i], b_lds[i]);
+    for (int i = 0; i < B_IT; ++i) unit(max(tid + i * 256 - B_SHIFT, 0), BN, row_fast<BL>(), b_fix0[i], b_var[i], b_lds[i]);   // non-owners: a valid unit, predicated off
+    // does this thread own B staging unit i?
+    auto b_on = [&](int i) __attribute__((always_inline)) {
+        return B_U % 256 == 0 || (tid + i * 256 >= B_SHIFT && tid + i * 256 - B_SHIFT < B_U);
+    };
 
     typename AL::Fixed afix[A_IT];
     typename BL::Fixed bfix[B_IT];
@@ -227,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             for (int q = 0; q < NL; ++q) {
                 const int kk = kb + b_var[i] + q;
                 bool ok;
-                breg[G][i][q] = bl.load(bfix[i], kk, (B_U % 256 == 0 || tid + i * 256 < B_U) && kk < k_end, ok);
+                breg[G][i][q] = bl.load(bfix[i], kk, b_on(i) && kk < k_end, ok);
                 bits |= ok ? (1u << ((A_IT + i) * NL + q)) : 0u;
             }
         okbits[G] = bits;
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             }
         } else {
             constexpr int i = u - A_IT;
-            if (B_U % 256 == 0 || tid + i * 256 < B_U) {
+            if (b_on(i)) {
                 uint4 r[NL];
 #pragma unroll
                 for (int q = 0; q < NL; ++q) r[q] = BL::finish(breg[G][i][q], (okbits[G] >> ((A_IT + i) * NL + q)) & 1u);
@@ -331,10 +340,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
             }(), ...);
         }(std::make_integer_sequence<int, KS>());
         if constexpr (EP::kColSum) {          // bias gradient: sums of the B tile's rows (a row holds one column's k)
-            if (c_tile % m_tiles == 0 && tid < BN) {
+            if (c_tile % m_tiles == 0 && tid >= CS0 && tid - CS0 < BN) {
 #pragma unroll
                 for (int c = 0; c < BK / 8; ++c) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(bs + tid * LD + c * 8);
+                    const uint4 v = *reinterpret_cast<const uint4*>(bs + (tid - CS0) * LD + c * 8);
                     colsum = dot2_ones(v.w, dot2_ones(v.z, dot2_ones(v.y, dot2_ones(v.x, colsum))));
                 }
             }
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL
         const int mt = c_tile % m_tiles, nt = c_tile / m_tiles;
         const int m0 = mt * BM, n0 = nt * BN;
         if constexpr (EP::kColSum) {
-            if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
+            if (mt == 0 && tid >= CS0 && tid - CS0 < BN && n0 + tid - CS0 < N) ep.store_colsum(n0 + tid - CS0, colsum, z);
             colsum = 0.f;
         }
 #pragma unroll
