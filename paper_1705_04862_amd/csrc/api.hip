@@ -84,7 +84,7 @@ Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
         p.sel_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, n_e), 64, 256);
         p.trn_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, p.Bp), 64, 256);
         for (int l = 0; l < n.n_conv; ++l)
-            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, 512);
+            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, l == 0 ? 768 : 512);   // the first layer's tile fits three workgroups per CU
         p.fc_wg = plan_split(p.B, fc_wgrad_tiles_bf16(n.arch), 64, 512);
     } else {
         p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);

@@ -57,9 +57,10 @@ __device__ __forceinline__ uint4 u8x8_to_bf16_if(bool ok, uint2 w) {      // zer
     return u8x8_to_bf16(make_uint2(ok ? w.x : 0u, ok ? w.y : 0u));
 }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_ = 3>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_ = 3, int MINW_ = 2>
 struct TileB {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, STAGES = STAGES_;
+    static constexpr int MINW = MINW_;                       // waves per SIMD the register budget is sized for
     static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(TM * WM * 32 == BM && TN * WN * 32 == BN, "tile must be whole 32x32 fragments");
@@ -106,7 +107,7 @@ template <class EP> struct EpiColMap<EP, std::enable_if_t<EP::kColMap>> {
 };
 
 template <class T, class AL, class BL, class EP>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
+__global__ __launch_bounds__(256, T::MINW) void gemm_bf16_kernel(const AL al, const BL bl, const EP ep, int M, int N, int K,
                                                         int k_per_split, int m_tiles, int n_tiles, int group_m,
                                                         int z_count) {
     static_assert(AL::kContig == BL::kContig, "both operands use the same staging mode");

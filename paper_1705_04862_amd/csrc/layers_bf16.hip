@@ -12,7 +12,7 @@ typedef ConvGeom<32, 20, 20, 4, 2, 64> NatC2;
 typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
 
 // 128 rows, four waves along m; 32 or 64 columns (a 16-wide output uses the 32-wide tile)
-typedef TileB<128, 32, 64, 4, 1, 3> B128x32;
+typedef TileB<128, 32, 64, 4, 1, 3, 3> B128x32;
 typedef TileB<128, 64, 64, 4, 1, 3> B128x64;
 template <int N> struct TileBForN { typedef B128x64 type; };
 template <> struct TileBForN<16> { typedef B128x32 type; };
