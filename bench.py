@@ -166,6 +166,14 @@ def main():
     # context figures: the halves of the step
     ms_select = 1e3 * timed(k2, "select") / k2
     ms_train = 1e3 * timed(k2, "train") / k2
+    # context: the same step with the opt-in rollout activation cache (the train step reuses the
+    # activations of the t_max select calls and only runs the forward pass of the bootstrap states);
+    # never the reported value
+    ctx.set_activation_cache(True)
+    for i in range(5):
+        step(i)
+    ms_cached = 1e3 * timed(k2) / k2
+    ctx.set_activation_cache(False)
 
     # per-kernel durations with HIP events on the library's stream
     ctx.set_profiling(True)
@@ -218,6 +226,7 @@ def main():
         "pct_mfma_peak_whole_step": round(100 * step_flop / elapsed * args.steps / (mfma_peak * 1e12), 3),
         "ms_select_x_tmax": round(ms_select, 4), "ms_train": round(ms_train, 4),
         "ms_per_step_graph_replay": round(ms_graph, 4), "ms_per_step_direct_launch": round(ms_eager, 4),
+        "ms_per_step_with_activation_cache": round(ms_cached, 4),
         "kernels": per_kernel,
         "paper_context": "derived from the paper's Table 1 training times and time split on a GTX 980 Ti: "
                          "about 7200 (arch_nips) / 4100-4300 (arch_nature) env-timesteps/s for this path",

@@ -135,6 +135,19 @@ int paac_fill_uniforms(paac_ctx* ctx, uint64_t seed, uint64_t offset, float* out
  * HIP graph and replayed afterwards; 0: kernels are launched one by one. */
 int paac_set_graphs(paac_ctx* ctx, int use_graphs);
 
+/* Rollout activation cache (opt-in, default off).  Algorithm 1 computes the network outputs of s_t
+ * during action selection and theta does not change until the update at the end of the iteration, so
+ * the forward pass of paac_train_step over states[0 .. t_max-1] repeats work already done.  With the
+ * cache on, the i-th paac_select_actions call since the last paac_train_step (i = 0 .. t_max-1)
+ * keeps its activations, logits and values as rows [i n_e, (i+1) n_e) of the training buffers, and
+ * the next paac_train_step computes the forward pass for states[t_max] only.  The caller promises
+ * that states[i] of that train step are the states given to the i-th select call (they are still
+ * read: the first layer's weight gradient needs them).  If the number of select calls since the last
+ * train step, paac_set_state or paac_init_params is not exactly t_max, the train step falls back to
+ * the full forward pass.  Results agree with the uncached path to rounding (other tile shapes and
+ * split counts are used at the smaller batch), not bit for bit. */
+int paac_set_activation_cache(paac_ctx* ctx, int enabled);
+
 /* Per-kernel timing for roofline reports.  While enabled, select/train launch kernel by kernel
  * with a HIP event pair around each on the context's stream.  paac_kernel_times synchronises and
  * returns up to `cap` entries: name_out[i] points to a static string, ms_out[i] is the summed

@@ -190,6 +190,8 @@ struct paac_ctx {
     hipStream_t cap_stream;   // private stream used only for graph capture
     int device;
     bool have_params;
+    bool cache_on;            // rollout activation cache enabled
+    int sel_count;            // select calls since the last train step / parameter load
     bool use_graphs, profiling;
     std::vector<GraphEntry> graphs;
     // hyper-parameter staging: pinned ring, one event per slot
@@ -268,47 +270,63 @@ struct SelectArgs { const uint8_t* states; const float* uniforms; int32_t* actio
 struct TrainArgs { const uint8_t* states; const int32_t* actions; const float* rewards; const uint8_t* dones; paac_train_stats* stats; };
 
 // Forward trunk shared by select and train: convs, fc partial sums.
-void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0) {
+// `row0`: first row of the activation buffers this launch writes (0, or the slab of a cached rollout).
+void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0, int row0) {
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf;
     const void* in = states;
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
+    auto act_at = [&](int l) {
+        const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout * (bf16 ? 2 : 4);
+        return static_cast<char*>(b.act[l]) + (size_t)row0 * per;
+    };
     for (int l = 0; l < n.n_conv; ++l) {
-        if (bf16) L.run(id0 + l, [&] { return conv_fwd_bf16(L.s, n.arch, l, in, b.wt[l], b.theta + a.conv_b[l], (bf16_t*)b.act[l], ns); });
-        else L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], (float*)b.act[l], ns); });
-        in = b.act[l];
+        void* out = act_at(l);
+        if (bf16) L.run(id0 + l, [&] { return conv_fwd_bf16(L.s, n.arch, l, in, b.wt[l], b.theta + a.conv_b[l], (bf16_t*)out, ns); });
+        else L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], (float*)out, ns); });
+        in = out;
     }
-    if (bf16) L.run(id0 + 3, [&] { return fc_fwd_bf16(L.s, n.arch, (const bf16_t*)b.act[n.n_conv - 1], b.fc_t, b.fc_partial, ns, fc_split); });
-    else L.run(id0 + 3, [&] { return fc_fwd(L.s, n.arch, (const float*)b.act[n.n_conv - 1], b.theta + a.fc_w, b.fc_partial, ns, fc_split); });
+    if (bf16) L.run(id0 + 3, [&] { return fc_fwd_bf16(L.s, n.arch, (const bf16_t*)in, b.fc_t, b.fc_partial, ns, fc_split); });
+    else L.run(id0 + 3, [&] { return fc_fwd(L.s, n.arch, (const float*)in, b.theta + a.fc_w, b.fc_partial, ns, fc_split); });
 }
 
-hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int* err_id) {
+// `slab` >= 0: keep activations, logits and values as rollout slab `slab` of the training buffers.
+hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int slab, int* err_id) {
     Launcher L{c, s, prof, hipSuccess, -1};
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
     if (prof) delay_us(s, 250);
-    enqueue_trunk(c, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1);
+    const int row0 = slab >= 0 ? slab * p.n_e : 0;
+    enqueue_trunk(c, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1, row0);
     HeadsArgs h{};
     h.fc_partial = b.fc_partial; h.n_split = p.sel_fc.n; h.split_stride = (size_t)p.n_e * n.fc;
     h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
     h.v_w = b.theta + a.v_w; h.v_b = b.theta + a.v_b;
     h.rows = p.n_e; h.A = n.n_actions;
     h.values_out = x.values; h.uniforms = x.uniforms; h.actions_out = x.actions; h.probs_out = x.probs;
+    if (slab >= 0) {
+        h.h_out = b.h + (size_t)row0 * n.fc; h.logits_out = b.logits + (size_t)row0 * n.n_actions; h.values_copy = b.values + row0;
+    }
     L.run(K_SEL_HEADS, [&] { return heads_fwd(L.s, n.fc, h); });
     *err_id = L.err_id;
     return L.err;
 }
 
-hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs& x, int* err_id) {
+// `cached`: rows [0, B) of the forward pass were kept by the select calls of this rollout.
+hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs& x, bool cached, int* err_id) {
     Launcher L{c, s, prof, hipSuccess, -1};
     const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
     const int A = n.n_actions, F = n.fc, last = n.n_conv - 1;
     // forward over all (t_max+1) n_e states: rows [0, B) are the batch, rows [B, Bp) the bootstrap
     if (prof) delay_us(s, 800);
-    enqueue_trunk(c, L, x.states, p.Bp, p.trn_fc, K_TRN_CONV1);
+    const int f_row0 = cached ? p.B : 0, f_rows = cached ? p.n_e : p.Bp;      // rows the forward pass still has to compute
+    const Split f_split = cached ? p.sel_fc : p.trn_fc;
+    const size_t sample_bytes = (size_t)c->cfg.in_c * c->cfg.in_h * c->cfg.in_w;
+    enqueue_trunk(c, L, x.states + (size_t)f_row0 * sample_bytes, f_rows, f_split, K_TRN_CONV1, f_row0);
     HeadsArgs h{};
-    h.fc_partial = b.fc_partial; h.n_split = p.trn_fc.n; h.split_stride = (size_t)p.Bp * F;
+    h.fc_partial = b.fc_partial; h.n_split = f_split.n; h.split_stride = (size_t)f_rows * F;
     h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
     h.v_w = b.theta + a.v_w; h.v_b = b.theta + a.v_b;
-    h.rows = p.Bp; h.A = A; h.h_out = b.h; h.logits_out = b.logits; h.values_out = b.values;
+    h.rows = f_rows; h.A = A; h.h_out = b.h + (size_t)f_row0 * F; h.logits_out = b.logits + (size_t)f_row0 * A;
+    h.values_out = b.values + f_row0;
     L.run(K_TRN_HEADS, [&] { return heads_fwd(L.s, F, h); });
     LossArgs la{};
     la.logits = b.logits; la.values = b.values; la.actions = x.actions; la.rewards = x.rewards; la.dones = x.dones;
@@ -513,6 +531,7 @@ int paac_set_state(paac_ctx* c, const float* params_host, const float* rms_host)
     if (c->cfg.precision == PAAC_PREC_BF16) HIP_TRY(c, make_bf16_weights(c->stream, c->buf.copies, c->buf.theta));
     HIP_TRY(c, hipDeviceSynchronize());
     c->have_params = true;
+    c->sel_count = 0;          // activations cached under the old parameters are stale
     return PAAC_OK;
 }
 
@@ -570,9 +589,15 @@ int paac_select_actions(paac_ctx* c, const uint8_t* states_dev, const float* uni
     if (reinterpret_cast<uintptr_t>(states_dev) % 4 != 0) return fail(c, PAAC_E_BADCONFIG, "states_dev must be 4-byte aligned");
     DeviceGuard dg(c->device);
     const SelectArgs x{states_dev, uniforms_dev, actions_dev, values_dev, probs_dev};
+    // cached rollout: calls 0 .. t_max-1 since the last train step fill slabs 0 .. t_max-1; further calls
+    // use the bootstrap slab (the train step recomputes it) and make the cache invalid by their count
+    const int slab = c->cache_on ? (c->sel_count < c->plan.T ? c->sel_count : c->plan.T) : -1;
     GraphKey key{};
     key.kind = 0; key.p[0] = states_dev; key.p[1] = uniforms_dev; key.p[2] = actions_dev; key.p[3] = values_dev; key.p[4] = probs_dev;
-    return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, s, prof, x, id); });
+    key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(slab + 1));
+    const int r = run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, s, prof, x, slab, id); });
+    if (r == PAAC_OK && c->cache_on && c->sel_count <= c->plan.T) ++c->sel_count;
+    return r;
 }
 
 int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actions_dev, const float* rewards_dev,
@@ -590,9 +615,12 @@ int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actio
     int r = upload_hparams(c, hp_host);
     if (r) return r;
     const TrainArgs x{states_dev, actions_dev, rewards_dev, dones_dev, stats_dev};
+    const bool cached = c->cache_on && c->sel_count == c->plan.T;
+    c->sel_count = 0;
     GraphKey key{};
     key.kind = 1; key.p[0] = states_dev; key.p[1] = actions_dev; key.p[2] = rewards_dev; key.p[3] = dones_dev; key.p[4] = stats_dev;
-    return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_train(c, s, prof, x, id); });
+    key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(cached ? 1 : 0));
+    return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_train(c, s, prof, x, cached, id); });
 }
 
 int paac_get_train_outputs(paac_ctx* c, float* logits_host, float* values_host, float* returns_host) {
@@ -610,6 +638,13 @@ int paac_fill_uniforms(paac_ctx* c, uint64_t seed, uint64_t offset, float* out_d
     if (!out_dev && n) return fail(c, PAAC_E_NULL, "out_dev is NULL");
     DeviceGuard dg(c->device);
     HIP_TRY(c, fill_uniforms(c->stream, seed, offset, out_dev, n));
+    return PAAC_OK;
+}
+
+int paac_set_activation_cache(paac_ctx* c, int enabled) {
+    if (!c) return PAAC_E_NULL;
+    c->cache_on = enabled != 0;
+    c->sel_count = 0;
     return PAAC_OK;
 }
 

@@ -90,6 +90,7 @@ struct HeadsArgs {
     float* h_out;          // [rows][F] or null
     float* logits_out;     // [rows][A] or null
     float* values_out;     // [rows] or null
+    float* values_copy;    // [rows] or null: a second destination for the values
     const float* uniforms; // select mode when non-null
     int32_t* actions_out;  // [rows]
     float* probs_out;      // [rows][A] or null

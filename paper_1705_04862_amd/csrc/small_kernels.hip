@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
     }
     v += a.v_b[0];
     if (a.values_out && lane == 0) a.values_out[row] = v;
+    if (a.values_copy && lane == 0) a.values_copy[row] = v;
     if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
     if (a.uniforms) {
         const float m = wave_max(z);
@@ -177,6 +178,7 @@ __global__ __launch_bounds__(256) void heads_fwd_row_kernel(const HeadsArgs a) {
     const float z = lane < a.A ? outs[lane] + a.pi_b[lane] : -INFINITY;
     const float v = outs[a.A] + a.v_b[0];
     if (a.values_out && lane == 0) a.values_out[row] = v;
+    if (a.values_copy && lane == 0) a.values_copy[row] = v;
     if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
     if (a.uniforms) {
         const float m = wave_max(z);

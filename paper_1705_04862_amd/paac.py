@@ -23,7 +23,7 @@ ERRORS = {0: "PAAC_OK", -1: "PAAC_E_NULL", -2: "PAAC_E_BADCONFIG", -3: "PAAC_E_W
 # every symbol include/paac.h declares
 SYMBOLS = ["paac_workspace_bytes", "paac_create", "paac_destroy", "paac_init_params",
            "paac_select_actions", "paac_train_step", "paac_param_count", "paac_get_state",
-           "paac_set_state", "paac_get_train_outputs", "paac_fill_uniforms", "paac_set_graphs",
+           "paac_set_state", "paac_get_train_outputs", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache",
            "paac_set_profiling", "paac_kernel_times", "paac_flops", "paac_last_error"]
 
 
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
         L.paac_get_train_outputs.argtypes = [vp, vp, vp, vp]
         L.paac_fill_uniforms.argtypes = [vp, u64, u64, vp, sz]
         L.paac_set_graphs.argtypes = [vp, C.c_int]
+        L.paac_set_activation_cache.argtypes = [vp, C.c_int]
         L.paac_set_profiling.argtypes = [vp, C.c_int]
         L.paac_kernel_times.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                         C.POINTER(i32), C.POINTER(i32)]
@@ -202,6 +203,9 @@ class Paac:
 
     def set_graphs(self, on: bool):
         self._check(self.L.paac_set_graphs(self.ctx, int(on)))
+
+    def set_activation_cache(self, on: bool):
+        self._check(self.L.paac_set_activation_cache(self.ctx, int(on)))
 
     def set_profiling(self, on: bool):
         self._check(self.L.paac_set_profiling(self.ctx, int(on)))

@@ -554,3 +554,56 @@ def test_heads_kernels_agree_across_the_batch_threshold(paac, oracle):
     # rounding, not to the bit
     assert relmax(got_small[1], got_big[1][:40].astype(np.float64)) < 1e-5
     assert relmax(got_small[2], got_big[2][:40].astype(np.float64)) < 1e-5
+
+
+@pytest.mark.parametrize("precision", [0, 1], ids=["fp32", "bf16"])
+def test_rollout_activation_cache(paac, oracle, precision):
+    """Opt-in mode: the train step reuses what the t_max select calls of the rollout computed (the
+    parameters do not change in between, Algorithm 1) and runs the forward pass for the bootstrap
+    states only.  Same answer as the oracle, and as the uncached step to rounding; a rollout with the
+    wrong number of select calls, or a parameter reload, falls back to the full forward pass."""
+    net, n_e, t_max = I.nature_net(18), 6, 4
+    params = I.make_params(77, net, bias_range=0.05)
+    rms = I.make_rms(77, net, hi=0.01)
+    ro = I.make_rollout(77, net, n_e, t_max, 0.05)
+    hp = I.HParams()
+    st, ac, rw, dn = dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones)
+
+    def rollout(ctx, n_select):
+        for t in range(n_select):
+            run_select(ctx, net, ro.states[t % t_max], ro.uniforms[t % t_max])
+
+    def train(ctx):
+        ctx.train_step(st, ac, rw, dn, hp)
+        torch.cuda.synchronize()
+        p2, r2, g = ctx.get_state()
+        return p2, r2, g, ctx.get_train_outputs()
+
+    ref = make_ctx(paac, net, n_e, t_max, precision=precision)
+    ref.set_state(params, rms)
+    p_ref, r_ref, g_ref, out_ref = train(ref)
+
+    ctx = make_ctx(paac, net, n_e, t_max, precision=precision)
+    ctx.set_activation_cache(True)
+    tol_g, tol_o = (1e-5, 1e-5) if precision == 0 else (TOL_BF16_FLIP, 5e-3)
+    for n_select in (t_max, t_max - 1, t_max + 2, t_max):      # cached, two fallbacks, cached again
+        ctx.set_state(params, rms)
+        rollout(ctx, n_select)
+        p2, r2, g, out = train(ctx)
+        assert rel_l2(g, g_ref) < tol_g, n_select
+        assert rel_l2(p2 - params, p_ref - params) < max(tol_g, 1e-4), n_select
+        for a, b in zip(out, out_ref):
+            assert relmax(a, b.astype(np.float64)) < tol_o, n_select
+        if n_select != t_max and precision == 0:
+            assert np.array_equal(g, g_ref)                     # the fallback is the uncached path, bit for bit
+    # against the oracle, cached
+    ctx.set_state(params, rms)
+    rollout(ctx, t_max)
+    if precision == 0:
+        ctx.train_step(st, ac, rw, dn, hp)
+        torch.cuda.synchronize()
+        want = oracle.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
+        p2, r2, g = ctx.get_state()
+        assert rel_l2(g, want.grads) < TOL_L2 and rel_l2(p2, want.params) < TOL_L2
+        lg, vl, rt = ctx.get_train_outputs()
+        assert relmax(lg, want.logits) < TOL_VAL and relmax(vl, want.values) < TOL_VAL and relmax(rt, want.returns) < TOL_VAL
