@@ -38,5 +38,21 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
+ACTORS_LIB = os.path.join(HERE, "libpaac_actors.so")
+
+
+def build_actors(verbose: bool = False) -> str:
+    """Host-only worker pool + synthetic environment (no GPU code)."""
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", os.path.join(CSRC, "actors.cpp"), "-o", ACTORS_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("g++ failed on actors.cpp")
+    if verbose:
+        print("built", ACTORS_LIB)
+    return ACTORS_LIB
+
+
 if __name__ == "__main__":
     build_lib(verbose=True)
+    build_actors(verbose=True)

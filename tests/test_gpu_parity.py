@@ -607,3 +607,19 @@ def test_rollout_activation_cache(paac, oracle, precision):
         assert rel_l2(g, want.grads) < TOL_L2 and rel_l2(p2, want.params) < TOL_L2
         lg, vl, rt = ctx.get_train_outputs()
         assert relmax(lg, want.logits) < TOL_VAL and relmax(vl, want.values) < TOL_VAL and relmax(rt, want.returns) < TOL_VAL
+
+
+@pytest.mark.gpu
+def test_actor_loop_runs_algorithm_1_with_the_worker_pool():
+    """Whole loop (worker pool -> upload -> select -> update) on the small configuration: the
+    statistics are finite, and the result does not depend on the number of workers or on the
+    activation cache beyond rounding."""
+    from paper_1705_04862_amd import actor_loop as AL
+    cfg = I.CONFIGS[0]
+    _, _, s1 = AL.run(cfg, 1, 6, 0, 6, 5, False, False)
+    _, _, s4 = AL.run(cfg, 4, 6, 0, 6, 5, False, True)
+    _, _, sc = AL.run(cfg, 2, 6, 0, 6, 5, True, False)
+    assert s1["nonfinite"] == 0 and np.isfinite(s1["total_loss"]) and s1["grad_norm"] > 0
+    assert s1 == s4
+    for k in ("policy_loss", "entropy", "value_loss", "grad_norm"):
+        assert abs(s1[k] - sc[k]) <= 1e-4 * max(1.0, abs(s1[k])), (k, s1[k], sc[k])
