@@ -499,6 +499,127 @@ void oracle_train_step(const OracleNet* net, float* params, float* rms, const ui
     if (returns_out) std::memcpy(returns_out, R.data(), R.size() * sizeof(double));
 }
 
+// ------------------------------------------------------------------------------------------------
+// Value-based variant of the framework (Section 2.2 "Model-free Value Based Methods": the Bellman
+// target r + gamma max_a' Q(s', a') and the squared loss against Q(s, a); Section 3: the framework
+// is the same for value-based methods, the policy being implicit in Q).  The network's A head
+// outputs are read as Q(s, .); the single value node is not used and receives a zero gradient.
+// Readings:
+//  * over a rollout of t_max steps the target is the n-step form of the same Bellman backup,
+//    R_{T+1} = max_a' Q(s_{T+1}, a'), R_t = r_t + gamma (1 - d_t) R_{t+1}; with t_max = 1 it is the
+//    printed one-step target.  The target is a constant for differentiation and uses the same
+//    parameters as Q(s, a) (the printed loss has one parameter set theta_i, no target network).
+//  * L = c_q (1/B) sum (R - Q(s, a))^2, so dL/dQ(s, a) = -2 c_q (R - Q(s, a)) / B; the factor printed
+//    in front of the gradient is a choice of c_q.
+//  * behaviour policy: epsilon-greedy on argmax_a Q(s, a) (smallest index among equal maxima) from
+//    ONE uniform u per state: u < epsilon explores with action floor((u / epsilon) A), which is
+//    uniform given u < epsilon; that quotient is evaluated in fp32, the precision of the kernel
+//    that takes the same decision.
+
+// Greedy / explore decision for one state.  q: A action values.
+int32_t oracle_q_pick_f32(const double* q, int A, float u, float epsilon) {
+    if (u < epsilon) {
+        const float x = (u / epsilon) * (float)A;
+        int k = (int)x;
+        return k < A ? k : A - 1;
+    }
+    int best = 0;
+    for (int k = 1; k < A; ++k) if (q[k] > q[best]) best = k;
+    return best;
+}
+
+// L = c_q (1/B) sum_i (R_i - Q_i[a_i])^2 ; *msq = (1/B) sum (R - Q)^2 ; dq [B][A] = dL/dQ (may be null).
+void oracle_q_loss_f64(const double* Q, const double* R, const int32_t* actions, int B, int A,
+                       double cq, double* msq, double* dq) {
+    double acc = 0.0;
+    for (int i = 0; i < B; ++i) {
+        int a = actions[i];
+        if (a < 0) a = 0;
+        if (a >= A) a = A - 1;
+        const double td = R[i] - Q[(size_t)i * A + a];
+        acc += td * td;
+        if (dq) {
+            for (int k = 0; k < A; ++k) dq[(size_t)i * A + k] = 0.0;
+            dq[(size_t)i * A + a] = -2.0 * cq * td / (double)B;
+        }
+    }
+    *msq = acc / (double)B;
+}
+
+// The scalar whose gradient the variant follows, targets held fixed (finite-difference pin).
+double oracle_q_surrogate_loss_f64(const OracleNet* net, const double* params, const uint8_t* states,
+                                   const int32_t* actions, const double* R, int B, double cq) {
+    const Shapes S = make_shapes(*net);
+    std::vector<double> Q((size_t)B * S.A), v(B);
+    forward_batch(S, params, states, B, nullptr, Q.data(), v.data());
+    double msq;
+    oracle_q_loss_f64(Q.data(), R, actions, B, S.A, cq, &msq, nullptr);
+    return cq * msq;
+}
+
+void oracle_q_surrogate_grad_f64(const OracleNet* net, const double* params, const uint8_t* states,
+                                 const int32_t* actions, const double* R, int B, double cq, double* grads) {
+    const Shapes S = make_shapes(*net);
+    std::vector<double> Q((size_t)B * S.A), v(B), acts((size_t)B * S.act_per_sample);
+    forward_batch(S, params, states, B, acts.data(), Q.data(), v.data());
+    std::vector<double> dq((size_t)B * S.A), dv(B, 0.0);
+    double msq;
+    oracle_q_loss_f64(Q.data(), R, actions, B, S.A, cq, &msq, dq.data());
+    backward_batch(S, params, states, acts.data(), dq.data(), dv.data(), B, grads);
+}
+
+// Action selection of the variant: forward at fp32-stored parameters, epsilon-greedy pick.
+// q_out (may be null): [n_e][A] action values in double.
+void oracle_q_select_actions(const OracleNet* net, const float* params, const uint8_t* states,
+                             const float* uniforms, int n_e, float epsilon, int32_t* actions, double* q_out) {
+    const Shapes S = make_shapes(*net);
+    std::vector<double> th(S.P);
+    for (size_t i = 0; i < S.P; ++i) th[i] = params[i];
+    std::vector<double> Q((size_t)n_e * S.A), v(n_e);
+    forward_batch(S, th.data(), states, n_e, nullptr, Q.data(), v.data());
+    for (int e = 0; e < n_e; ++e) actions[e] = oracle_q_pick_f32(Q.data() + (size_t)e * S.A, S.A, uniforms[e], epsilon);
+    if (q_out) std::memcpy(q_out, Q.data(), Q.size() * sizeof(double));
+}
+
+// One update of the variant; arguments as oracle_train_step.  stats: value_loss = mean squared TD
+// error, total_loss = c_q * value_loss (c_q = hp->value_coef), policy_loss = entropy = 0.
+void oracle_q_train_step(const OracleNet* net, float* params, float* rms, const uint8_t* states,
+                         const int32_t* actions, const float* rewards, const uint8_t* dones,
+                         const OracleHParams* hp, int T, int n_e, OracleStats* stats,
+                         double* grads_out, double* q_out, double* returns_out) {
+    const Shapes S = make_shapes(*net);
+    const int B = T * n_e, Bp = (T + 1) * n_e;
+    std::vector<double> th(S.P), g2(S.P);
+    for (size_t i = 0; i < S.P; ++i) { th[i] = params[i]; g2[i] = rms[i]; }
+    std::vector<double> Q((size_t)Bp * S.A), v(Bp), acts((size_t)Bp * S.act_per_sample);
+    forward_batch(S, th.data(), states, Bp, acts.data(), Q.data(), v.data());
+    std::vector<double> boot(n_e), R(B);
+    for (int e = 0; e < n_e; ++e) {
+        const double* q = Q.data() + (size_t)(B + e) * S.A;
+        double m = q[0];
+        for (int k = 1; k < S.A; ++k) if (q[k] > m) m = q[k];
+        boot[e] = m;
+    }
+    returns_scan(rewards, dones, boot.data(), hp->gamma, T, n_e, R.data());
+    std::vector<double> dq((size_t)B * S.A), dv(B, 0.0), g(S.P);
+    double msq;
+    oracle_q_loss_f64(Q.data(), R.data(), actions, B, S.A, hp->value_coef, &msq, dq.data());
+    backward_batch(S, th.data(), states, acts.data(), dq.data(), dv.data(), B, g.data());
+    if (grads_out) std::memcpy(grads_out, g.data(), S.P * sizeof(double));
+    double norm = 0.0;
+    const double scale = oracle_clip_f64(g.data(), S.P, hp->clip_norm, &norm);
+    oracle_rmsprop_f64(th.data(), g2.data(), g.data(), S.P, hp->lr, hp->rms_alpha, hp->rms_eps);
+    for (size_t i = 0; i < S.P; ++i) { params[i] = (float)th[i]; rms[i] = (float)g2[i]; }
+    if (stats) {
+        stats->policy_loss = 0.0; stats->entropy = 0.0; stats->value_loss = msq;
+        stats->total_loss = hp->value_coef * msq;
+        stats->grad_norm = norm; stats->clip_scale = scale;
+        stats->nonfinite = (std::isfinite(stats->total_loss) && std::isfinite(norm)) ? 0 : 1;
+    }
+    if (q_out) std::memcpy(q_out, Q.data(), Q.size() * sizeof(double));
+    if (returns_out) std::memcpy(returns_out, R.data(), R.size() * sizeof(double));
+}
+
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw 2011, "Parallel random numbers: as easy as 1, 2, 3"):
 // counter (c0..c3), key (k0,k1) -> four 32-bit words.
 void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {

@@ -295,3 +295,86 @@ def init_params(net, seed: int) -> np.ndarray:
     out = np.empty(param_count(net), np.float32)
     L.oracle_init_params(C.byref(_net(net)), C.c_uint64(seed), _p(out, C.c_float))
     return out
+
+
+# ---- value-based variant (Section 2.2) ----
+def q_pick_f32(q, u, epsilon) -> int:
+    L = _load()
+    q = _c(q, np.float64)
+    L.oracle_q_pick_f32.restype = C.c_int32
+    return int(L.oracle_q_pick_f32(_p(q, C.c_double), q.size, C.c_float(float(u)), C.c_float(float(epsilon))))
+
+
+def q_loss_f64(Q, R, actions, cq):
+    """-> (mean squared TD error, dL/dQ [B,A]) for L = cq * mean((R - Q[a])^2)."""
+    L = _load()
+    Q = _c(Q, np.float64)
+    B, A = Q.shape
+    msq = C.c_double()
+    dq = np.empty((B, A), np.float64)
+    L.oracle_q_loss_f64(_p(Q, C.c_double), _p(_c(R, np.float64).reshape(B), C.c_double),
+                        _p(_c(actions, np.int32).reshape(B), C.c_int32), B, A, C.c_double(cq),
+                        C.byref(msq), _p(dq, C.c_double))
+    return msq.value, dq
+
+
+def q_surrogate_loss_f64(net, params, states, actions, R, cq) -> float:
+    L = _load()
+    L.oracle_q_surrogate_loss_f64.restype = C.c_double
+    params = _c(params, np.float64)
+    states = _c(states, np.uint8)
+    return float(L.oracle_q_surrogate_loss_f64(
+        C.byref(_net(net)), _p(params, C.c_double), _p(states, C.c_uint8),
+        _p(_c(actions, np.int32), C.c_int32), _p(_c(R, np.float64), C.c_double), states.shape[0],
+        C.c_double(cq)))
+
+
+def q_surrogate_grad_f64(net, params, states, actions, R, cq):
+    L = _load()
+    params = _c(params, np.float64)
+    states = _c(states, np.uint8)
+    g = np.empty(params.size, np.float64)
+    L.oracle_q_surrogate_grad_f64(
+        C.byref(_net(net)), _p(params, C.c_double), _p(states, C.c_uint8),
+        _p(_c(actions, np.int32), C.c_int32), _p(_c(R, np.float64), C.c_double), states.shape[0],
+        C.c_double(cq), _p(g, C.c_double))
+    return g
+
+
+def q_select_actions(net, params, states, uniforms, epsilon):
+    """-> dict(actions int32 [n_e], q float64 [n_e,A])."""
+    L = _load()
+    params = _c(params, np.float32)
+    states = _c(states, np.uint8)
+    uniforms = _c(uniforms, np.float32)
+    n_e = states.shape[0]
+    actions = np.empty(n_e, np.int32)
+    q = np.empty((n_e, net.n_actions), np.float64)
+    L.oracle_q_select_actions(C.byref(_net(net)), _p(params, C.c_float), _p(states, C.c_uint8),
+                              _p(uniforms, C.c_float), n_e, C.c_float(float(epsilon)),
+                              _p(actions, C.c_int32), _p(q, C.c_double))
+    return dict(actions=actions, q=q)
+
+
+def q_train_step(net, params, rms, states, actions, rewards, dones, hp) -> TrainResult:
+    """One update of the value-based variant; TrainResult.logits holds Q, .values is empty."""
+    L = _load()
+    params = np.array(params, dtype=np.float32, copy=True)
+    rms = np.array(rms, dtype=np.float32, copy=True)
+    states = _c(states, np.uint8)
+    T, n_e = states.shape[0] - 1, states.shape[1]
+    actions = _c(actions, np.int32)
+    rewards = _c(rewards, np.float32)
+    dones = _c(dones, np.uint8)
+    assert actions.shape == (T, n_e) and rewards.shape == (T, n_e) and dones.shape == (T, n_e)
+    h = _HP(hp.gamma, hp.beta, hp.value_coef, hp.lr, hp.rms_alpha, hp.rms_eps, hp.clip_norm)
+    st = _Stats()
+    grads = np.empty(params.size, np.float64)
+    q = np.empty(((T + 1) * n_e, net.n_actions), np.float64)
+    returns = np.empty((T, n_e), np.float64)
+    L.oracle_q_train_step(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
+                          _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
+                          _p(dones, C.c_uint8), C.byref(h), T, n_e, C.byref(st),
+                          _p(grads, C.c_double), _p(q, C.c_double), _p(returns, C.c_double))
+    stats = {n: getattr(st, n) for n, _ in _Stats._fields_}
+    return TrainResult(params, rms, grads, q, np.empty(0), returns, stats)
