@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--n_e", type=int, default=0, help="override the configuration's environment count (n_e sweep)")
     ap.add_argument("--t_max", type=int, default=0, help="override the configuration's rollout length")
     ap.add_argument("--lr", type=float, default=0.0, help="override the configuration's learning rate")
+    ap.add_argument("--algorithm", choices=["a2c", "nstep-q"], default="a2c",
+                    help="a2c: the paper's actor-critic (the reported metric); nstep-q: the value-based variant on the same kernels")
+    ap.add_argument("--epsilon", type=float, default=0.1, help="exploration rate of --algorithm nstep-q")
     ap.add_argument("--sweep-ne", default="", help="comma separated n_e values: one line with the throughput at each (lr = 0.0007 n_e)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -116,6 +119,8 @@ def main():
     ctx = P.Paac(net.arch, n_e, T, net.n_actions, cfg.precision)
     params = I.config_params(cfg)
     ctx.set_state(params)
+    if args.algorithm == "nstep-q":
+        ctx.set_algorithm(P.PAAC_ALG_NSTEP_Q, args.epsilon)
 
     to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
     host_rollouts = [I.config_rollout(cfg, k) for k in range(args.rollouts)]
@@ -213,13 +218,14 @@ def main():
     sel_f, trn_f = ctx.flops()
     step_flop = T * sel_f + trn_f
     out = {
-        "metric": "env-timesteps/sec (select+train) at n_e=%d,t_max=%d; %% MFMA peak" % (n_e, T),
+        "metric": "env-timesteps/sec (select+train) at n_e=%d,t_max=%d; %% MFMA peak" % (n_e, T) +
+                  ("" if args.algorithm == "a2c" else " [value-based variant, not the paper's measured method]"),
         "value": round(value, 1), "unit": "env-timesteps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.precision == 1 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "net": net.name, "n_e": n_e, "t_max": T, "n_actions": net.n_actions,
-                   "rollouts_rotated": len(R),
+                   "rollouts_rotated": len(R), "algorithm": args.algorithm,
                    "launch": "hip-graph replay (t_max select graphs + 1 train graph)" if use_graphs else "direct kernel launches on one stream"},
         "roofline": roof,
         "step_gflop": round(step_flop / 1e9, 3),
@@ -238,6 +244,11 @@ def main():
         rms = I.make_rms(0, net)
 
         def oracle_iter():
+            if args.algorithm == "nstep-q":
+                for t in range(T):
+                    O.q_select_actions(net, params, ro.states[t], ro.uniforms[t], args.epsilon)
+                O.q_train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp)
+                return
             for t in range(T):
                 O.select_actions(net, params, ro.states[t], ro.uniforms[t])
             O.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp)

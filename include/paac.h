@@ -148,6 +148,23 @@ int paac_set_graphs(paac_ctx* ctx, int use_graphs);
  * split counts are used at the smaller batch), not bit for bit. */
 int paac_set_activation_cache(paac_ctx* ctx, int enabled);
 
+/* Which algorithm the three calls run on the shared framework (Section 3: the framework serves
+ * value-based methods as well as policy-gradient ones).  Default PAAC_ALG_ACTOR_CRITIC.
+ * PAAC_ALG_NSTEP_Q is the value-based method of Section 2.2 on the same network: the A head outputs
+ * are Q(s, .), the value node is unused (zero gradient, its parameters stay as they are).
+ *   paac_select_actions: epsilon-greedy on argmax_a Q(s, a) (smallest index among equal maxima) from
+ *     the one uniform per state: u < epsilon picks action floor((u / epsilon) A) (fp32), else the
+ *     greedy one.  probs_dev, if given, receives that distribution; values_dev the unused node.
+ *   paac_train_step: R_{T+1} = max_a' Q(s_{T+1}, a'); R_t = r_t + gamma (1 - d_t) R_{t+1} (the Bellman
+ *     target, a constant for differentiation; the printed one-step target when t_max = 1);
+ *     L = value_coef mean((R_t - Q(s_t, a_t))^2); clip and RMSProp as before.  stats: value_loss is the
+ *     mean squared TD error, total_loss = value_coef * value_loss, policy_loss = entropy = 0;
+ *     paac_get_train_outputs returns Q in logits_host.
+ * epsilon in [0, 1] (ignored for actor-critic).  Takes effect from the next call. */
+#define PAAC_ALG_ACTOR_CRITIC 0
+#define PAAC_ALG_NSTEP_Q 1
+int paac_set_algorithm(paac_ctx* ctx, int algorithm, float epsilon);
+
 /* Per-kernel timing for roofline reports.  While enabled, select/train launch kernel by kernel
  * with a HIP event pair around each on the context's stream.  paac_kernel_times synchronises and
  * returns up to `cap` entries: name_out[i] points to a static string, ms_out[i] is the summed

@@ -174,7 +174,10 @@ const char* const kKernelNames[K_COUNT] = {
 struct GraphKey {
     int kind;                 // 0 select, 1 train
     const void* p[6];
-    bool operator==(const GraphKey& o) const { return kind == o.kind && memcmp(p, o.p, sizeof(p)) == 0; }
+    int algorithm; float epsilon;
+    bool operator==(const GraphKey& o) const {
+        return kind == o.kind && algorithm == o.algorithm && epsilon == o.epsilon && memcmp(p, o.p, sizeof(p)) == 0;
+    }
 };
 struct GraphEntry { GraphKey key; hipGraph_t graph; hipGraphExec_t exec; };
 
@@ -192,6 +195,8 @@ struct paac_ctx {
     bool have_params;
     bool cache_on;            // rollout activation cache enabled
     int sel_count;            // select calls since the last train step / parameter load
+    int algorithm;            // PAAC_ALG_*
+    float epsilon;            // exploration rate of PAAC_ALG_NSTEP_Q
     bool use_graphs, profiling;
     std::vector<GraphEntry> graphs;
     // hyper-parameter staging: pinned ring, one event per slot
@@ -302,6 +307,7 @@ hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArg
     h.v_w = b.theta + a.v_w; h.v_b = b.theta + a.v_b;
     h.rows = p.n_e; h.A = n.n_actions;
     h.values_out = x.values; h.uniforms = x.uniforms; h.actions_out = x.actions; h.probs_out = x.probs;
+    h.algorithm = c->algorithm; h.epsilon = c->epsilon;
     if (slab >= 0) {
         h.h_out = b.h + (size_t)row0 * n.fc; h.logits_out = b.logits + (size_t)row0 * n.n_actions; h.values_copy = b.values + row0;
     }
@@ -332,6 +338,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     la.logits = b.logits; la.values = b.values; la.actions = x.actions; la.rewards = x.rewards; la.dones = x.dones;
     la.hp = b.hp; la.T = p.T; la.n_e = p.n_e; la.A = A;
     la.returns = b.returns; la.dz = b.dz; la.dv = b.dv; la.loss_partials = b.loss_partials;
+    la.algorithm = c->algorithm;
     L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
     // heads backward
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
@@ -490,6 +497,7 @@ int paac_create(const paac_config* cfg, void* workspace_dev, size_t workspace_by
     if (c->buf.bytes > workspace_bytes) { delete c; return PAAC_E_WORKSPACE; }
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->have_params = false; c->use_graphs = true; c->profiling = false;
+    c->algorithm = PAAC_ALG_ACTOR_CRITIC; c->epsilon = 0.f;
     c->hp_next = 0; c->hp_valid = false;
     memset(c->hp_ev_used, 0, sizeof(c->hp_ev_used));
     memset(c->k_ms, 0, sizeof(c->k_ms)); memset(c->k_calls, 0, sizeof(c->k_calls));
@@ -595,6 +603,7 @@ int paac_select_actions(paac_ctx* c, const uint8_t* states_dev, const float* uni
     GraphKey key{};
     key.kind = 0; key.p[0] = states_dev; key.p[1] = uniforms_dev; key.p[2] = actions_dev; key.p[3] = values_dev; key.p[4] = probs_dev;
     key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(slab + 1));
+    key.algorithm = c->algorithm; key.epsilon = c->epsilon;
     const int r = run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, s, prof, x, slab, id); });
     if (r == PAAC_OK && c->cache_on && c->sel_count <= c->plan.T) ++c->sel_count;
     return r;
@@ -620,6 +629,7 @@ int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actio
     GraphKey key{};
     key.kind = 1; key.p[0] = states_dev; key.p[1] = actions_dev; key.p[2] = rewards_dev; key.p[3] = dones_dev; key.p[4] = stats_dev;
     key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(cached ? 1 : 0));
+    key.algorithm = c->algorithm; key.epsilon = 0.f;
     return run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_train(c, s, prof, x, cached, id); });
 }
 
@@ -644,6 +654,16 @@ int paac_fill_uniforms(paac_ctx* c, uint64_t seed, uint64_t offset, float* out_d
 int paac_set_activation_cache(paac_ctx* c, int enabled) {
     if (!c) return PAAC_E_NULL;
     c->cache_on = enabled != 0;
+    c->sel_count = 0;
+    return PAAC_OK;
+}
+
+int paac_set_algorithm(paac_ctx* c, int algorithm, float epsilon) {
+    if (!c) return PAAC_E_NULL;
+    if (algorithm != PAAC_ALG_ACTOR_CRITIC && algorithm != PAAC_ALG_NSTEP_Q) return fail(c, PAAC_E_BADCONFIG, "unknown algorithm");
+    if (algorithm == PAAC_ALG_NSTEP_Q && !(epsilon >= 0.f && epsilon <= 1.f)) return fail(c, PAAC_E_BADCONFIG, "epsilon must be in [0, 1]");
+    c->algorithm = algorithm;
+    c->epsilon = algorithm == PAAC_ALG_NSTEP_Q ? epsilon : 0.f;
     c->sel_count = 0;
     return PAAC_OK;
 }

@@ -94,6 +94,8 @@ struct HeadsArgs {
     const float* uniforms; // select mode when non-null
     int32_t* actions_out;  // [rows]
     float* probs_out;      // [rows][A] or null
+    int algorithm;         // ALG_*: how the action is drawn from the head outputs
+    float epsilon;         // exploration rate of ALG_NSTEP_Q
 };
 hipError_t heads_fwd(hipStream_t s, int F, const HeadsArgs& a);
 
@@ -104,6 +106,7 @@ struct LossArgs {
     int T, n_e, A;
     float* returns; float* dz; float* dv;                // [T n_e], [T n_e][A], [T n_e]
     float* loss_partials;                                // [blocks][4]
+    int algorithm;                                       // ALG_*
 };
 int loss_blocks(int n_e);
 hipError_t returns_loss(hipStream_t s, const LossArgs& a);
@@ -115,6 +118,7 @@ hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, cons
 hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
                        const float* h, float* partial_w, float* partial_b);
 
+enum { ALG_ACTOR_CRITIC = 0, ALG_NSTEP_Q = 1 };
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };
 
 constexpr int kMaxSeg = 12;

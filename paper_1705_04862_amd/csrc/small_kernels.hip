@@ -34,6 +34,41 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ------------------------------------------------------------------------------------ heads
+// Action of one state row, taken by a whole wavefront; lane k < A holds head output k, the other
+// lanes -inf.  Actor-critic: softmax, then the inverse CDF of the probabilities summed in ascending
+// order in fp32.  Value-based variant (Section 2.2: the policy is argmax_a Q(s, a)): epsilon-greedy
+// from the one uniform, u < epsilon picks floor(u / epsilon * A), otherwise the smallest index among
+// the maxima.
+__device__ __forceinline__ void choose_action(const HeadsArgs& a, float z, int lane, int row) {
+    const float m = wave_max(z);
+    const float u = a.uniforms[row];
+    if (a.algorithm == ALG_NSTEP_Q) {
+        const unsigned long long eq = __ballot(lane < a.A && z == m);
+        int greedy = __ffsll(eq) - 1;
+        greedy = greedy < 0 ? 0 : greedy;          // no maximum (NaN outputs): a valid index all the same
+        int act = greedy;
+        if (u < a.epsilon) {
+            const int k = (int)((u / a.epsilon) * (float)a.A);
+            act = k < a.A ? k : a.A - 1;
+        }
+        if (a.probs_out && lane < a.A)
+            a.probs_out[(size_t)row * a.A + lane] = a.epsilon / (float)a.A + (lane == greedy ? 1.f - a.epsilon : 0.f);
+        if (lane == 0) a.actions_out[row] = act;
+        return;
+    }
+    const float e = lane < a.A ? expf(z - m) : 0.f;
+    const float p = e / wave_sum(e);
+    if (a.probs_out && lane < a.A) a.probs_out[(size_t)row * a.A + lane] = p;
+    float cdf = 0.f;
+    int act = a.A - 1;
+    bool found = false;
+    for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
+        cdf = cdf + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), k));
+        if (!found && u < cdf) { act = k; found = true; }
+    }
+    if (lane == 0) a.actions_out[row] = act;
+}
+
 // One wavefront per state row.  The fc layer's split partial sums are added, bias and ReLU applied,
 // then A+1 dot products (policy logits, value) are reduced across the 64 lanes; lane k ends up
 // holding logit k.  In select mode the same wavefront computes the softmax and draws the action.
@@ -92,21 +127,7 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
     if (a.values_out && lane == 0) a.values_out[row] = v;
     if (a.values_copy && lane == 0) a.values_copy[row] = v;
     if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
-    if (a.uniforms) {
-        const float m = wave_max(z);
-        const float e = lane < a.A ? expf(z - m) : 0.f;
-        const float p = e / wave_sum(e);
-        if (a.probs_out && lane < a.A) a.probs_out[(size_t)row * a.A + lane] = p;
-        const float u = a.uniforms[row];
-        float cdf = 0.f;
-        int act = a.A - 1;
-        bool found = false;
-        for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
-            cdf = cdf + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), k));
-            if (!found && u < cdf) { act = k; found = true; }
-        }
-        if (lane == 0) a.actions_out[row] = act;
-    }
+    if (a.uniforms) choose_action(a, z, lane, row);
 }
 
 // Small batches (every select call of the paper's configurations, the train forward up to a few
@@ -180,21 +201,7 @@ __global__ __launch_bounds__(256) void heads_fwd_row_kernel(const HeadsArgs a) {
     if (a.values_out && lane == 0) a.values_out[row] = v;
     if (a.values_copy && lane == 0) a.values_copy[row] = v;
     if (a.logits_out && lane < a.A) a.logits_out[(size_t)row * a.A + lane] = z;
-    if (a.uniforms) {
-        const float m = wave_max(z);
-        const float e = lane < a.A ? expf(z - m) : 0.f;
-        const float p = e / wave_sum(e);
-        if (a.probs_out && lane < a.A) a.probs_out[(size_t)row * a.A + lane] = p;
-        const float u = a.uniforms[row];
-        float cdf = 0.f;
-        int act = a.A - 1;
-        bool found = false;
-        for (int k = 0; k < a.A; ++k) {            // ascending order, sequential fp32 sum
-            cdf = cdf + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), k));
-            if (!found && u < cdf) { act = k; found = true; }
-        }
-        if (lane == 0) a.actions_out[row] = act;
-    }
+    if (a.uniforms) choose_action(a, z, lane, row);
 }
 
 template <int F, int KMAX> static void launch_heads(hipStream_t s, const HeadsArgs& a) {
@@ -233,7 +240,14 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
     const float gamma = a.hp[HP_GAMMA], beta = a.hp[HP_BETA], cv = a.hp[HP_VCOEF];
     if (tid < ne_blk) {
         const int e = e0 + tid;
-        float R = a.values[B + e];
+        float R;
+        if (a.algorithm == ALG_NSTEP_Q) {             // Bellman target: R_{T+1} = max_a' Q(s_{T+1}, a')
+            const float* q = a.logits + (size_t)(B + e) * a.A;
+            R = q[0];
+            for (int k = 1; k < a.A; ++k) R = fmaxf(R, q[k]);
+        } else {
+            R = a.values[B + e];
+        }
         for (int t1 = a.T; t1 > 0; t1 -= 8) {          // eight timesteps of loads in flight, then the scan
             float r[8]; uint8_t d[8];
 #pragma unroll
@@ -264,6 +278,18 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
         const float V = a.values[i], R = a.returns[i], adv = R - V;
         int act = a.actions[i];
         act = act < 0 ? 0 : (act >= a.A ? a.A - 1 : act);
+        if (a.algorithm == ALG_NSTEP_Q) {             // L = c (R - Q(s,a))^2 averaged; the value node is unused
+            float qa = z[0];
+#pragma unroll
+            for (int k = 1; k < AMAX; ++k) qa = (k == act) ? z[k] : qa;
+            const float td = R - qa;
+            s_vl += td * td;
+#pragma unroll
+            for (int k = 0; k < AMAX; ++k)
+                if (k < a.A) a.dz[(size_t)i * a.A + k] = (k == act) ? -2.f * cv * td * invB : 0.f;
+            a.dv[i] = 0.f;
+            continue;
+        }
         float m = z[0];
 #pragma unroll
         for (int k = 1; k < AMAX; ++k) m = fmaxf(m, z[k]);

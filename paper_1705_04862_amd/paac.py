@@ -17,13 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libpaac.so")
 
 PAAC_ARCH_NIPS, PAAC_ARCH_NATURE = 0, 1
 PAAC_PREC_FP32, PAAC_PREC_BF16 = 0, 1
+PAAC_ALG_ACTOR_CRITIC, PAAC_ALG_NSTEP_Q = 0, 1
 ERRORS = {0: "PAAC_OK", -1: "PAAC_E_NULL", -2: "PAAC_E_BADCONFIG", -3: "PAAC_E_WORKSPACE",
           -4: "PAAC_E_HIP", -5: "PAAC_E_STATE"}
 
 # every symbol include/paac.h declares
 SYMBOLS = ["paac_workspace_bytes", "paac_create", "paac_destroy", "paac_init_params",
            "paac_select_actions", "paac_train_step", "paac_param_count", "paac_get_state",
-           "paac_set_state", "paac_get_train_outputs", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache",
+           "paac_set_state", "paac_get_train_outputs", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache", "paac_set_algorithm",
            "paac_set_profiling", "paac_kernel_times", "paac_flops", "paac_last_error"]
 
 
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
         L.paac_fill_uniforms.argtypes = [vp, u64, u64, vp, sz]
         L.paac_set_graphs.argtypes = [vp, C.c_int]
         L.paac_set_activation_cache.argtypes = [vp, C.c_int]
+        L.paac_set_algorithm.argtypes = [vp, C.c_int, C.c_float]
         L.paac_set_profiling.argtypes = [vp, C.c_int]
         L.paac_kernel_times.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_float),
                                         C.POINTER(i32), C.POINTER(i32)]
@@ -206,6 +208,10 @@ class Paac:
 
     def set_activation_cache(self, on: bool):
         self._check(self.L.paac_set_activation_cache(self.ctx, int(on)))
+
+    def set_algorithm(self, algorithm: int, epsilon: float = 0.0):
+        """0 = actor-critic (default), 1 = n-step Q-learning with epsilon-greedy selection."""
+        self._check(self.L.paac_set_algorithm(self.ctx, int(algorithm), float(epsilon)))
 
     def set_profiling(self, on: bool):
         self._check(self.L.paac_set_profiling(self.ctx, int(on)))
