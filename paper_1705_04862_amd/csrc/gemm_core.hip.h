@@ -423,28 +423,6 @@ __device__ __forceinline__ float4 u8x4_to_unit(uint32_t w) {
 // compiler wait for every outstanding load at the join, which would serialise the prefetch stages.)
 //   load(fixed, var, ok): `ok` = the caller's own predicate (k-range, tile bounds)
 
-// im2col rows of a uint8 NCHW image batch, k = (c, ky, kx); value = byte / 255.
-template <class G> struct ConvU8RowsK {
-    static constexpr bool kContig = true;
-    typedef uint32_t Raw;
-    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, u8x4_to_unit(r)); }
-    const uint8_t* x; int rows;
-    struct Fixed { const uint8_t* p; bool ok; };
-    __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.ok = row < rows;
-        row = f.ok ? row : 0;
-        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        f.p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        ok = pred && f.ok;
-        k = ok ? k : 0;
-        const int c = k / (G::KS * G::KS), r = k % (G::KS * G::KS), ky = r / G::KS, kx = r % G::KS;
-        return *reinterpret_cast<const uint32_t*>(f.p + c * (G::H * G::W) + ky * G::W + kx);
-    }
-};
-
 // im2col rows of a float NHWC activation, k = (ky, kx, c).
 template <class G> struct ConvNHWCRowsK {
     static constexpr bool kContig = true;

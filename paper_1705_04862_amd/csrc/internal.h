@@ -80,6 +80,8 @@ struct WeightCopies {            // see make_bf16_weights_kernel for the modes
     int n, total;
     bf16_t* dst[kMaxCopies]; int start[kMaxCopies], src_off[kMaxCopies], K[kMaxCopies], C[kMaxCopies], cin[kMaxCopies], mode[kMaxCopies];
 };
+// first convolution of the fp32 path from the three bf16 parts of its weights, fp32 NHWC output
+hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* w_parts, const float* b, float* out, int ns);
 hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);
 
 // ---- small kernels (small_kernels.hip) ----
@@ -133,7 +135,9 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, f
 struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
                           const float* block_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
-                          StatsOut* stats_a, StatsOut* stats_b);
+                          StatsOut* stats_a, StatsOut* stats_b, bf16_t* w1_parts, int w1_off, int w1_cout);
+// first-layer weights W[k][cout] (fp32) as three bf16 parts [3][32 k-groups][32 c_out][8] whose sum is the weight
+hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t* parts);
 hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n);
 
 hipError_t delay_us(hipStream_t s, unsigned us);

@@ -96,15 +96,6 @@ Split plan_split(int k_total, int tiles, int granule, int target_wgs) {
 
 // ---------------------------------------------------------------------------------- forward
 template <class G>
-static hipError_t conv_fwd_u8(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
-    typedef TileForN<G::COUT> TS;
-    const int M = ns * G::HO * G::WO;
-    ConvU8RowsK<G> al{(const uint8_t*)in, M};
-    DenseKCols bl{W, G::COUT, G::COUT};
-    EpiBiasRelu ep{out, b, G::COUT};
-    return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::COUT, G::KK, 1);
-}
-template <class G>
 static hipError_t conv_fwd_f32(hipStream_t s, const void* in, const float* W, const float* b, float* out, int ns) {
     typedef TileForN<G::COUT> TS;
     const int M = ns * G::HO * G::WO;
@@ -114,13 +105,12 @@ static hipError_t conv_fwd_f32(hipStream_t s, const void* in, const float* W, co
     return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::COUT, G::KK, 1);
 }
 
+// layers 1.. of the fp32 path (the first layer runs in conv1_fwd_exact)
 hipError_t conv_fwd(hipStream_t s, int arch, int layer, const void* in, const float* W, const float* b,
                     float* out, int ns) {
     if (arch == 0) {
-        if (layer == 0) return conv_fwd_u8<NipsC1>(s, in, W, b, out, ns);
         if (layer == 1) return conv_fwd_f32<NipsC2>(s, in, W, b, out, ns);
     } else {
-        if (layer == 0) return conv_fwd_u8<NatC1>(s, in, W, b, out, ns);
         if (layer == 1) return conv_fwd_f32<NatC2>(s, in, W, b, out, ns);
         if (layer == 2) return conv_fwd_f32<NatC3>(s, in, W, b, out, ns);
     }

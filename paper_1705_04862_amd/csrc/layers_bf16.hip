@@ -46,6 +46,12 @@ hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, con
     return hipErrorInvalidValue;
 }
 
+// First convolution of the fp32 path: bf16 matrix cores on exact operands (see conv1_exact_kernel).
+hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* Wk, const float* b, float* out, int ns) {
+    if (arch == 0) return launch_conv1_exact<NipsC1>(s, x, Wk, b, out, ns);
+    return launch_conv1_exact<NatC1>(s, x, Wk, b, out, ns);
+}
+
 // ---------------------------------------------------------------------------------- data gradient
 template <class G>
 static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in, bf16_t* dx, int ns) {

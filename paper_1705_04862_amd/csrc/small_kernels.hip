@@ -448,10 +448,38 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, f
 // Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
 //   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
 // Every block re-derives the norm from the per-block partial sums (same order everywhere).
+// An fp32 number as three bf16 numbers whose sum it is: its 24 significand bits cut into 8 + 8 + 8
+// by truncation (both residuals are exact).  parts: [3][32 k-groups of 8][32 c_out][8] bf16, the
+// order in which the lanes of the first-layer kernel read their MFMA B fragments (16 bytes each).
+__device__ __forceinline__ void store_split3(float w, int co, int k, bf16_t* parts) {
+    const uint32_t hb = __float_as_uint(w) & 0xffff0000u;
+    const float r1 = w - __uint_as_float(hb);
+    const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mb);
+    const int at = (k >> 3) * 256 + co * 8 + (k & 7);
+    parts[at] = (bf16_t)(hb >> 16);
+    parts[8192 + at] = (bf16_t)(mb >> 16);
+    parts[2 * 8192 + at] = (bf16_t)(__float_as_uint(r2) >> 16);
+}
+
+// First-layer weights W[k][cout] (fp32) -> their three bf16 parts; rows cout..31 are zero.
+__global__ __launch_bounds__(256) void split_conv1_weights_kernel(const float* Wk, int cout, bf16_t* parts) {
+    const int co = blockIdx.x, k = threadIdx.x;
+    store_split3(co < cout ? Wk[k * cout + co] : 0.f, co, k, parts);
+}
+hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t* parts) {
+    if (cout < 1 || cout > 32) return hipErrorInvalidValue;
+    launch_k(split_conv1_weights_kernel, dim3(32), dim3(256), s, Wk, cout, parts);
+    return hipGetLastError();
+}
+
+// w1_parts (may be null): the updated first-layer weights, arena floats [w1_off, w1_off + 256 w1_cout),
+// are also written as their three bf16 parts for the next forward pass.
 __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
                                                              const float* block_ss, int n_ss, const float* hp,
                                                              const float* loss_partials, int n_loss_blocks,
-                                                             StatsOut* stats_a, StatsOut* stats_b) {
+                                                             StatsOut* stats_a, StatsOut* stats_b,
+                                                             bf16_t* w1_parts, int w1_off, int w1_cout) {
     __shared__ float red[256];
     float part = 0.f;
     for (int q = threadIdx.x; q < n_ss; q += 256) part += block_ss[q];
@@ -468,6 +496,12 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
         t.x -= lr * g.x / sqrtf(v.x + eps); t.y -= lr * g.y / sqrtf(v.y + eps);
         t.z -= lr * g.z / sqrtf(v.z + eps); t.w -= lr * g.w / sqrtf(v.w + eps);
         g2[i] = v; theta[i] = t;
+        const int e0 = i * 4 - w1_off;
+        if (w1_parts && e0 >= 0 && e0 < 256 * w1_cout) {           // w1_off and 256 w1_cout are multiples of 4
+            const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) store_split3(tv[e], (e0 + e) % w1_cout, (e0 + e) / w1_cout, w1_parts);
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         float pl = 0.f, en = 0.f, vl = 0.f;
@@ -484,12 +518,14 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
 }
 
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads, const float* block_ss,
-                          const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b) {
+                          const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b,
+                          bf16_t* w1_parts, int w1_off, int w1_cout) {
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 512) blocks = 512;       // grid-stride loop: fewer, longer-lived workgroups
     launch_k(rmsprop_update_kernel, dim3(blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
-                       (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b);
+                       (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b,
+                       w1_parts, w1_off, w1_cout);
     return hipGetLastError();
 }
 
