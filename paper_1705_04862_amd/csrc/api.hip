@@ -138,7 +138,8 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
         b.pw[l] = take((size_t)p.wg[l].n * n.conv[l].kk * n.conv[l].cout);
         b.pb[l] = take((size_t)p.wg[l].n * n.conv[l].cout);
     }
-    b.fc_pw = take((size_t)p.fc_wg.n * n.flat * n.fc); b.fc_pb = take((size_t)p.fc_wg.n * n.fc);
+    // an unsplit fc weight gradient is written straight into the gradient arena (no partial buffer)
+    b.fc_pw = p.fc_wg.n > 1 ? take((size_t)p.fc_wg.n * n.flat * n.fc) : nullptr; b.fc_pb = take((size_t)p.fc_wg.n * n.fc);
     b.hd_pw = take((size_t)p.head_chunks * (n.n_actions + 1) * n.fc);
     b.hd_pb = take((size_t)p.head_chunks * (n.n_actions + 1));
     if (!bf16) b.w1_parts = reinterpret_cast<bf16_t*>(take(3 * 32 * 256 / 2));
@@ -346,6 +347,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
     // heads backward
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
+    float* const fc_pw = p.fc_wg.n > 1 ? b.fc_pw : b.grads + a.fc_w;
     L.run(K_TRN_HEADS_DH, [&] {
         return heads_dh(L.s, F, A, p.B, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, bf16 ? nullptr : (float*)b.dh,
                         bf16 ? (bf16_t*)b.dh : nullptr);
@@ -353,12 +355,12 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     L.run(K_TRN_HEADS_WG, [&] { return heads_wgrad(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.h, b.hd_pw, b.hd_pb); });
     // fc backward
     if (bf16) {
-        L.run(K_TRN_FC_WG, [&] { return fc_wgrad_bf16(L.s, n.arch, (const bf16_t*)b.act[last], (const bf16_t*)b.dh, b.fc_pw, b.fc_pb, p.B, p.fc_wg); });
+        L.run(K_TRN_FC_WG, [&] { return fc_wgrad_bf16(L.s, n.arch, (const bf16_t*)b.act[last], (const bf16_t*)b.dh, fc_pw, b.fc_pb, p.B, p.fc_wg); });
         L.run(K_TRN_FC_DG, [&] { return fc_dgrad_bf16(L.s, n.arch, (const bf16_t*)b.dh, b.fc_c, (const bf16_t*)b.act[last], (bf16_t*)b.dact[last], p.B); });
     } else {
         L.run(K_TRN_FC_BWD, [&] {
             return fc_bwd(L.s, n.arch, (const float*)b.act[last], (const float*)b.dh, b.theta + a.fc_w, (float*)b.dact[last],
-                          b.fc_pw, b.fc_pb, p.B, p.fc_wg);
+                          fc_pw, b.fc_pb, p.B, p.fc_wg);
         });
     }
     // conv backward, last layer first
@@ -391,7 +393,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
         seg(b.pw[l], p.wg[l].n, wn, wn, a.conv_w[l]);
         seg(b.pb[l], p.wg[l].n, n.conv[l].cout, n.conv[l].cout, a.conv_b[l]);
     }
-    seg(b.fc_pw, p.fc_wg.n, (size_t)n.flat * F, n.flat * F, a.fc_w);
+    seg(fc_pw, p.fc_wg.n, (size_t)n.flat * F, n.flat * F, a.fc_w);
     seg(b.fc_pb, p.fc_wg.n, F, F, a.fc_b);
     seg(b.hd_pw, p.head_chunks, (size_t)(A + 1) * F, A * F, a.pi_w);
     seg(b.hd_pb, p.head_chunks, A + 1, A, a.pi_b);

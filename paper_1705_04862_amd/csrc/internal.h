@@ -124,7 +124,7 @@ enum { ALG_ACTOR_CRITIC = 0, ALG_NSTEP_Q = 1 };
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };
 
 constexpr int kMaxSeg = 12;
-inline int norm_blocks(int p_int) { return (p_int + 255) / 256; }   // one sum of squares per block
+inline int norm_blocks(int p_int) { return (p_int + 1023) / 1024; }   // one sum of squares per block of 1024 elements
 struct GradSegments {
     int n;
     const float* partial[kMaxSeg]; int n_split[kMaxSeg]; size_t stride[kMaxSeg];

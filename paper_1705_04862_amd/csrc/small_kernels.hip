@@ -412,31 +412,67 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 }
 
 // Sums the split partial gradients in a fixed order (bit-stable from run to run), writes the
-// gradient arena and one partial sum of squares per block.  One arena element per thread.
+// gradient arena and one partial sum of squares per block.  Four consecutive arena elements per
+// thread (tensors start at multiples of 64 floats, so the four belong to one tensor), 16-byte loads
+// where the partial buffer allows.  Split q goes to accumulator q mod 8 in ascending q, the eight
+// are added as a tree; 8 or 16 loads are issued before the first addition (a first-layer weight gradient
+// has 60+ splits: issued one after the other they were the critical path of the whole kernel).
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float add4(float a, float b) { return a + b; }
+template <class V> __device__ __forceinline__ V zero_v();
+template <> __device__ __forceinline__ float zero_v<float>() { return 0.f; }
+template <> __device__ __forceinline__ float4 zero_v<float4>() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+
+template <class V, int R>
+__device__ __forceinline__ void sum_rounds(const float* p, size_t st, int ns, V (&acc)[8]) {
+    for (int q = 0; q < ns; q += R) {
+        V v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = *reinterpret_cast<const V*>(p + (size_t)min(q + r, ns - 1) * st);   // clamped: ignored below
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r & 7] = add4(acc[r & 7], q + r < ns ? v[r] : zero_v<V>());
+    }
+}
+template <class V>
+__device__ __forceinline__ V sum_splits(const float* p, size_t st, int ns) {
+    V acc[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) acc[r] = zero_v<V>();
+    if (ns == 1) return *reinterpret_cast<const V*>(p);
+    if (ns > 8) sum_rounds<V, 16>(p, st, ns, acc);
+    else sum_rounds<V, 8>(p, st, ns, acc);
+    return add4(add4(add4(acc[0], acc[1]), add4(acc[2], acc[3])), add4(add4(acc[4], acc[5]), add4(acc[6], acc[7])));
+}
+
 __global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegments seg, int p_int, float* grads, float* block_ss) {
     __shared__ float red[256];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    float g = 0.f;
+    const int i = (blockIdx.x * 256 + threadIdx.x) * 4;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < p_int) {
-        int sidx = 0;
-        for (int q = 1; q < seg.n; ++q) if (i >= seg.off[q]) sidx = q;
-        const int local = i - seg.off[sidx];
-        if (local < seg.count[sidx]) {
-            const float* p = seg.partial[sidx] + local;
-            const size_t st = seg.stride[sidx];
-            const int ns = seg.n_split[sidx];
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            int q = 0;
-            for (; q + 8 <= ns; q += 8) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) acc[r] += p[(size_t)(q + r) * st];
-            }
-            for (; q < ns; ++q) acc[0] += p[(size_t)q * st];
-            g = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+        // the segment of element i: every table entry is read with a wave-uniform index (scalar loads of
+        // the kernel arguments) and kept or dropped per lane; a per-lane index into the argument struct
+        // would turn into vector loads from the argument buffer, which lives in host memory
+        const float* base = seg.partial[0];
+        size_t st = seg.stride[0];
+        int off = seg.off[0], count = seg.count[0], ns = seg.n_split[0];
+        for (int q = 1; q < seg.n; ++q) {
+            const bool in = i >= seg.off[q];
+            base = in ? seg.partial[q] : base; st = in ? seg.stride[q] : st;
+            off = in ? seg.off[q] : off; count = in ? seg.count[q] : count; ns = in ? seg.n_split[q] : ns;
         }
-        grads[i] = g;
+        const int local = i - off;
+        const float* p = base + local;
+        if (local + 3 < count && (reinterpret_cast<uintptr_t>(p) & 15) == 0 && (st & 3) == 0) {
+            g = sum_splits<float4>(p, st, ns);
+        } else {
+            if (local < count) g.x = sum_splits<float>(p, st, ns);
+            if (local + 1 < count) g.y = sum_splits<float>(p + 1, st, ns);
+            if (local + 2 < count) g.z = sum_splits<float>(p + 2, st, ns);
+            if (local + 3 < count) g.w = sum_splits<float>(p + 3, st, ns);
+        }
+        if (p != grads + i) *reinterpret_cast<float4*>(grads + i) = g;     // p_int is a multiple of 64; an unsplit gradient may already be in place
     }
-    const float tot = block_sum_256(g * g, red);
+    const float tot = block_sum_256((g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w), red);
     if (threadIdx.x == 0) block_ss[blockIdx.x] = tot;
 }
 
@@ -445,9 +481,6 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, f
     return hipGetLastError();
 }
 
-// Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
-//   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
-// Every block re-derives the norm from the per-block partial sums (same order everywhere).
 // An fp32 number as three bf16 numbers whose sum it is: its 24 significand bits cut into 8 + 8 + 8
 // by truncation (both residuals are exact).  parts: [3][32 k-groups of 8][32 c_out][8] bf16, the
 // order in which the lanes of the first-layer kernel read their MFMA B fragments (16 bytes each).
@@ -473,6 +506,9 @@ hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t*
     return hipGetLastError();
 }
 
+// Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
+//   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
+// Every block re-derives the norm from the per-block partial sums (same order everywhere).
 // w1_parts (may be null): the updated first-layer weights, arena floats [w1_off, w1_off + 256 w1_cout),
 // are also written as their three bf16 parts for the next forward pass.
 __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
@@ -488,8 +524,7 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
     const float clip = hp[HP_CLIP], lr = hp[HP_LR], alpha = hp[HP_ALPHA], eps = hp[HP_EPS];
     const float scale = norm > clip ? clip / norm : 1.0f;
     const float oma = 1.0f - alpha;
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < n4; i += gridDim.x * 256) {
-        float4 g = grads[i], v = g2[i], t = theta[i];
+    auto update = [&](int i, float4 g, float4 v, float4 t) __attribute__((always_inline)) {
         g.x *= scale; g.y *= scale; g.z *= scale; g.w *= scale;
         v.x = alpha * v.x + oma * g.x * g.x; v.y = alpha * v.y + oma * g.y * g.y;
         v.z = alpha * v.z + oma * g.z * g.z; v.w = alpha * v.w + oma * g.w * g.w;
@@ -502,7 +537,16 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
 #pragma unroll
             for (int e = 0; e < 4; ++e) store_split3(tv[e], (e0 + e) % w1_cout, (e0 + e) / w1_cout, w1_parts);
         }
+    };
+    const int stride = gridDim.x * 256;
+    int i = blockIdx.x * 256 + threadIdx.x;
+    for (; i + stride < n4; i += 2 * stride) {                    // two elements' loads in flight
+        const float4 ga = grads[i], va = g2[i], ta = theta[i];
+        const float4 gb = grads[i + stride], vb = g2[i + stride], tb = theta[i + stride];
+        update(i, ga, va, ta);
+        update(i + stride, gb, vb, tb);
     }
+    if (i < n4) update(i, grads[i], g2[i], theta[i]);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         float pl = 0.f, en = 0.f, vl = 0.f;
         for (int b = 0; b < n_loss_blocks; ++b) { pl += loss_partials[b * 4]; en += loss_partials[b * 4 + 1]; vl += loss_partials[b * 4 + 2]; }
