@@ -83,16 +83,20 @@ Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
     if (bf16) {
         p.sel_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, n_e), 64, 256);
         p.trn_fc = plan_split(n.flat, fc_fwd_tiles_bf16(n.arch, p.Bp), 64, 256);
-        for (int l = 0; l < n.n_conv; ++l)
-            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, l == 0 ? 768 : 512);   // the first layer's tile fits three workgroups per CU
+        for (int l = 1; l < n.n_conv; ++l)
+            p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, 512);
         p.fc_wg = plan_split(p.B, fc_wgrad_tiles_bf16(n.arch), 64, 512);
     } else {
         p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
         p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
-        for (int l = 0; l < n.n_conv; ++l)
+        for (int l = 1; l < n.n_conv; ++l)
             p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 64, 256);
         p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 256);
     }
+    // the first layer's weight gradient runs in the direct kernel, one partial per workgroup: three
+    // (bf16) or one and a half (fp32, larger LDS tile) workgroups per compute unit, at most one per band
+    const int c1_cap = bf16 ? 768 : 384;
+    p.wg[0].n = 4 * p.B < c1_cap ? 4 * p.B : c1_cap; p.wg[0].k_per = 0;
     p.head_chunks = p.B / 8 < 1 ? 1 : (p.B / 8 > 128 ? 128 : p.B / 8);
     p.n_loss_blocks = loss_blocks(n_e);
     return p;
@@ -122,7 +126,7 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
         return ptr;
     };
     b.theta = take(a.p_int); b.g2 = take(a.p_int); b.grads = take(a.p_int);
-    b.hp = take(HP_COUNT); b.block_ss = take(norm_blocks(a.p_int)); b.loss_partials = take((size_t)p.n_loss_blocks * 4);
+    b.hp = take(HP_COUNT); b.block_ss = take(norm_blocks_cap(a.p_int)); b.loss_partials = take((size_t)p.n_loss_blocks * 4);
     b.stats = reinterpret_cast<StatsOut*>(take(16));
     for (int l = 0; l < n.n_conv; ++l) {
         const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout;
@@ -374,7 +378,9 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
             });
             continue;
         }
-        if (bf16) L.run(wg_id, [&] { return conv_wgrad_bf16(L.s, n.arch, l, in, (const bf16_t*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
+        if (l == 0)
+            L.run(wg_id, [&] { return conv1_wgrad_direct(L.s, n.arch, !bf16, x.states, b.dact[0], b.pw[0], b.pb[0], p.B, p.wg[0].n); });
+        else if (bf16) L.run(wg_id, [&] { return conv_wgrad_bf16(L.s, n.arch, l, in, (const bf16_t*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
         else L.run(wg_id, [&] { return conv_wgrad(L.s, n.arch, l, in, (const float*)b.dact[l], b.pw[l], b.pb[l], p.B, p.wg[l]); });
         if (l > 0) {
             const int dg_id = l == 2 ? K_TRN_CONV3_DG : K_TRN_CONV2_DG;
@@ -399,9 +405,11 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     seg(b.hd_pb, p.head_chunks, A + 1, A, a.pi_b);
     seg(b.hd_pw + (size_t)A * F, p.head_chunks, (size_t)(A + 1) * F, F, a.v_w);
     seg(b.hd_pb + A, p.head_chunks, A + 1, 1, a.v_b);
-    L.run(K_TRN_GRAD_REDUCE, [&] { return grad_reduce_norm(L.s, g, a.p_int, b.grads, b.block_ss); });
+    const int n_ss = plan_reduce_blocks(g);
+    if (n_ss > norm_blocks_cap(a.p_int)) { *err_id = K_TRN_GRAD_REDUCE; return hipErrorInvalidValue; }
+    L.run(K_TRN_GRAD_REDUCE, [&] { return grad_reduce_norm(L.s, g, b.grads, b.block_ss); });
     L.run(K_TRN_RMSPROP, [&] {
-        return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, b.hp, b.loss_partials, p.n_loss_blocks,
+        return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, n_ss, b.hp, b.loss_partials, p.n_loss_blocks,
                               b.stats, reinterpret_cast<StatsOut*>(x.stats), bf16 ? nullptr : b.w1_parts, a.conv_w[0], n.conv[0].cout);
     });
     if (bf16) L.run(K_TRN_BF16W, [&] { return make_bf16_weights(L.s, b.copies, b.theta); });

@@ -53,9 +53,6 @@ __device__ __forceinline__ uint4 u8x8_to_bf16(uint2 w) {
     return make_uint4(u8pair_to_bf16(cv(w.x, 0), cv(w.x, 8)), u8pair_to_bf16(cv(w.x, 16), cv(w.x, 24)),
                       u8pair_to_bf16(cv(w.y, 0), cv(w.y, 8)), u8pair_to_bf16(cv(w.y, 16), cv(w.y, 24)));
 }
-__device__ __forceinline__ uint4 u8x8_to_bf16_if(bool ok, uint2 w) {      // zeroing on the two raw words
-    return u8x8_to_bf16(make_uint2(ok ? w.x : 0u, ok ? w.y : 0u));
-}
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_ = 3, int MINW_ = 2>
 struct TileB {
@@ -597,32 +594,6 @@ template <class G> struct DgradWeightRowsK8 {
 // ----------------------------------------------------------------------------------------------
 // KRow operands (contiguous along m / n; var = reduction index)
 
-template <class G> struct ConvU8KCols8 {       // A(m = (c,ky,kx), k = output position), 8 kx per load
-    static_assert(G::KS == 8, "one 8-byte load covers one kernel row");
-    static constexpr bool kContig = false, kRowTab = true;
-    typedef uint2 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return u8x8_to_bf16_if(ok, r); }
-    const uint8_t* x; int rows;
-    struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.ok = col < G::KK;
-        col = f.ok ? col : 0;
-        const int c = col / 64, ky = (col % 64) / 8;
-        f.off = c * (G::H * G::W) + ky * G::W;
-        return f;
-    }
-    __device__ __forceinline__ int row_entry(int row) const {       // byte offset of the window's corner, -1 past the end
-        if (row >= rows) return -1;
-        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        return n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST;
-    }
-    __device__ __forceinline__ Raw load_at(const Fixed& f, int ent, bool pred, bool& ok) const {
-        ok = pred && f.ok && ent >= 0;
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(at(x, ok ? ent + f.off : 0));
-        return make_uint2(p[0], p[1]);
-    }
-};
-
 template <class G> struct ConvNHWCKCols8 {     // A(m = (ky,kx,c), k = output position) from bf16 NHWC
     static constexpr bool kContig = false, kRowTab = true;
     typedef uint4 Raw;
@@ -671,19 +642,6 @@ struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col
     __device__ __forceinline__ bf16_t value(float v, float b) const { return f2bf(fmaxf(v * scale + b, 0.f)); }
     __device__ __forceinline__ bf16_t* dst() const { return out; }
     __device__ __forceinline__ const bf16_t* mask() const { return nullptr; }
-};
-
-struct EpiPartialScaled {       // out[z][row][col] = scale * v, column sums of B unscaled
-    static constexpr bool kColSum = true;
-    typedef int Aux;
-    float* out; size_t z_stride; int ldo; float* colsum; int colsum_stride; float scale;
-    __device__ __forceinline__ Aux aux(int, int, int, bool) const { return 0; }
-    __device__ __forceinline__ void store(int row, int col, float v, int z, Aux) const {
-        out[z * z_stride + (size_t)row * ldo + col] = v * scale;
-    }
-    __device__ __forceinline__ void store_colsum(int col, float v, int z) const {
-        colsum[(size_t)z * colsum_stride + col] = v;
-    }
 };
 
 // Data gradient output: row = (n, yy, xx) block of ST x ST input positions, column = (py, px, ci);

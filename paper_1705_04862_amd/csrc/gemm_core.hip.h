@@ -412,12 +412,6 @@ __device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.
 __device__ __forceinline__ float4 keep_if(bool ok, float4 v) {
     return make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
 }
-__device__ __forceinline__ float4 u8x4_to_unit(uint32_t w) {
-    const float s = 1.0f / 255.0f;
-    return make_float4((float)(w & 255u) * s, (float)((w >> 8) & 255u) * s, (float)((w >> 16) & 255u) * s,
-                       (float)(w >> 24) * s);
-}
-
 // All loaders are branch free: an out-of-range coordinate is clamped to a valid address, the load
 // is always issued, and the value is replaced by zero afterwards.  (A load under a branch makes the
 // compiler wait for every outstanding load at the join, which would serialise the prefetch stages.)
@@ -523,29 +517,6 @@ template <class G> struct DgradWeightColsK {
         const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
         const int ky = f.py + G::ST * ty, kx = f.px + G::ST * tx;
         return *reinterpret_cast<const float4*>(f.p + (size_t)(ky * G::KS + kx) * (G::CIN * G::COUT) + co);
-    }
-};
-
-// Weight gradient of the first layer: A(m = (c,ky,kx), k = output position) = byte / 255.
-template <class G> struct ConvU8KCols {
-    static constexpr bool kContig = false;
-    typedef uint32_t Raw;
-    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, u8x4_to_unit(r)); }
-    const uint8_t* x; int rows;
-    struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.ok = col < G::KK;
-        col = f.ok ? col : 0;
-        const int c = col / (G::KS * G::KS), r = col % (G::KS * G::KS), ky = r / G::KS, kx = r % G::KS;
-        f.off = c * (G::H * G::W) + ky * G::W + kx;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int row, bool pred, bool& ok) const {
-        ok = pred && f.ok && row < rows;
-        row = ok ? row : 0;
-        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        const uint8_t* p = x + (size_t)n * (G::CIN * G::H * G::W) + (oy * G::ST) * G::W + ox * G::ST + f.off;
-        return *reinterpret_cast<const uint32_t*>(p);
     }
 };
 

@@ -82,6 +82,8 @@ struct WeightCopies {            // see make_bf16_weights_kernel for the modes
 };
 // first convolution of the fp32 path from the three bf16 parts of its weights, fp32 NHWC output
 hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* w_parts, const float* b, float* out, int ns);
+// first convolution's weight gradient from the image; dy fp32 (exact) or bf16; writes n_wgs partials [256][cout] / [cout]
+hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs);
 hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);
 
 // ---- small kernels (small_kernels.hip) ----
@@ -124,17 +126,33 @@ enum { ALG_ACTOR_CRITIC = 0, ALG_NSTEP_Q = 1 };
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };
 
 constexpr int kMaxSeg = 12;
-inline int norm_blocks(int p_int) { return (p_int + 1023) / 1024; }   // one sum of squares per block of 1024 elements
+// Gradient reduction: one segment per parameter tensor.  A workgroup of the reduction belongs to one
+// segment; a thread owns four consecutive elements and, in segments with many splits, one of eight
+// split lanes (lanes[s] = 8: the splits q = j, j + 8, ... go to lane j, the eight lanes are added as
+// a tree), so that a tensor with hundreds of partial sums is not summed by a handful of threads.
 struct GradSegments {
     int n;
     const float* partial[kMaxSeg]; int n_split[kMaxSeg]; size_t stride[kMaxSeg];
     int count[kMaxSeg]; int off[kMaxSeg]; int padded[kMaxSeg];
+    int lanes[kMaxSeg]; int blk_off[kMaxSeg + 1];         // filled by plan_reduce_blocks
 };
-// grads[i] = sum over splits of the partial gradients; block_ss[norm_blocks(p_int)] = partial sums of g^2
-hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss);
+inline int norm_blocks_cap(int p_int) { return p_int / 128 + 2 * kMaxSeg; }   // upper bound of the reduction's workgroups
+inline int plan_reduce_blocks(GradSegments& g) {
+    int blocks = 0;
+    for (int s = 0; s < g.n; ++s) {
+        const bool vec = (reinterpret_cast<uintptr_t>(g.partial[s]) & 15) == 0 && (g.stride[s] & 3) == 0 && (g.count[s] & 3) == 0;
+        g.lanes[s] = (vec && g.n_split[s] >= 32) ? 8 : 1;
+        g.blk_off[s] = blocks;
+        blocks += (g.padded[s] / 4 * g.lanes[s] + 255) / 256;
+    }
+    g.blk_off[g.n] = blocks;
+    return blocks;
+}
+// grads[i] = sum over splits of the partial gradients; block_ss[workgroup] = partial sums of g^2
+hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, float* grads, float* block_ss);
 struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
-                          const float* block_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
+                          const float* block_ss, int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
                           StatsOut* stats_a, StatsOut* stats_b, bf16_t* w1_parts, int w1_off, int w1_cout);
 // first-layer weights W[k][cout] (fp32) as three bf16 parts [3][32 k-groups][32 c_out][8] whose sum is the weight
 hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t* parts);

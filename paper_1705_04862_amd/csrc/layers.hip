@@ -141,35 +141,29 @@ template <class G> static int wgrad_tiles_t() {
     typedef typename TileForN<G::COUT>::wg T;
     return ((G::KK + T::BM - 1) / T::BM) * ((G::COUT + T::BN - 1) / T::BN);
 }
+// layers 1.. (the first layer's weight gradient runs in conv1_wgrad_direct)
 int conv_wgrad_tiles(int arch, int layer) {
-    if (arch == 0) return layer == 0 ? wgrad_tiles_t<NipsC1>() : wgrad_tiles_t<NipsC2>();
-    return layer == 0 ? wgrad_tiles_t<NatC1>() : layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
+    if (arch == 0) return wgrad_tiles_t<NipsC2>();
+    return layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
 }
 
-template <class G, bool U8>
+template <class G>
 static hipError_t conv_wgrad_t(hipStream_t s, const void* in, const float* dy, float* pw, float* pb, int ns, Split sp) {
     typedef typename TileForN<G::COUT>::wg T;
     const int R = ns * G::HO * G::WO;     // reduction length
     DenseKCols bl{dy, G::COUT, G::COUT};
     EpiPartial<true> ep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
-    if constexpr (U8) {
-        ConvU8KCols<G> al{(const uint8_t*)in, R};
-        return launch_gemm<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
-    } else {
-        ConvNHWCKCols<G> al{(const float*)in, R};
-        return launch_gemm<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
-    }
+    ConvNHWCKCols<G> al{(const float*)in, R};
+    return launch_gemm<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
 }
 
 hipError_t conv_wgrad(hipStream_t s, int arch, int layer, const void* in, const float* dy, float* pw, float* pb,
                       int ns, Split sp) {
     if (arch == 0) {
-        if (layer == 0) return conv_wgrad_t<NipsC1, true>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 1) return conv_wgrad_t<NipsC2, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NipsC2>(s, in, dy, pw, pb, ns, sp);
     } else {
-        if (layer == 0) return conv_wgrad_t<NatC1, true>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 1) return conv_wgrad_t<NatC2, false>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 2) return conv_wgrad_t<NatC3, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NatC2>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 2) return conv_wgrad_t<NatC3>(s, in, dy, pw, pb, ns, sp);
     }
     return hipErrorInvalidValue;
 }

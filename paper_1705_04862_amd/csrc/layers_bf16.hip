@@ -1,6 +1,7 @@
 // Dense layers of the PAAC network with bf16 operands (bf16 activations and weight copies, fp32
 // accumulation and fp32 gradients): the same six contractions as layers.hip on the bf16 GEMM core.
 #include "conv1_direct.hip.h"
+#include "conv1_wgrad_direct.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -52,6 +53,15 @@ hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16
     return launch_conv1_exact<NatC1>(s, x, Wk, b, out, ns);
 }
 
+// First convolution's weight gradient straight from the image (see conv1_wgrad_direct_kernel): dy is
+// fp32 when exact (fp32 path) and bf16 otherwise; n_wgs partials are written.
+hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs) {
+    if (arch == 0) return exact ? launch_conv1_wgrad_direct<NipsC1, true>(s, x, dy, pw, pb, ns, n_wgs)
+                                : launch_conv1_wgrad_direct<NipsC1, false>(s, x, dy, pw, pb, ns, n_wgs);
+    return exact ? launch_conv1_wgrad_direct<NatC1, true>(s, x, dy, pw, pb, ns, n_wgs)
+                 : launch_conv1_wgrad_direct<NatC1, false>(s, x, dy, pw, pb, ns, n_wgs);
+}
+
 // ---------------------------------------------------------------------------------- data gradient
 template <class G>
 static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in, bf16_t* dx, int ns) {
@@ -75,36 +85,29 @@ template <class G> static int wgrad_tiles_t() {
     typedef typename TileBForN<G::COUT>::type T;
     return ((G::KK + T::BM - 1) / T::BM) * ((G::COUT + T::BN - 1) / T::BN);
 }
+// layers 1.. (the first layer's weight gradient runs in conv1_wgrad_direct)
 int conv_wgrad_tiles_bf16(int arch, int layer) {
-    if (arch == 0) return layer == 0 ? wgrad_tiles_t<NipsC1>() : wgrad_tiles_t<NipsC2>();
-    return layer == 0 ? wgrad_tiles_t<NatC1>() : layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
+    if (arch == 0) return wgrad_tiles_t<NipsC2>();
+    return layer == 1 ? wgrad_tiles_t<NatC2>() : wgrad_tiles_t<NatC3>();
 }
 
-template <class G, bool U8>
+template <class G>
 static hipError_t conv_wgrad_t(hipStream_t s, const void* in, const bf16_t* dy, float* pw, float* pb, int ns, Split sp) {
     typedef typename TileBForN<G::COUT>::type T;
     const int R = ns * G::HO * G::WO;
     DenseKCols8 bl{dy, G::COUT, G::COUT};
     EpiPartial<true> ep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
-    if constexpr (U8) {
-        ConvU8KCols8<G> al{(const uint8_t*)in, R};
-        EpiPartialScaled eps{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT, 1.0f / 255.0f};
-        return launch_gemm_bf16<T>(s, al, bl, eps, G::KK, G::COUT, R, sp.n, sp.k_per);
-    } else {
-        ConvNHWCKCols8<G> al{(const bf16_t*)in, R};
-        return launch_gemm_bf16<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
-    }
+    ConvNHWCKCols8<G> al{(const bf16_t*)in, R};
+    return launch_gemm_bf16<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
 }
 
 hipError_t conv_wgrad_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* dy, float* pw, float* pb,
                            int ns, Split sp) {
     if (arch == 0) {
-        if (layer == 0) return conv_wgrad_t<NipsC1, true>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 1) return conv_wgrad_t<NipsC2, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NipsC2>(s, in, dy, pw, pb, ns, sp);
     } else {
-        if (layer == 0) return conv_wgrad_t<NatC1, true>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 1) return conv_wgrad_t<NatC2, false>(s, in, dy, pw, pb, ns, sp);
-        if (layer == 2) return conv_wgrad_t<NatC3, false>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 1) return conv_wgrad_t<NatC2>(s, in, dy, pw, pb, ns, sp);
+        if (layer == 2) return conv_wgrad_t<NatC3>(s, in, dy, pw, pb, ns, sp);
     }
     return hipErrorInvalidValue;
 }

@@ -444,40 +444,65 @@ __device__ __forceinline__ V sum_splits(const float* p, size_t st, int ns) {
     return add4(add4(add4(acc[0], acc[1]), add4(acc[2], acc[3])), add4(add4(acc[4], acc[5]), add4(acc[6], acc[7])));
 }
 
-__global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegments seg, int p_int, float* grads, float* block_ss) {
+__global__ __launch_bounds__(256) void grad_reduce_norm_kernel(const GradSegments seg, float* grads, float* block_ss) {
     __shared__ float red[256];
-    const int i = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int sidx = 0;
+    for (int q = 1; q < seg.n; ++q) if ((int)blockIdx.x >= seg.blk_off[q]) sidx = q;      // uniform: scalar loads of the arguments
+    const int lb = blockIdx.x - seg.blk_off[sidx];
+    const int count = seg.count[sidx], padded = seg.padded[sidx], ns = seg.n_split[sidx];
+    const size_t st = seg.stride[sidx];
     float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < p_int) {
-        // the segment of element i: every table entry is read with a wave-uniform index (scalar loads of
-        // the kernel arguments) and kept or dropped per lane; a per-lane index into the argument struct
-        // would turn into vector loads from the argument buffer, which lives in host memory
-        const float* base = seg.partial[0];
-        size_t st = seg.stride[0];
-        int off = seg.off[0], count = seg.count[0], ns = seg.n_split[0];
-        for (int q = 1; q < seg.n; ++q) {
-            const bool in = i >= seg.off[q];
-            base = in ? seg.partial[q] : base; st = in ? seg.stride[q] : st;
-            off = in ? seg.off[q] : off; count = in ? seg.count[q] : count; ns = in ? seg.n_split[q] : ns;
+    bool owner = true;
+    int local;
+    if (seg.lanes[sidx] == 1) {
+        local = (lb * 256 + tid) * 4;
+        if (local < padded) {
+            const float* p = seg.partial[sidx] + local;
+            if (local + 3 < count && (reinterpret_cast<uintptr_t>(p) & 15) == 0 && (st & 3) == 0) {
+                g = sum_splits<float4>(p, st, ns);
+            } else {
+                if (local < count) g.x = sum_splits<float>(p, st, ns);
+                if (local + 1 < count) g.y = sum_splits<float>(p + 1, st, ns);
+                if (local + 2 < count) g.z = sum_splits<float>(p + 2, st, ns);
+                if (local + 3 < count) g.w = sum_splits<float>(p + 3, st, ns);
+            }
         }
-        const int local = i - off;
-        const float* p = base + local;
-        if (local + 3 < count && (reinterpret_cast<uintptr_t>(p) & 15) == 0 && (st & 3) == 0) {
-            g = sum_splits<float4>(p, st, ns);
-        } else {
-            if (local < count) g.x = sum_splits<float>(p, st, ns);
-            if (local + 1 < count) g.y = sum_splits<float>(p + 1, st, ns);
-            if (local + 2 < count) g.z = sum_splits<float>(p + 2, st, ns);
-            if (local + 3 < count) g.w = sum_splits<float>(p + 3, st, ns);
+    } else {
+        // eight consecutive quads per wave and split lane: lane = j * 8 + quad (128 contiguous bytes per split lane)
+        const int j = lane >> 3;
+        local = ((lb * 4 + wave) * 8 + (lane & 7)) * 4;
+        owner = j == 0;
+        if (local < count) {                                      // count is a multiple of 4 in these segments
+            const float* p = seg.partial[sidx] + local;
+            for (int q = j; q < ns; q += 8 * 16) {
+                float4 v[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = *reinterpret_cast<const float4*>(p + (size_t)min(q + 8 * r, ns - 1) * st);   // clamped: ignored below
+#pragma unroll
+                for (int r = 0; r < 16; ++r) if (q + 8 * r < ns) g = add4(g, v[r]);
+            }
         }
-        if (p != grads + i) *reinterpret_cast<float4*>(grads + i) = g;     // p_int is a multiple of 64; an unsplit gradient may already be in place
+        // lanes j and j^1, then pairs, then halves: ((0+1)+(2+3)) + ((4+5)+(6+7))
+#pragma unroll
+        for (int o = 8; o < 64; o <<= 1) {
+            g.x += __shfl_xor(g.x, o); g.y += __shfl_xor(g.y, o); g.z += __shfl_xor(g.z, o); g.w += __shfl_xor(g.w, o);
+        }
     }
-    const float tot = block_sum_256((g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w), red);
-    if (threadIdx.x == 0) block_ss[blockIdx.x] = tot;
+    float ss = 0.f;
+    if (owner && local < padded) {
+        float* dst = grads + seg.off[sidx] + local;
+        if (seg.partial[sidx] + local != dst) *reinterpret_cast<float4*>(dst) = g;      // an unsplit gradient may already be in place
+        ss = (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
+    }
+    const float tot = block_sum_256(ss, red);
+    if (tid == 0) block_ss[blockIdx.x] = tot;
 }
 
-hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, int p_int, float* grads, float* block_ss) {
-    launch_k(grad_reduce_norm_kernel, dim3(norm_blocks(p_int)), dim3(256), s, seg, p_int, grads, block_ss);
+hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, float* grads, float* block_ss) {
+    const int blocks = seg.blk_off[seg.n];
+    if (blocks < 1) return hipErrorInvalidValue;
+    launch_k(grad_reduce_norm_kernel, dim3(blocks), dim3(256), s, seg, grads, block_ss);
     return hipGetLastError();
 }
 
@@ -562,13 +587,13 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
 }
 
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads, const float* block_ss,
-                          const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b,
+                          int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b,
                           bf16_t* w1_parts, int w1_off, int w1_cout) {
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 512) blocks = 512;       // grid-stride loop: fewer, longer-lived workgroups
     launch_k(rmsprop_update_kernel, dim3(blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
-                       (const float4*)grads, block_ss, norm_blocks(p_int), hp, loss_partials, n_loss_blocks, stats_a, stats_b,
+                       (const float4*)grads, block_ss, n_ss, hp, loss_partials, n_loss_blocks, stats_a, stats_b,
                        w1_parts, w1_off, w1_cout);
     return hipGetLastError();
 }
