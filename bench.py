@@ -201,7 +201,7 @@ def main():
     kind, amount = work[dom]
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not (args.n_e or args.t_max):      # counters were taken at the configuration's own size
         traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
     mfma_peak = PEAK_BF16_MFMA_TFLOPS if cfg.precision == 1 else PEAK_FP32_MFMA_TFLOPS
     if kind == "flop":
