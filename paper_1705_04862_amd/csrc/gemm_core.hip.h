@@ -52,6 +52,16 @@ template <> struct Mma<32> {
     static __device__ __forceinline__ int row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
     static __device__ __forceinline__ int col(int lane) { return lane & 31; }
 };
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <> struct Mma<16> {              // 16 x 16 x 4, 32 cycles: the same rate in a quarter of the output
+    typedef f32x4 Acc;
+    static constexpr int KSTEP = 4, NACC = 4;
+    static __device__ __forceinline__ Acc mma(float a, float b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int r, int lane) { return (lane >> 4) * 4 + r; }
+    static __device__ __forceinline__ int col(int lane) { return lane & 15; }
+};
 // BM x BN x BK tile; the four waves are arranged WM (along m) x WN (along n) x WK (along k): with
 // WK > 1 several waves accumulate the same output fragments over different k-steps of every tile
 // and their accumulators are added through LDS before the epilogue.  This keeps four MFMA pipes

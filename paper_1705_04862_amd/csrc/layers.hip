@@ -25,6 +25,11 @@ typedef Tile<32, 64, 64, 1, 2, 2, 32, 4> T32x64;
 // Measured at n_e = 32: first layer 10.3 -> 9.2 us; a 32x64 eight-wave tile for the 64-wide layers
 // (half the workgroups of the 32x32 tile) was slower, 8.2 -> 9.7 us, and is not used.
 typedef Tile<64, 32, 64, 2, 1, 4, 32, 4> T64x32w8;
+// 16-row tiles on the 16x16x4 MFMA for the smallest launches (a batch of 32 states in the second and
+// third layer): four times the workgroups of the 32x32 tile, a quarter of the chain of MFMAs per wave
+// (n_e = 32: third layer 8.5 -> 6.1 us, second 8.3 -> 7.4 us, arch_nips second layer 5.8 -> 4.4 us; a
+// 16x32 tile was between the two)
+typedef Tile<16, 16, 64, 1, 1, 4, 16, 4> T16x16;
 
 // big / middle / small tile per output width for single launches, pbig / pmid / psmall for launches
 // that pair two GEMMs (four waves each); wg = tile of the weight-gradient GEMMs.  A 16-wide
@@ -53,6 +58,7 @@ static hipError_t launch_auto(hipStream_t s, const AL& al, const BL& bl, const E
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * z; };
     if (wgs(TBig::BM, TBig::BN) >= kMinWgs) return launch_gemm<TBig>(s, al, bl, ep, M, N, K, z, 0);
     if (wgs(TMid::BM, TMid::BN) >= kMinWgs) return launch_gemm<TMid>(s, al, bl, ep, M, N, K, z, 0);
+    if (wgs(TSmall::BM, TSmall::BN) < kMinWgs) return launch_gemm<T16x16>(s, al, bl, ep, M, N, K, z, 0);
     return launch_gemm<TSmall>(s, al, bl, ep, M, N, K, z, 0);
 }
 
