@@ -87,8 +87,8 @@ Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
             p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles_bf16(n.arch, l), 64, 512);
         p.fc_wg = plan_split(p.B, fc_wgrad_tiles_bf16(n.arch), 64, 512);
     } else {
-        p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, 256);
-        p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, 256);
+        p.sel_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, n_e), 32, fc_fwd_target_wgs(n_e));
+        p.trn_fc = plan_split(n.flat, fc_fwd_tiles(n.arch, p.Bp), 32, fc_fwd_target_wgs(p.Bp));
         for (int l = 1; l < n.n_conv; ++l)
             p.wg[l] = plan_split(p.B * n.conv[l].ho * n.conv[l].wo, conv_wgrad_tiles(n.arch, l), 64, 256);
         p.fc_wg = plan_split(p.B, fc_wgrad_tiles(n.arch), 32, 256);

@@ -45,6 +45,7 @@ hipError_t conv_wgrad(hipStream_t s, int arch, int layer, const void* in, const 
                       float* partial_b, int ns, Split sp);
 // fc forward: partial[split][ns][fc] = x[ns][flat(k-range)] . W[flat][fc]   (no bias, no ReLU)
 int fc_fwd_tiles(int arch, int ns);
+int fc_fwd_target_wgs(int ns);
 hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float* partial, int ns, Split sp);
 // dx[ns][flat] = (dh[ns][fc] . W^T) * 1[act > 0]
 hipError_t fc_dgrad(hipStream_t s, int arch, const float* dh, const float* W, const float* act, float* dx, int ns);

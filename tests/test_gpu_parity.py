@@ -623,3 +623,25 @@ def test_actor_loop_runs_algorithm_1_with_the_worker_pool():
     assert s1 == s4
     for k in ("policy_loss", "entropy", "value_loss", "grad_norm"):
         assert abs(s1[k] - sc[k]) <= 1e-4 * max(1.0, abs(s1[k])), (k, s1[k], sc[k])
+
+
+@pytest.mark.parametrize("ci", [1, 2])
+def test_fp32_forward_error_is_at_rounding_level(paac, oracle, ci):
+    """The first layer of the fp32 path runs on the bf16 matrix cores with exact operands (bytes are
+    exact in bf16, weights are three bf16 parts whose sum is the fp32 weight): the forward pass must
+    stay at fp32 rounding level against the double-precision oracle, far inside the 1e-4 bar.
+    (Gradients are not held to this: a ReLU unit whose pre-activation is within rounding of zero can
+    take the other side than in double and moves a whole per-sample term.)"""
+    cfg = I.CONFIGS[ci]
+    ctx = make_ctx(paac, cfg.net, cfg.n_e, cfg.t_max)
+    params = I.config_params(cfg, bias_range=0.05)
+    rms = I.make_rms(1, cfg.net, hi=0.01)
+    ro = I.config_rollout(cfg)
+    ctx.set_state(params, rms)
+    ctx.train_step(dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones), cfg.hp)
+    torch.cuda.synchronize()
+    logits, values, returns = ctx.get_train_outputs()
+    want = oracle.train_step(cfg.net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp)
+    assert relmax(logits, want.logits) < 5e-6
+    assert relmax(values, want.values) < 5e-6
+    assert relmax(returns, want.returns) < 5e-6
