@@ -102,9 +102,14 @@ template <class L, class = void> struct RowFast { static constexpr bool value = 
 template <class L> struct RowFast<L, std::enable_if_t<L::kRowFast>> { static constexpr bool value = true; };
 template <class L> __host__ __device__ constexpr bool row_fast() { return RowFast<L>::value; }
 
-// LDS floats of one workgroup: two buffers per operand
+// LDS floats of one workgroup: two buffers per operand.  An operand that is contiguous along k in
+// memory (kContig) is kept row-major, [row][BK + 4]: a thread stores its four k with one 16-byte store
+// and a lane reads four k of its fragment row with one 16-byte read (the pad makes the pitch an odd
+// multiple of 16 bytes: sixteen rows fall into sixteen different bank groups).  The others are
+// contiguous along the row and are kept k-major, [k][rows + 4].
 template <class T, class AL, class BL> constexpr int gemm_smem_floats() {
-    return 2 * T::BK * (AL::kContig ? T::BM + 1 : T::BM + 4) + 2 * T::BK * (BL::kContig ? T::BN + 1 : T::BN + 4);
+    return 2 * (AL::kContig ? T::BM * (T::BK + 4) : T::BK * (T::BM + 4)) +
+           2 * (BL::kContig ? T::BN * (T::BK + 4) : T::BK * (T::BN + 4));
 }
 
 // One workgroup's share of a GEMM: output tile `tile_idx` (m tiles fastest), k-split `z`.
@@ -113,14 +118,15 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
                                           int m_tiles, int tile_idx, int z, float* smem) {
     typedef Mma<T::MF> MM;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MF = T::MF, TM = T::TM, TN = T::TN;
-    // leading dimensions: odd-ish for transposed scalar stores, multiple of 4 for 16-byte stores
-    constexpr int LDA = AL::kContig ? BM + 1 : BM + 4;
-    constexpr int LDB = BL::kContig ? BN + 1 : BN + 4;
+    // leading dimensions (floats): row pitch of a row-major operand, k pitch of a k-major one
+    constexpr int LDA = AL::kContig ? BK + 4 : BM + 4;
+    constexpr int LDB = BL::kContig ? BK + 4 : BN + 4;
     constexpr int A_F4 = BM * BK / 4, B_F4 = BN * BK / 4;
     constexpr int NT = T::NT;
     constexpr int A_IT = (A_F4 + NT - 1) / NT, B_IT = (B_F4 + NT - 1) / NT;
 
-    constexpr int A_BUF = BK * LDA, B_BUF = BK * LDB;      // floats per LDS buffer (multiples of 4)
+    constexpr int A_BUF = AL::kContig ? BM * LDA : BK * LDA;      // floats per LDS buffer (multiples of 4)
+    constexpr int B_BUF = BL::kContig ? BN * LDB : BK * LDB;
     static_assert(2 * A_BUF + 2 * B_BUF == gemm_smem_floats<T, AL, BL>(), "LDS size");
     float* const As = smem;                 // As[buf] = As + buf * A_BUF
     float* const Bs = smem + 2 * A_BUF;
@@ -148,7 +154,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
             const int kq = row_fast<AL>() ? f / BM : f % (BK / 4), row = row_fast<AL>() ? f % BM : f / (BK / 4);
             afix[i] = al.prep(m0 + row, z);
             a_var[i] = kq * 4;
-            a_lds[i] = (kq * 4) * LDA + row;
+            a_lds[i] = row * LDA + kq * 4;
         } else {
             const int mq = f % (BM / 4), k = f / (BM / 4);
             afix[i] = al.prep(m0 + mq * 4, z);
@@ -163,7 +169,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
             const int kq = f % (BK / 4), col = f / (BK / 4);
             bfix[i] = bl.prep(n0 + col, z);
             b_var[i] = kq * 4;
-            b_lds[i] = (kq * 4) * LDB + col;
+            b_lds[i] = col * LDB + kq * 4;
         } else {
             const int nq = f % (BN / 4), k = f / (BN / 4);
             bfix[i] = bl.prep(n0 + nq * 4, z);
@@ -209,16 +215,14 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
             if (A_F4 % NT == 0 || tid + i * NT < A_F4) {
                 float* p = As + buf * A_BUF + a_lds[i];
                 const float4 v = AL::finish(areg[G][i], (okbits[G] >> i) & 1u);
-                if (AL::kContig) { p[0] = v.x; p[LDA] = v.y; p[2 * LDA] = v.z; p[3 * LDA] = v.w; }
-                else *reinterpret_cast<float4*>(p) = v;
+                *reinterpret_cast<float4*>(p) = v;
             }
         } else {
             constexpr int i = u - A_IT;
             if (B_F4 % NT == 0 || tid + i * NT < B_F4) {
                 float* p = Bs + buf * B_BUF + b_lds[i];
                 const float4 v = BL::finish(breg[G][i], (okbits[G] >> (16 + i)) & 1u);
-                if (BL::kContig) { p[0] = v.x; p[LDB] = v.y; p[2 * LDB] = v.z; p[3 * LDB] = v.w; }
-                else *reinterpret_cast<float4*>(p) = v;
+                *reinterpret_cast<float4*>(p) = v;
             }
         }
     };
@@ -251,7 +255,8 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     // of one staging unit placed after an MFMA runs in its shadow instead of after the last MFMA
     // (at small batch a wave has its SIMD to itself, nothing else would fill the gap).  The
     // scheduling barriers keep the compiler from regrouping it.
-    constexpr int NS = BK / MM::KSTEP / T::WK;      // k-steps of this wave: wk, wk + WK, ...
+    constexpr int NS = BK / MM::KSTEP / T::WK;      // k-steps of this wave
+    static_assert(NS % 4 == 0, "k-steps are taken in groups of four");
     constexpr int UNITS = A_IT + B_IT;
     static_assert(UNITS <= NS, "at most one staging unit per k-step");
     auto compute_and_store = [&](int buf, auto stage_next, int buf_next) {
@@ -259,14 +264,33 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         const float* bs = Bs + buf * B_BUF;
         // every LDS read of the tile is issued before the first MFMA: one LDS latency per tile
         // instead of one per group of MFMAs
+        // k-wave wk owns the k range [wk NS KSTEP, (wk + 1) NS KSTEP) of the tile; within it MFMA step
+        // 4 g + j of lane-group fk multiplies k = 4 KSTEP g + 4 fk + j (any order of k is a valid dot
+        // product as long as both operands use it): four consecutive k per lane and group of four steps
         float a[NS][TM], b[NS][TN];
 #pragma unroll
-        for (int st = 0; st < NS; ++st) {
-            const int krow = (st * T::WK + wk) * MM::KSTEP + fk;
+        for (int g = 0; g < NS / 4; ++g) {
+            const int k0 = (wk * NS + 4 * g) * MM::KSTEP + 4 * fk;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[st][i] = as[krow * LDA + a_base + i * MF];
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (AL::kContig) {
+                    const float4 v = *reinterpret_cast<const float4*>(as + (a_base + i * MF) * LDA + k0);
+                    a[4 * g][i] = v.x; a[4 * g + 1][i] = v.y; a[4 * g + 2][i] = v.z; a[4 * g + 3][i] = v.w;
+                } else {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[st][j] = bs[krow * LDB + b_base + j * MF];
+                    for (int j = 0; j < 4; ++j) a[4 * g + j][i] = as[(k0 + j) * LDA + a_base + i * MF];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                if constexpr (BL::kContig) {
+                    const float4 v = *reinterpret_cast<const float4*>(bs + (b_base + i * MF) * LDB + k0);
+                    b[4 * g][i] = v.x; b[4 * g + 1][i] = v.y; b[4 * g + 2][i] = v.z; b[4 * g + 3][i] = v.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) b[4 * g + j][i] = bs[(k0 + j) * LDB + b_base + i * MF];
+                }
+            }
         }
         [&]<int... ST>(std::integer_sequence<int, ST...>) {
             ([&] {
@@ -290,7 +314,7 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         if constexpr (EP::kColSum) {
             if (mt == 0 && tid < BN) {
 #pragma unroll 8
-                for (int k = 0; k < BK; ++k) colsum += bs[k * LDB + tid];
+                for (int k = 0; k < BK; ++k) colsum += BL::kContig ? bs[tid * LDB + k] : bs[k * LDB + tid];
             }
         }
     };
