@@ -6,12 +6,14 @@
 //   C[m][n] = sum_k A(m,k) * B(k,n)          m < M, n < N, k in this workgroup's k-range
 //
 // A workgroup of 4 (or 8) wavefronts of 64 owns a BM x BN tile.  Both operands are staged
-// through LDS in k-major order (As[k][m], Bs[k][n]) so that the 32 lanes that feed one
-// MFMA operand read consecutive words: bank-conflict free without swizzling.  An operand whose
-// global layout is contiguous along k ("kContig") is transposed on its way into LDS; an operand
-// contiguous along m/n is copied with 16-byte stores.  Global loads run S k-tiles ahead of the
+// through LDS.  An operand whose global layout is contiguous along k ("kContig") is kept row-major,
+// [row][BK + 4]: one 16-byte store per thread and one 16-byte fragment read per lane and four MFMA
+// steps (a lane takes four consecutive k; the order in which the k of a tile are multiplied is free).
+// An operand contiguous along m/n is kept k-major, [k][rows + 4], copied with 16-byte stores and read
+// word by word (32 consecutive lanes read consecutive words).  Global loads run S k-tiles ahead of the
 // MFMAs through S register stages (two LDS buffers, one barrier per tile): these layers are bound by
-// memory latency, not bandwidth, at the paper's batch sizes.
+// memory latency, not bandwidth, at the paper's batch sizes.  MFMA fragments are 32x32x2 or, for the
+// smallest launches, 16x16x4.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
