@@ -556,6 +556,31 @@ template <class G> struct DgradWeightColsK {
     }
 };
 
+// The same with all ST*ST parity classes as columns, n = (z, ci): the classes of one block of input
+// positions read the same gathered dY rows, so one GEMM with N = ST*ST*CIN gathers them once.
+template <class G> struct DgradWeightColsKAll {
+    static constexpr bool kContig = true;
+    typedef float4 Raw;
+    static __device__ __forceinline__ float4 finish(Raw r, bool ok) { return keep_if(ok, r); }
+    const float* w;
+    struct Fixed { const float* p; int py, px; bool ok; };
+    __device__ __forceinline__ Fixed prep(int col, int) const {
+        Fixed f; f.ok = col < G::ST * G::ST * G::CIN;
+        col = f.ok ? col : 0;
+        const int z = col / G::CIN, ci = col % G::CIN;
+        f.py = z / G::ST; f.px = z % G::ST;
+        f.p = w + (size_t)ci * G::COUT;
+        return f;
+    }
+    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
+        ok = pred && f.ok;
+        k = ok ? k : 0;
+        const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
+        const int ky = f.py + G::ST * ty, kx = f.px + G::ST * tx;
+        return *reinterpret_cast<const float4*>(f.p + (size_t)(ky * G::KS + kx) * (G::CIN * G::COUT) + co);
+    }
+};
+
 // Weight gradient of the later conv layers: A(m = (ky,kx,c), k = output position) from NHWC input.
 template <class G> struct ConvNHWCKCols {
     static constexpr bool kContig = false;
@@ -615,6 +640,21 @@ template <class G> struct EpiDgradMask {     // scatter a parity class back to N
     __device__ __forceinline__ Aux aux(int row, int col, int z, bool ok) const { return act[ok ? addr(row, col, z) : 0]; }
     __device__ __forceinline__ void store(int row, int col, float v, int z, Aux a) const {
         dx[addr(row, col, z)] = a > 0.f ? v : 0.f;
+    }
+};
+
+template <class G> struct EpiDgradMaskAll {  // the same for columns n = (z, ci) of all parity classes
+    static constexpr bool kColSum = false;
+    typedef float Aux;
+    float* dx; const float* act;
+    __device__ __forceinline__ size_t addr(int row, int col) const {
+        const int z = col / G::CIN, ci = col % G::CIN, py = z / G::ST, px = z % G::ST;
+        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
+        return ((size_t)(n * G::H + yy * G::ST + py) * G::W + xx * G::ST + px) * G::CIN + ci;
+    }
+    __device__ __forceinline__ Aux aux(int row, int col, int, bool ok) const { return act[ok ? addr(row, col) : 0]; }
+    __device__ __forceinline__ void store(int row, int col, float v, int, Aux a) const {
+        dx[addr(row, col)] = a > 0.f ? v : 0.f;
     }
 };
 

@@ -31,6 +31,10 @@ typedef Tile<64, 32, 64, 2, 1, 4, 32, 4> T64x32w8;
 // 16x32 tile was between the two)
 typedef Tile<16, 16, 64, 1, 1, 4, 16, 4> T16x16;
 
+// wide tiles for the data gradient of a strided layer with all parity classes as columns
+typedef Tile<64, 128, 32, 2, 2, 1, 32, 3> T64x128;
+typedef Tile<32, 128, 32, 1, 4, 1, 32, 3> T32x128;
+
 // big / middle / small tile per output width for single launches, pbig / pmid / psmall for launches
 // that pair two GEMMs (four waves each); wg = tile of the weight-gradient GEMMs.  A 16-wide
 // output (first layer of arch_nips) runs on the 32-wide tiles: the upper 16 columns load zeros and
@@ -188,6 +192,17 @@ static hipError_t conv_bwd_pair(hipStream_t s, const float* dy, const float* W, 
     return launch_pair(s, make_call<TD>(al, bl, ep, M, G::CIN, G::KD, G::ST * G::ST, 0), wcall);
 }
 
+// A strided layer's parity classes share their gathered dY rows: all classes as columns of one GEMM.
+template <class TD, class G, class CW>
+static hipError_t conv_bwd_pair_all(hipStream_t s, const float* dy, const float* W, const float* act_in, float* dx, int ns,
+                                    const CW& wcall) {
+    const int M = ns * G::HC * G::WC;
+    DgradGatherRowsK<G> al{dy, M};
+    DgradWeightColsKAll<G> bl{W};
+    EpiDgradMaskAll<G> ep{dx, act_in};
+    return launch_pair(s, make_call<TD>(al, bl, ep, M, G::ST * G::ST * G::CIN, G::KD, 1, 0), wcall);
+}
+
 template <class G>
 static hipError_t conv_bwd_t(hipStream_t s, const float* act_in, const float* dy, const float* W, float* dx, float* pw,
                              float* pb, int ns, Split sp) {
@@ -197,6 +212,16 @@ static hipError_t conv_bwd_t(hipStream_t s, const float* act_in, const float* dy
     DenseKCols wbl{dy, G::COUT, G::COUT};
     EpiPartial<true> wep{pw, (size_t)G::KK * G::COUT, G::COUT, pb, G::COUT};
     const auto wcall = make_call<typename TileForN<G::COUT>::wg>(wal, wbl, wep, G::KK, G::COUT, R, sp.n, sp.k_per);
+    if constexpr (G::ST > 1) {
+        constexpr int NA = G::ST * G::ST * G::CIN;
+        if constexpr (NA == 128) {
+            if ((M + 63) / 64 >= kMinWgs) return conv_bwd_pair_all<T64x128, G>(s, dy, W, act_in, dx, ns, wcall);
+            if ((M + 31) / 32 >= kMinWgs) return conv_bwd_pair_all<T32x128, G>(s, dy, W, act_in, dx, ns, wcall);
+        } else if constexpr (NA == 64) {
+            if ((M + 63) / 64 >= kMinWgs) return conv_bwd_pair_all<T64x64, G>(s, dy, W, act_in, dx, ns, wcall);
+            if ((M + 31) / 32 >= kMinWgs) return conv_bwd_pair_all<T32x64, G>(s, dy, W, act_in, dx, ns, wcall);
+        }
+    }
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((G::CIN + bn - 1) / bn) * z; };
     if (wgs(TS::pbig::BM, TS::pbig::BN) >= kMinWgs) return conv_bwd_pair<typename TS::pbig, G>(s, dy, W, act_in, dx, ns, wcall);
     if (wgs(TS::pmid::BM, TS::pmid::BN) >= kMinWgs) return conv_bwd_pair<typename TS::pmid, G>(s, dy, W, act_in, dx, ns, wcall);
