@@ -50,8 +50,7 @@ def kernel_work(net, n_e, t_max):
         w[f"train.conv{l + 1}_bwd"] = ("flop", 2 * conv[l] * B)
     w["select.heads_sample"] = ("flop", hd * n_e)
     w["train.heads_fwd"] = ("flop", hd * Bp)
-    w["train.heads_dh"] = ("flop", hd * B)
-    w["train.heads_wgrad"] = ("flop", hd * B)
+    w["train.heads_bwd"] = ("flop", 2 * hd * B)
     w["train.returns_loss"] = ("byte", 4.0 * (Bp * (A + 1) + B * (A + 4)))
     w["train.grad_reduce_norm"] = ("byte", 8.0 * P)      # read one gradient copy, write the arena
     w["train.clip_rmsprop"] = ("byte", 20.0 * P)         # read theta, g, g2; write theta, g2

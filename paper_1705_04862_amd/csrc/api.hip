@@ -167,14 +167,14 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
 
 enum KernelId {
     K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
-    K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_DH, K_TRN_HEADS_WG,
+    K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_BWD,
     K_TRN_FC_WG, K_TRN_FC_DG, K_TRN_CONV3_WG, K_TRN_CONV3_DG, K_TRN_CONV2_WG, K_TRN_CONV2_DG, K_TRN_CONV1_WG,
     K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_TRN_FC_BWD, K_TRN_CONV3_BWD, K_TRN_CONV2_BWD, K_COUNT
 };
 const char* const kKernelNames[K_COUNT] = {
     "select.conv1_fwd", "select.conv2_fwd", "select.conv3_fwd", "select.fc_fwd", "select.heads_sample",
     "train.conv1_fwd", "train.conv2_fwd", "train.conv3_fwd", "train.fc_fwd", "train.heads_fwd", "train.returns_loss",
-    "train.heads_dh", "train.heads_wgrad", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
+    "train.heads_bwd", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
     "train.conv3_dgrad", "train.conv2_wgrad", "train.conv2_dgrad", "train.conv1_wgrad", "train.grad_reduce_norm",
     "train.clip_rmsprop", "train.bf16_weight_copies", "train.fc_bwd", "train.conv3_bwd", "train.conv2_bwd"};
 
@@ -352,11 +352,10 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     // heads backward
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
     float* const fc_pw = p.fc_wg.n > 1 ? b.fc_pw : b.grads + a.fc_w;
-    L.run(K_TRN_HEADS_DH, [&] {
-        return heads_dh(L.s, F, A, p.B, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, bf16 ? nullptr : (float*)b.dh,
-                        bf16 ? (bf16_t*)b.dh : nullptr);
+    L.run(K_TRN_HEADS_BWD, [&] {
+        return heads_bwd(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, bf16 ? nullptr : (float*)b.dh,
+                         bf16 ? (bf16_t*)b.dh : nullptr, b.hd_pw, b.hd_pb);
     });
-    L.run(K_TRN_HEADS_WG, [&] { return heads_wgrad(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.h, b.hd_pw, b.hd_pb); });
     // fc backward
     if (bf16) {
         L.run(K_TRN_FC_WG, [&] { return fc_wgrad_bf16(L.s, n.arch, (const bf16_t*)b.act[last], (const bf16_t*)b.dh, fc_pw, b.fc_pb, p.B, p.fc_wg); });

@@ -116,12 +116,10 @@ struct LossArgs {
 int loss_blocks(int n_e);
 hipError_t returns_loss(hipStream_t s, const LossArgs& a);
 
-// dh is written as fp32 (dh) or, when dh_b is non-null, as bf16 (dh_b)
-hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
-                    const float* v_w, const float* h, float* dh, bf16_t* dh_b);
+// head backward in one launch: dh (fp32, or bf16 when dh_b is non-null) and the split weight gradients
 // partial_w[chunk][A+1][F] (row A = value head), partial_b[chunk][A+1]
-hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
-                       const float* h, float* partial_w, float* partial_b);
+hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv, const float* pi_w,
+                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* partial_w, float* partial_b);
 
 enum { ALG_ACTOR_CRITIC = 0, ALG_NSTEP_Q = 1 };
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };

@@ -333,45 +333,42 @@ hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
 }
 
 // ------------------------------------------------------------------------------------ head backward
-// dh[row][j] = 1[h > 0] * (sum_a dz[row][a] pi_w[a][j] + dv[row] v_w[j])
-__global__ __launch_bounds__(256) void heads_dh_kernel(int F4, int A, int rows, const float* dz, const float* dv,
-                                                       const float* pi_w, const float* v_w, const float* h, float* dh,
-                                                       bf16_t* dh_b) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * F4) return;
-    const int row = idx / F4, j = (idx % F4) * 4, F = F4 * 4;
-    const float d = dv[row];
-    const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
-    float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
-    for (int k = 0; k < A; ++k) {
-        const float g = dz[(size_t)row * A + k];
-        const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
-        acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+// Two independent jobs that both start from dz / dv share one launch (at the paper's batch each is a
+// few microseconds of latency, and a kernel boundary costs 2.5):
+//   blocks [0, n_dh):  dh[row][j] = 1[h > 0] * (sum_a dz[row][a] pi_w[a][j] + dv[row] v_w[j])
+//   the others:        partial_w[chunk][a][j] = sum over the chunk's rows of coef(row, a) * h[row][j],
+//                      coef = dz (a < A) or dv (a == A); partial_b[chunk][a] = sum of coef.
+__global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, int n_dh, int rows_per_chunk, const float* dz,
+                                                        const float* dv, const float* pi_w, const float* v_w, const float* h,
+                                                        float* dh, bf16_t* dh_b, float* pw, float* pb) {
+    if ((int)blockIdx.x < n_dh) {
+        const int F4 = F / 4;
+        const int idx = blockIdx.x * 256 + threadIdx.x;
+        if (idx >= rows * F4) return;
+        const int row = idx / F4, j = (idx % F4) * 4;
+        const float d = dv[row];
+        const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
+        float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
+        for (int k = 0; k < A; ++k) {
+            const float g = dz[(size_t)row * A + k];
+            const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
+            acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+        }
+        const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
+        acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
+        acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
+        if (dh_b) {
+            auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
+            *reinterpret_cast<uint2*>(dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
+        } else {
+            *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+        }
+        return;
     }
-    const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
-    acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
-    acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
-    if (dh_b) {
-        auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
-        *reinterpret_cast<uint2*>(dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
-    } else {
-        *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
-    }
-}
-
-hipError_t heads_dh(hipStream_t s, int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
-                    const float* v_w, const float* h, float* dh, bf16_t* dh_b) {
-    const int n = rows * (F / 4);
-    launch_k(heads_dh_kernel, dim3((n + 255) / 256), dim3(256), s, F / 4, A, rows, dz, dv, pi_w, v_w, h, dh, dh_b);
-    return hipGetLastError();
-}
-
-// partial_w[chunk][a][j] = sum over the chunk's rows of coef(row, a) * h[row][j], coef = dz (a < A)
-// or dv (a == A); partial_b[chunk][a] = sum of coef.
-__global__ __launch_bounds__(256) void heads_wgrad_kernel(int F, int A, int rows, int rows_per_chunk, const float* dz,
-                                                          const float* dv, const float* h, float* pw, float* pb) {
-    const int j = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y, c = blockIdx.z;
-    const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+    // weight-gradient block (x: 256 hidden units, k: output, c: chunk of rows)
+    const int wb = blockIdx.x - n_dh, fx = F / 256;
+    const int j = (wb % fx) * 256 + threadIdx.x, k = (wb / fx) % (A + 1), c = wb / (fx * (A + 1));
+    const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);      // a trailing chunk may be empty: zeros
     float acc = 0.f, accb = 0.f;
     for (int r = r0; r < r1; r += 8) {                 // eight rows of loads in flight
         float g[8], hv[8];
@@ -390,10 +387,13 @@ __global__ __launch_bounds__(256) void heads_wgrad_kernel(int F, int A, int rows
     if (j == 0) pb[c * (A + 1) + k] = accb;
 }
 
-hipError_t heads_wgrad(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv,
-                       const float* h, float* pw, float* pb) {
+hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv, const float* pi_w,
+                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* pw, float* pb) {
+    if (rows <= 0 || n_chunk <= 0 || F % 256 != 0) return hipErrorInvalidValue;
+    const int n_dh = (rows * (F / 4) + 255) / 256;
     const int rpc = (rows + n_chunk - 1) / n_chunk;
-    launch_k(heads_wgrad_kernel, dim3(F / 256, A + 1, n_chunk), dim3(256), s, F, A, rows, rpc, dz, dv, h, pw, pb);
+    launch_k(heads_bwd_kernel, dim3(n_dh + (F / 256) * (A + 1) * n_chunk), dim3(256), s, F, A, rows, n_dh, rpc, dz, dv, pi_w, v_w, h,
+             dh, dh_b, pw, pb);
     return hipGetLastError();
 }
 
