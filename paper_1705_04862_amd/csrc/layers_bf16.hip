@@ -2,6 +2,7 @@
 // accumulation and fp32 gradients): the same six contractions as layers.hip on the bf16 GEMM core.
 #include "conv1_direct.hip.h"
 #include "conv1_wgrad_direct.hip.h"
+#include "conv_dgrad_direct.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -74,8 +75,9 @@ static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd
 
 hipError_t conv_dgrad_bf16(hipStream_t s, int arch, int layer, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in,
                            bf16_t* dx, int ns) {
-    if (arch == 0 && layer == 1) return conv_dgrad_t<NipsC2>(s, dy, Wd, act_in, dx, ns);
-    if (arch == 1 && layer == 1) return conv_dgrad_t<NatC2>(s, dy, Wd, act_in, dx, ns);
+    // the strided second layer: one sample at a time from LDS; the third layer: gather-form GEMM
+    if (arch == 0 && layer == 1) return launch_conv_dgrad_direct<NipsC2>(s, dy, Wd, act_in, dx, ns);
+    if (arch == 1 && layer == 1) return launch_conv_dgrad_direct<NatC2>(s, dy, Wd, act_in, dx, ns);
     if (arch == 1 && layer == 2) return conv_dgrad_t<NatC3>(s, dy, Wd, act_in, dx, ns);
     return hipErrorInvalidValue;
 }
