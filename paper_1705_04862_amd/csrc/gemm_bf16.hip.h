@@ -526,71 +526,6 @@ struct DenseRowsK8 {            // element (row, k) = base[row*ld + k]
     }
 };
 
-// Data gradient, gather form (see DgradGatherRowsK): k = (ty, tx, co), co in groups of 8.  The row
-// part is the offset of dy[n][yy][xx][0] (a position that need not exist), the k part moves it back
-// by the tap; which taps fall inside the output map is a per-row bit mask.
-template <class G> struct DgradGatherRowsK8 {
-    static constexpr bool kContig = true;
-    static constexpr bool kRowFast = true;
-    static_assert(G::TAPS * G::TAPS <= 31, "tap mask");
-    typedef uint4 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
-    const bf16_t* dy; int rows;
-    struct Fixed { int off; unsigned taps; };
-    __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f;
-        const bool rok = row < rows;
-        row = rok ? row : 0;
-        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
-        f.off = ((n * (G::HO * G::WO) + yy * G::WO + xx) * G::COUT) * 2;
-        unsigned m = 0;
-#pragma unroll
-        for (int t = 0; t < G::TAPS * G::TAPS; ++t) {
-            const int oy = yy - t / G::TAPS, ox = xx - t % G::TAPS;
-            m |= (oy >= 0 && oy < G::HO && ox >= 0 && ox < G::WO) ? (1u << t) : 0u;
-        }
-        f.taps = rok ? m : 0u;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        k = pred ? k : 0;
-        const int tap = k / G::COUT, co = k % G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
-        ok = pred && ((f.taps >> tap) & 1u);
-        const int off = f.off + (co - (ty * G::WO + tx) * G::COUT) * 2;
-        return *reinterpret_cast<const uint4*>(at(dy, ok ? off : 0));
-    }
-};
-
-// Weights seen by the data gradient, from the bf16 copy laid out [ci][ky][kx][co].  All ST*ST parity
-// classes of input positions share the gathered dY rows (the taps (ty, tx) reach the same output
-// positions whatever the class), so the classes are columns of ONE GEMM:
-//   B(k = (ty,tx,co), n = (py,px,ci)) = W[ci][py + ST*ty][px + ST*tx][co].
-template <class G> struct DgradWeightRowsK8 {
-    static constexpr bool kContig = true;
-    static constexpr int NCOL = G::ST * G::ST * G::CIN;
-    typedef uint4 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
-    const bf16_t* w;
-    struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int col, int) const {
-        Fixed f; f.ok = col < NCOL;
-        col = f.ok ? col : 0;
-        const int cls = col / G::CIN, ci = col % G::CIN, py = cls / G::ST, px = cls % G::ST;
-        f.off = (ci * (G::KS * G::KS) + py * G::KS + px) * G::COUT * 2;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        ok = pred && f.ok;
-        k = pred ? k : 0;
-        // a 64-wide k tile lies inside one tap when COUT is a multiple of 64: the tap is then the same
-        // for every lane of the wave
-        int tap = k / G::COUT;
-        if (G::COUT % 64 == 0) tap = __builtin_amdgcn_readfirstlane(tap);
-        const int co = k - tap * G::COUT, ty = tap / G::TAPS, tx = tap % G::TAPS;
-        return *reinterpret_cast<const uint4*>(at(w, f.off + ((G::ST * ty * G::KS + G::ST * tx) * G::COUT + co) * 2));
-    }
-};
-
 // ----------------------------------------------------------------------------------------------
 // KRow operands (contiguous along m / n; var = reduction index)
 
@@ -642,25 +577,6 @@ struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col
     __device__ __forceinline__ bf16_t value(float v, float b) const { return f2bf(fmaxf(v * scale + b, 0.f)); }
     __device__ __forceinline__ bf16_t* dst() const { return out; }
     __device__ __forceinline__ const bf16_t* mask() const { return nullptr; }
-};
-
-// Data gradient output: row = (n, yy, xx) block of ST x ST input positions, column = (py, px, ci);
-// element goes to dx[n][yy*ST + py][xx*ST + px][ci], times ReLU'(act) at the same place.
-template <class G> struct EpiDgradMaskB {
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = true, kColMap = true, kMask = true, kBias = false;
-    static_assert(G::CIN % 8 == 0, "eight consecutive columns stay inside one parity class");
-    bf16_t* dx; const bf16_t* act; const float* bias;
-    __device__ __forceinline__ int row_entry(int row, int) const {
-        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
-        return ((n * G::H + yy * G::ST) * G::W + xx * G::ST) * G::CIN;
-    }
-    __device__ __forceinline__ int col_off(int col) const {
-        const int cls = col / G::CIN, ci = col % G::CIN;
-        return ((cls / G::ST) * G::W + cls % G::ST) * G::CIN + ci;
-    }
-    __device__ __forceinline__ bf16_t value(float v, float) const { return f2bf(v); }
-    __device__ __forceinline__ bf16_t* dst() const { return dx; }
-    __device__ __forceinline__ const bf16_t* mask() const { return act; }
 };
 
 struct EpiDenseMaskB {          // out[row][col] = v * 1[act[row][col] > 0]

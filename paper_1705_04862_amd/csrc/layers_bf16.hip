@@ -64,21 +64,12 @@ hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t
 }
 
 // ---------------------------------------------------------------------------------- data gradient
-template <class G>
-static hipError_t conv_dgrad_t(hipStream_t s, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in, bf16_t* dx, int ns) {
-    const int M = ns * G::HC * G::WC;                // blocks of ST x ST input positions
-    DgradGatherRowsK8<G> al{dy, M};
-    DgradWeightRowsK8<G> bl{Wd};
-    EpiDgradMaskB<G> ep{dx, act_in, nullptr};
-    return launch_gemm_bf16<B128x64>(s, al, bl, ep, M, G::ST * G::ST * G::CIN, G::KD, 1, 0);
-}
-
 hipError_t conv_dgrad_bf16(hipStream_t s, int arch, int layer, const bf16_t* dy, const bf16_t* Wd, const bf16_t* act_in,
                            bf16_t* dx, int ns) {
-    // the strided second layer: one sample at a time from LDS; the third layer: gather-form GEMM
+    // one sample at a time from LDS
     if (arch == 0 && layer == 1) return launch_conv_dgrad_direct<NipsC2>(s, dy, Wd, act_in, dx, ns);
     if (arch == 1 && layer == 1) return launch_conv_dgrad_direct<NatC2>(s, dy, Wd, act_in, dx, ns);
-    if (arch == 1 && layer == 2) return conv_dgrad_t<NatC3>(s, dy, Wd, act_in, dx, ns);
+    if (arch == 1 && layer == 2) return launch_conv_dgrad_direct_s1<NatC3>(s, dy, Wd, act_in, dx, ns);
     return hipErrorInvalidValue;
 }
 
