@@ -49,12 +49,12 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
     }
 
     // raw data of a sample in registers: dY one sample ahead of the MFMAs, the mask during the epilogue
-    uint4 pdy[DY_IT], pact[DX_IT];
+    u32x4 pdy[DY_IT], pact[DX_IT];
 #define PAAC_PREFETCH_DY(S_)                                                                                             \
     {                                                                                                                    \
         const bf16_t* base_ = dy + (size_t)(S_) * (G::HO * G::WO * COUT);                                                \
         _Pragma("unroll") for (int i = 0; i < DY_IT; ++i)                                                                \
-            pdy[i] = *reinterpret_cast<const uint4*>(base_ + (size_t)min(tid + i * 256, DY_CH - 1) * 8);                 \
+            pdy[i] = *reinterpret_cast<const u32x4*>(base_ + (size_t)min(tid + i * 256, DY_CH - 1) * 8);                 \
     }
     int s = blockIdx.x;
     if (s >= ns) return;
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
             const int ch = tid + i * 256;
             if (ch < DY_CH) {
                 const int pos = ch / (COUT / 8), c8 = ch % (COUT / 8);
-                *reinterpret_cast<uint4*>(dyp + ((pos / G::WO + 1) * PADW + (pos % G::WO + 1)) * PP + c8 * 8) = pdy[i];
+                *reinterpret_cast<u32x4*>(dyp + ((pos / G::WO + 1) * PADW + (pos % G::WO + 1)) * PP + c8 * 8) = pdy[i];
             }
         }
         __syncthreads();                               // also: the previous sample's dX image has been read
@@ -90,14 +90,14 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
         // the fragments of k-step ks + 1 are read while those of ks are multiplied (the scheduling barriers
         // keep the reads ahead: read-wait-multiply in a row would expose the LDS latency 64 times a sample)
         auto koff = [](int ks) { return (ks % CS) * 16 - (((ks / CS) >> 1) * PADW + ((ks / CS) & 1)) * PP; };   // constant after unrolling
-        uint4 a_cur[FRAGS], a_nxt[FRAGS];
+        u32x4 a_cur[FRAGS], a_nxt[FRAGS];
 #pragma unroll
-        for (int f = 0; f < FRAGS; ++f) a_cur[f] = *reinterpret_cast<const uint4*>(dyp + a_off[f] + koff(0));
+        for (int f = 0; f < FRAGS; ++f) a_cur[f] = *reinterpret_cast<const u32x4*>(dyp + a_off[f] + koff(0));
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             if (ks + 1 < KSTEPS) {
 #pragma unroll
-                for (int f = 0; f < FRAGS; ++f) a_nxt[f] = *reinterpret_cast<const uint4*>(dyp + a_off[f] + koff(ks + 1));
+                for (int f = 0; f < FRAGS; ++f) a_nxt[f] = *reinterpret_cast<const u32x4*>(dyp + a_off[f] + koff(ks + 1));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
         {                                              // the mask: in flight while the accumulators go to the dX image
             const bf16_t* base = act_in + (size_t)s * (G::H * G::W * CIN);
 #pragma unroll
-            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const uint4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
+            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const u32x4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
         }
         // lanes m and m ^ 1 hold neighbouring channels of the same position: the even lane stores both as
         // one word for even q, the odd lane for odd q (half as many LDS stores, none narrower than a bank word)
@@ -191,12 +191,12 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
         bfr[i] = __builtin_bit_cast(bf16x8, kh ? w1 : w0);
     }
 
-    uint4 pdy[DY_IT], pact[DX_IT];
+    u32x4 pdy[DY_IT], pact[DX_IT];
 #define PAAC_PREFETCH_DY(S_)                                                                                             \
     {                                                                                                                    \
         const bf16_t* base_ = dy + (size_t)(S_) * (G::HO * G::WO * COUT);                                                \
         _Pragma("unroll") for (int i = 0; i < DY_IT; ++i)                                                                \
-            pdy[i] = *reinterpret_cast<const uint4*>(base_ + (size_t)min(tid + i * 256, DY_CH - 1) * 8);                 \
+            pdy[i] = *reinterpret_cast<const u32x4*>(base_ + (size_t)min(tid + i * 256, DY_CH - 1) * 8);                 \
     }
     int s = blockIdx.x;
     if (s >= ns) return;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
             const int ch = tid + i * 256;
             if (ch < DY_CH) {
                 const int pos = ch / (COUT / 8), c8 = ch % (COUT / 8);
-                *reinterpret_cast<uint4*>(dyp + ((pos / G::WO + PAD) * PADW + (pos % G::WO + PAD)) * PP + c8 * 8) = pdy[i];
+                *reinterpret_cast<u32x4*>(dyp + ((pos / G::WO + PAD) * PADW + (pos % G::WO + PAD)) * PP + c8 * 8) = pdy[i];
             }
         }
         __syncthreads();                               // also: the previous sample's dX image has been read
@@ -236,14 +236,14 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
             const int off1 = (ks1 % CS) * 16 - ((ks1 / CS / G::KS) * PADW + (ks1 / CS % G::KS)) * PP;
             return kh ? off1 : off0;
         };
-        uint4 a_cur[FRAGS], a_nxt[FRAGS];
+        u32x4 a_cur[FRAGS], a_nxt[FRAGS];
 #pragma unroll
-        for (int f = 0; f < FRAGS; ++f) a_cur[f] = *reinterpret_cast<const uint4*>(dyp + a_off[f] + koff(0));
+        for (int f = 0; f < FRAGS; ++f) a_cur[f] = *reinterpret_cast<const u32x4*>(dyp + a_off[f] + koff(0));
 #pragma unroll
         for (int i = 0; i < KH; ++i) {
             if (i + 1 < KH) {
 #pragma unroll
-                for (int f = 0; f < FRAGS; ++f) a_nxt[f] = *reinterpret_cast<const uint4*>(dyp + a_off[f] + koff(i + 1));
+                for (int f = 0; f < FRAGS; ++f) a_nxt[f] = *reinterpret_cast<const u32x4*>(dyp + a_off[f] + koff(i + 1));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
         {                                              // the mask: in flight during the reduction
             const bf16_t* base = act_in + (size_t)s * (ROWS * CIN);
 #pragma unroll
-            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const uint4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
+            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const u32x4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
         }
         if (kh == 1) {
 #pragma unroll

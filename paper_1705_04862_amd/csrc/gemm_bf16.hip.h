@@ -37,6 +37,9 @@ __device__ __forceinline__ unsigned mask2(unsigned v, unsigned a) {
     return v & (lo | hi);
 }
 
+// staging registers as a native vector type: an array of the uint4 struct that is only copied in and
+// out is lowered to memcpy through private memory (scratch) instead of registers
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
 __device__ __forceinline__ uint4 keep_if_u4(bool ok, uint4 v) {
     return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
@@ -485,32 +488,6 @@ __device__ __forceinline__ const char* at(const void* base, int byte_off) {
     return static_cast<const char*>(base) + (unsigned)byte_off;      // tensors are far below 4 GiB
 }
 
-// im2col rows of a bf16 NHWC activation, k = (ky, kx, c), c in groups of 8.
-template <class G> struct ConvNHWCRowsK8 {
-    static_assert(G::CIN % 8 == 0, "channels in groups of 8");
-    static_assert((G::KS * G::CIN) % 64 == 0 && G::KK % 64 == 0, "a 64-wide k tile stays inside one kernel row");
-    static constexpr bool kContig = true;      // lanes along k: eight lanes read 128 contiguous bytes
-    typedef uint4 Raw;
-    static __device__ __forceinline__ uint4 finish(Raw r, bool ok) { return keep_if_u4(ok, r); }
-    const bf16_t* x; int rows;
-    struct Fixed { int off; bool ok; };
-    __device__ __forceinline__ Fixed prep(int row, int) const {
-        Fixed f; f.ok = row < rows;
-        row = f.ok ? row : 0;
-        const int n = row / (G::HO * G::WO), r = row % (G::HO * G::WO), oy = r / G::WO, ox = r % G::WO;
-        f.off = (((n * G::H + oy * G::ST) * G::W + ox * G::ST) * G::CIN) * 2;
-        return f;
-    }
-    __device__ __forceinline__ Raw load(const Fixed& f, int k, bool pred, bool& ok) const {
-        ok = pred && f.ok;
-        // all lanes work on the same 64-wide k tile: its kernel row and offset are wave-uniform
-        int kb = __builtin_amdgcn_readfirstlane(k & ~63);
-        kb = kb < G::KK ? kb : 0;
-        const int ky = kb / (G::KS * G::CIN), rem = kb % (G::KS * G::CIN);
-        return *reinterpret_cast<const uint4*>(at(x, f.off + (ky * (G::W * G::CIN) + rem) * 2 + (k & 63) * 2));
-    }
-};
-
 struct DenseRowsK8 {            // element (row, k) = base[row*ld + k]
     static constexpr bool kContig = true;
     typedef uint4 Raw;
@@ -569,16 +546,6 @@ struct DenseKCols8 {            // element (k, col) = base[k*ld + col]
 };
 
 // ----------------------------------------------------------------------------------------------
-// Epilogues with bf16 outputs (EpiPartial of the fp32 core is reused for fp32 partial sums)
-struct EpiBiasReluB {           // out[row][col] = bf16(max(scale * v + bias[col], 0))
-    static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kMask = false, kBias = true;
-    bf16_t* out; const float* bias; int ldo; float scale;
-    __device__ __forceinline__ int row_entry(int row, int) const { return row * ldo; }
-    __device__ __forceinline__ bf16_t value(float v, float b) const { return f2bf(fmaxf(v * scale + b, 0.f)); }
-    __device__ __forceinline__ bf16_t* dst() const { return out; }
-    __device__ __forceinline__ const bf16_t* mask() const { return nullptr; }
-};
-
 struct EpiDenseMaskB {          // out[row][col] = v * 1[act[row][col] > 0]
     static constexpr bool kColSum = false, kEntry = true, kRowTable = false, kMask = true, kBias = false;
     bf16_t* out; const bf16_t* act; int ld; const float* bias;

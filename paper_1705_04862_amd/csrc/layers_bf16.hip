@@ -3,6 +3,7 @@
 #include "conv1_direct.hip.h"
 #include "conv1_wgrad_direct.hip.h"
 #include "conv_dgrad_direct.hip.h"
+#include "conv_fwd_direct.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -21,29 +22,16 @@ template <> struct TileBForN<16> { typedef B128x32 type; };
 template <> struct TileBForN<32> { typedef B128x32 type; };
 
 // ---------------------------------------------------------------------------------- forward
-template <class G, bool U8>
-static hipError_t conv_fwd_t(hipStream_t s, const void* in, const bf16_t* Wt, const float* b, bf16_t* out, int ns) {
-    typedef typename TileBForN<G::COUT>::type T;
-    const int M = ns * G::HO * G::WO;
-    DenseRowsK8 bl{Wt, G::COUT, G::KK};              // B(k, n = co) = Wt[co][k]
-    EpiBiasReluB ep{out, b, G::COUT, U8 ? 1.0f / 255.0f : 1.0f};     // bytes enter unscaled
-    if constexpr (U8) {
-        return launch_conv1_direct<G>(s, (const uint8_t*)in, Wt, b, out, ns);
-    } else {
-        ConvNHWCRowsK8<G> al{(const bf16_t*)in, M};
-        return launch_gemm_bf16<T>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
-    }
-}
-
+// first layer: bytes straight from the image; layers 2 and 3: one sample at a time from LDS
 hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* Wt, const float* b,
                          bf16_t* out, int ns) {
     if (arch == 0) {
-        if (layer == 0) return conv_fwd_t<NipsC1, true>(s, in, Wt, b, out, ns);
-        if (layer == 1) return conv_fwd_t<NipsC2, false>(s, in, Wt, b, out, ns);
+        if (layer == 0) return launch_conv1_direct<NipsC1>(s, (const uint8_t*)in, Wt, b, out, ns);
+        if (layer == 1) return launch_conv_fwd_direct<NipsC2>(s, (const bf16_t*)in, Wt, b, out, ns);
     } else {
-        if (layer == 0) return conv_fwd_t<NatC1, true>(s, in, Wt, b, out, ns);
-        if (layer == 1) return conv_fwd_t<NatC2, false>(s, in, Wt, b, out, ns);
-        if (layer == 2) return conv_fwd_t<NatC3, false>(s, in, Wt, b, out, ns);
+        if (layer == 0) return launch_conv1_direct<NatC1>(s, (const uint8_t*)in, Wt, b, out, ns);
+        if (layer == 1) return launch_conv_fwd_direct<NatC2>(s, (const bf16_t*)in, Wt, b, out, ns);
+        if (layer == 2) return launch_conv_fwd_direct<NatC3>(s, (const bf16_t*)in, Wt, b, out, ns);
     }
     return hipErrorInvalidValue;
 }
