@@ -150,12 +150,13 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
     if (bf16) {
         WeightCopies& w = b.copies;
         auto copy = [&](bf16_t*& dst, int src_off, int K, int C, int cin, int mode) {
-            dst = reinterpret_cast<bf16_t*>(take(((size_t)K * C + 1) / 2));
+            const int count = mode == 3 ? K * 32 : K * C;       // mode 3 pads the columns to 32
+            dst = reinterpret_cast<bf16_t*>(take(((size_t)count + 1) / 2));
             w.dst[w.n] = dst; w.start[w.n] = w.total; w.src_off[w.n] = src_off; w.K[w.n] = K; w.C[w.n] = C;
-            w.cin[w.n] = cin; w.mode[w.n] = mode; w.total += K * C; ++w.n;
+            w.cin[w.n] = cin; w.mode[w.n] = mode; w.total += count; ++w.n;
         };
         for (int l = 0; l < n.n_conv; ++l) {
-            copy(b.wt[l], a.conv_w[l], n.conv[l].kk, n.conv[l].cout, n.conv[l].cin, 0);
+            copy(b.wt[l], a.conv_w[l], n.conv[l].kk, n.conv[l].cout, n.conv[l].cin, l == 0 ? 3 : 0);
             if (l > 0) copy(b.wd[l], a.conv_w[l], n.conv[l].kk, n.conv[l].cout, n.conv[l].cin, 2);
         }
         copy(b.fc_t, a.fc_w, n.flat, n.fc, 1, 0);

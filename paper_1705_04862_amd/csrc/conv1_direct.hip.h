@@ -7,7 +7,7 @@
 // The MFMA A fragment of an output position (oy, ox) and k-group (c, ky) is then the 16 bytes at
 //   img[c][4*oy + ky][4*ox .. 4*ox + 7],
 // i.e. one base address per fragment plus compile-time offsets; the weights (COUT x 256) stay in
-// registers for the lifetime of the workgroup.  An image row is 84 elements = 42 words: the rows of
+// registers for the lifetime of the workgroup (read from a copy in fragment order).  An image row is 84 elements = 42 words: the rows of
 // consecutive output rows continue each other's bank sequence, no padding is needed.
 // NS = 1 (56 KB of LDS) lets two workgroups share a compute unit, so that one converts and waits
 // while the other multiplies; its 400 output rows are 12.5 fragments of 32 (the last is half empty).
@@ -35,14 +35,11 @@ __global__ __launch_bounds__(256, 2) void conv1_direct_kernel(const uint8_t* __r
     const int pairs = (ns + NS - 1) / NS;                   // groups of NS samples
     const long total_bytes = (long)ns * SAMPLE;
 
-    // weights of output channel fidx: sixteen k-steps of 16, this lane's eight k of each
+    // weights of output channel fidx: sixteen k-steps of 16, this lane's eight k of each; the copy is laid
+    // out [k/8][32 channels][8] (channels past COUT zero), so a wave reads one contiguous KB per k-step
     bf16x8 breg[16];
 #pragma unroll
-    for (int kt = 0; kt < 16; ++kt) {
-        uint4 w = zero_u4();
-        if (fidx < G::COUT) w = *reinterpret_cast<const uint4*>(Wt + fidx * 256 + kt * 16 + kg * 8);
-        breg[kt] = __builtin_bit_cast(bf16x8, w);
-    }
+    for (int kt = 0; kt < 16; ++kt) breg[kt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Wt + (kt * 64 + lane) * 8));
     const float bias_r = fidx < G::COUT ? bias[fidx] : 0.f;
 
     uint4 pre[IT];

@@ -139,6 +139,8 @@ hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t*
 //   mode 0: dst[c*K + k]              = src[k*C + c]           (forward: [c_out][K])
 //   mode 1: dst[i]                    = src[i]                 (fc data gradient: [flat][fc])
 //   mode 2: dst[(ci*T + t)*C + co]    = src[(t*CIN + ci)*C + co]   (conv data gradient: [ci][ky,kx][co])
+//   mode 3: dst[(k/8)*256 + c*8 + k%8] = src[k*C + c], zero for c in [C, 32)   (first layer forward: the
+//           order in which the lanes read their MFMA B fragments, one contiguous KB per wave and load)
 __global__ __launch_bounds__(256) void make_bf16_weights_kernel(const WeightCopies w, const float* theta) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= w.total) return;
@@ -150,7 +152,11 @@ __global__ __launch_bounds__(256) void make_bf16_weights_kernel(const WeightCopi
     int si;
     if (w.mode[sidx] == 0) { const int c = o / K, k = o % K; si = k * C + c; }
     else if (w.mode[sidx] == 1) si = o;
-    else {
+    else if (w.mode[sidx] == 3) {
+        const int c = (o % 256) / 8, k = (o / 256) * 8 + o % 8;
+        if (c >= C) { w.dst[sidx][o] = 0; return; }
+        si = k * C + c;
+    } else {
         const int T = K / w.cin[sidx];                      // taps
         const int co = o % C, t = (o / C) % T, ci = o / (C * T);
         si = (t * w.cin[sidx] + ci) * C + co;
