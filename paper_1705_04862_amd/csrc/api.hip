@@ -111,7 +111,7 @@ struct Buffers {
     void* dh;               // gradient w.r.t. the fc output (same element type as act)
     void* dact[3];          // gradient w.r.t. conv outputs, B rows
     bf16_t *wt[3], *wd[3], *fc_t, *fc_c;   // bf16 weight copies (bf16 configuration only)
-    bf16_t* w1_parts;       // fp32 configuration: first-layer weights as three bf16 parts (3 x 8192)
+    WeightSplits splits;    // fp32 configuration: conv weights as three bf16 parts each
     WeightCopies copies;
     float *pw[3], *pb[3], *fc_pw, *fc_pb, *hd_pw, *hd_pb;
     size_t bytes;
@@ -146,7 +146,14 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
     b.fc_pw = p.fc_wg.n > 1 ? take((size_t)p.fc_wg.n * n.flat * n.fc) : nullptr; b.fc_pb = take((size_t)p.fc_wg.n * n.fc);
     b.hd_pw = take((size_t)p.head_chunks * (n.n_actions + 1) * n.fc);
     b.hd_pb = take((size_t)p.head_chunks * (n.n_actions + 1));
-    if (!bf16) b.w1_parts = reinterpret_cast<bf16_t*>(take(3 * 32 * 256 / 2));
+    if (!bf16) {
+        WeightSplits& w = b.splits;
+        w.n = n.n_conv;
+        for (int l = 0; l < n.n_conv; ++l) {
+            w.off[l] = a.conv_w[l]; w.K[l] = n.conv[l].kk; w.C[l] = n.conv[l].cout;
+            w.dst[l] = reinterpret_cast<bf16_t*>(take(((size_t)3 * w.plane(l) + 1) / 2));
+        }
+    }
     if (bf16) {
         WeightCopies& w = b.copies;
         auto copy = [&](bf16_t*& dst, int src_off, int K, int C, int cin, int mode) {
@@ -282,6 +289,10 @@ struct Launcher {
 struct SelectArgs { const uint8_t* states; const float* uniforms; int32_t* actions; float* values; float* probs; };
 struct TrainArgs { const uint8_t* states; const int32_t* actions; const float* rewards; const uint8_t* dones; paac_train_stats* stats; };
 
+// fp32 configuration, layers 1..: from this many samples on a launch takes the kernel that works one
+// sample per workgroup on exact bf16 parts; below, the tiled fp32 GEMM fills the chip better.
+constexpr int kExactMinSamples = 96;
+
 // Forward trunk shared by select and train: convs, fc partial sums.
 // `row0`: first row of the activation buffers this launch writes (0, or the slab of a cached rollout).
 void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0, int row0) {
@@ -296,7 +307,9 @@ void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Spli
         void* out = act_at(l);
         if (bf16) L.run(id0 + l, [&] { return conv_fwd_bf16(L.s, n.arch, l, in, b.wt[l], b.theta + a.conv_b[l], (bf16_t*)out, ns); });
         else if (l == 0)
-            L.run(id0, [&] { return conv1_fwd_exact(L.s, n.arch, states, b.w1_parts, b.theta + a.conv_b[0], (float*)out, ns); });
+            L.run(id0, [&] { return conv1_fwd_exact(L.s, n.arch, states, b.splits.dst[0], b.theta + a.conv_b[0], (float*)out, ns); });
+        else if (ns >= kExactMinSamples)
+            L.run(id0 + l, [&] { return conv_fwd_exact(L.s, n.arch, l, (const float*)in, b.splits.dst[l], b.theta + a.conv_b[l], (float*)out, ns); });
         else L.run(id0 + l, [&] { return conv_fwd(L.s, n.arch, l, in, b.theta + a.conv_w[l], b.theta + a.conv_b[l], (float*)out, ns); });
         in = out;
     }
@@ -410,7 +423,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     L.run(K_TRN_GRAD_REDUCE, [&] { return grad_reduce_norm(L.s, g, b.grads, b.block_ss); });
     L.run(K_TRN_RMSPROP, [&] {
         return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, n_ss, b.hp, b.loss_partials, p.n_loss_blocks,
-                              b.stats, reinterpret_cast<StatsOut*>(x.stats), bf16 ? nullptr : b.w1_parts, a.conv_w[0], n.conv[0].cout);
+                              b.stats, reinterpret_cast<StatsOut*>(x.stats), b.splits);
     });
     if (bf16) L.run(K_TRN_BF16W, [&] { return make_bf16_weights(L.s, b.copies, b.theta); });
     *err_id = L.err_id;
@@ -551,7 +564,7 @@ int paac_set_state(paac_ctx* c, const float* params_host, const float* rms_host)
     HIP_TRY(c, hipMemcpy(c->buf.g2, g2.data(), a.p_int * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemset(c->buf.grads, 0, a.p_int * sizeof(float)));
     if (c->cfg.precision == PAAC_PREC_BF16) HIP_TRY(c, make_bf16_weights(c->stream, c->buf.copies, c->buf.theta));
-    else HIP_TRY(c, split_conv1_weights(c->stream, c->buf.theta + a.conv_w[0], c->net.conv[0].cout, c->buf.w1_parts));
+    else HIP_TRY(c, split_weights(c->stream, c->buf.splits, c->buf.theta));
     HIP_TRY(c, hipDeviceSynchronize());
     c->have_params = true;
     c->sel_count = 0;          // activations cached under the old parameters are stale

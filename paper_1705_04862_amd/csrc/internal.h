@@ -17,6 +17,12 @@ inline void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t s, Args... arg
     if (tl_prof.start) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, tl_prof.start, tl_prof.stop, 0, args...);
     else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
 }
+// the same with `lds_bytes` of dynamic LDS
+template <class K, class... Args>
+inline void launch_k_lds(K kernel, dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t s, Args... args) {
+    if (tl_prof.start) hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, s, tl_prof.start, tl_prof.stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, args...);
+}
 
 // Static description of one of the two networks (Experiments: arch_nips, arch_nature).
 struct ConvDesc { int cin, h, w, ks, st, cout, ho, wo, kk; };
@@ -81,8 +87,20 @@ struct WeightCopies {            // see make_bf16_weights_kernel for the modes
     int n, total;
     bf16_t* dst[kMaxCopies]; int start[kMaxCopies], src_off[kMaxCopies], K[kMaxCopies], C[kMaxCopies], cin[kMaxCopies], mode[kMaxCopies];
 };
+// fp32 configuration: convolution weights W[K][C] also kept as three bf16 parts whose sum they are, in
+// the order in which the lanes of the exact-operand kernels read their MFMA B fragments:
+//   dst[part][C/32 rounded up][K/16][64 lanes = (k%16)/8 * 32 + c%32][8 = k%8]   (columns past C are zero)
+struct WeightSplits {
+    int n;
+    int off[3], K[3], C[3];      // arena offset (floats, multiple of 4), rows (multiple of 16), columns
+    bf16_t* dst[3];
+    __host__ __device__ int plane(int l) const { return (C[l] + 31) / 32 * 32 * K[l]; }
+};
+hipError_t split_weights(hipStream_t s, const WeightSplits& ws, const float* theta);
 // first convolution of the fp32 path from the three bf16 parts of its weights, fp32 NHWC output
 hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* w_parts, const float* b, float* out, int ns);
+// layers 1.. of the fp32 path, one sample per workgroup, from the parts of weights and activations
+hipError_t conv_fwd_exact(hipStream_t s, int arch, int layer, const float* in, const bf16_t* w_parts, const float* b, float* out, int ns);
 // first convolution's weight gradient from the image; dy fp32 (exact) or bf16; writes n_wgs partials [256][cout] / [cout]
 hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs);
 hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);
@@ -152,9 +170,7 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, float* grads
 struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
                           const float* block_ss, int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
-                          StatsOut* stats_a, StatsOut* stats_b, bf16_t* w1_parts, int w1_off, int w1_cout);
-// first-layer weights W[k][cout] (fp32) as three bf16 parts [3][32 k-groups][32 c_out][8] whose sum is the weight
-hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t* parts);
+                          StatsOut* stats_a, StatsOut* stats_b, const WeightSplits& ws);
 hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n);
 
 hipError_t delay_us(hipStream_t s, unsigned us);

@@ -4,6 +4,7 @@
 #include "conv1_wgrad_direct.hip.h"
 #include "conv_dgrad_direct.hip.h"
 #include "conv_fwd_direct.hip.h"
+#include "conv_fwd_exact.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -40,6 +41,14 @@ hipError_t conv_fwd_bf16(hipStream_t s, int arch, int layer, const void* in, con
 hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* Wk, const float* b, float* out, int ns) {
     if (arch == 0) return launch_conv1_exact<NipsC1>(s, x, Wk, b, out, ns);
     return launch_conv1_exact<NatC1>(s, x, Wk, b, out, ns);
+}
+
+// Layers 1.. of the fp32 path on exact bf16 parts, one sample per workgroup (see conv_fwd_exact_kernel).
+hipError_t conv_fwd_exact(hipStream_t s, int arch, int layer, const float* in, const bf16_t* Wp, const float* b, float* out, int ns) {
+    if (arch == 0 && layer == 1) return launch_conv_fwd_exact<NipsC2>(s, in, Wp, b, out, ns);
+    if (arch == 1 && layer == 1) return launch_conv_fwd_exact<NatC2>(s, in, Wp, b, out, ns);
+    if (arch == 1 && layer == 2) return launch_conv_fwd_exact<NatC3>(s, in, Wp, b, out, ns);
+    return hipErrorInvalidValue;
 }
 
 // First convolution's weight gradient straight from the image (see conv1_wgrad_direct_kernel): dy is

@@ -507,40 +507,65 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, float* grads
 }
 
 // An fp32 number as three bf16 numbers whose sum it is: its 24 significand bits cut into 8 + 8 + 8
-// by truncation (both residuals are exact).  parts: [3][32 k-groups of 8][32 c_out][8] bf16, the
-// order in which the lanes of the first-layer kernel read their MFMA B fragments (16 bytes each).
-__device__ __forceinline__ void store_split3(float w, int co, int k, bf16_t* parts) {
+// by truncation (both residuals are exact).  Element (k, c) of weight matrix l goes to its place in
+// the fragment order described at WeightSplits.
+__device__ __forceinline__ void store_split3(float w, int c, int k, bf16_t* parts, int K, int plane) {
     const uint32_t hb = __float_as_uint(w) & 0xffff0000u;
     const float r1 = w - __uint_as_float(hb);
     const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
     const float r2 = r1 - __uint_as_float(mb);
-    const int at = (k >> 3) * 256 + co * 8 + (k & 7);
+    const int at = (((c >> 5) * (K >> 4) + (k >> 4)) * 64 + ((k >> 3) & 1) * 32 + (c & 31)) * 8 + (k & 7);
     parts[at] = (bf16_t)(hb >> 16);
-    parts[8192 + at] = (bf16_t)(mb >> 16);
-    parts[2 * 8192 + at] = (bf16_t)(__float_as_uint(r2) >> 16);
+    parts[plane + at] = (bf16_t)(mb >> 16);
+    parts[2 * plane + at] = (bf16_t)(__float_as_uint(r2) >> 16);
 }
 
-// First-layer weights W[k][cout] (fp32) -> their three bf16 parts; rows cout..31 are zero.
-__global__ __launch_bounds__(256) void split_conv1_weights_kernel(const float* Wk, int cout, bf16_t* parts) {
-    const int co = blockIdx.x, k = threadIdx.x;
-    store_split3(co < cout ? Wk[k * cout + co] : 0.f, co, k, parts);
+// the same for two numbers, parts packed (a in the low half)
+__device__ __forceinline__ void split3_pack(float a, float b, unsigned& hi, unsigned& mid, unsigned& lo) {
+    const uint32_t ah = __float_as_uint(a) & 0xffff0000u, bh = __float_as_uint(b) & 0xffff0000u;
+    const float a1 = a - __uint_as_float(ah), b1 = b - __uint_as_float(bh);
+    const uint32_t am = __float_as_uint(a1) & 0xffff0000u, bm = __float_as_uint(b1) & 0xffff0000u;
+    const float a2 = a1 - __uint_as_float(am), b2 = b1 - __uint_as_float(bm);
+    hi = (ah >> 16) | bh;
+    mid = (am >> 16) | bm;
+    lo = (__float_as_uint(a2) >> 16) | (__float_as_uint(b2) & 0xffff0000u);
 }
-hipError_t split_conv1_weights(hipStream_t s, const float* Wk, int cout, bf16_t* parts) {
-    if (cout < 1 || cout > 32) return hipErrorInvalidValue;
-    launch_k(split_conv1_weights_kernel, dim3(32), dim3(256), s, Wk, cout, parts);
+
+// Every weight matrix of ws from the fp32 arena; one thread per element of the padded matrices
+// (columns C .. next multiple of 32 are written as zeros).
+__global__ __launch_bounds__(256) void split_weights_kernel(const WeightSplits ws, const float* theta) {
+    int i = blockIdx.x * 256 + threadIdx.x;
+    for (int l = 0; l < ws.n; ++l) {
+        const int plane = ws.plane(l);
+        if (i < plane) {
+            const int cp = plane / ws.K[l], k = i / cp, c = i % cp;
+            store_split3(c < ws.C[l] ? theta[ws.off[l] + k * ws.C[l] + c] : 0.f, c, k, ws.dst[l], ws.K[l], plane);
+            return;
+        }
+        i -= plane;
+    }
+}
+hipError_t split_weights(hipStream_t s, const WeightSplits& ws, const float* theta) {
+    int total = 0;
+    for (int l = 0; l < ws.n; ++l) {
+        if (ws.K[l] % 16 != 0 || ws.off[l] % 4 != 0 || (ws.K[l] * ws.C[l]) % 4 != 0 || !ws.dst[l]) return hipErrorInvalidValue;
+        total += ws.plane(l);
+    }
+    if (total == 0) return hipSuccess;
+    launch_k(split_weights_kernel, dim3((total + 255) / 256), dim3(256), s, ws, theta);
     return hipGetLastError();
 }
 
 // Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
 //   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
 // Every block re-derives the norm from the per-block partial sums (same order everywhere).
-// w1_parts (may be null): the updated first-layer weights, arena floats [w1_off, w1_off + 256 w1_cout),
-// are also written as their three bf16 parts for the next forward pass.
+// The updated weights of the matrices listed in ws (fp32 configuration; ws.n = 0 otherwise) are also
+// written as their three bf16 parts for the next forward pass.
 __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
                                                              const float* block_ss, int n_ss, const float* hp,
                                                              const float* loss_partials, int n_loss_blocks,
                                                              StatsOut* stats_a, StatsOut* stats_b,
-                                                             bf16_t* w1_parts, int w1_off, int w1_cout) {
+                                                             const WeightSplits ws, int ws_blocks) {
     __shared__ float red[256];
     float part = 0.f;
     for (int q = threadIdx.x; q < n_ss; q += 256) part += block_ss[q];
@@ -549,22 +574,59 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
     const float clip = hp[HP_CLIP], lr = hp[HP_LR], alpha = hp[HP_ALPHA], eps = hp[HP_EPS];
     const float scale = norm > clip ? clip / norm : 1.0f;
     const float oma = 1.0f - alpha;
+    // The matrices of ws are updated by the first ws_blocks workgroups, one thread per (eight
+    // consecutive k, column): lanes along the columns read and write whole rows, and a thread holds
+    // exactly the eight values of one 16-byte fragment slot of each part.
+    if ((int)blockIdx.x < ws_blocks) {
+        int u = blockIdx.x * 256 + threadIdx.x;
+        for (int l = 0; l < ws.n; ++l) {
+            const int C = ws.C[l], K = ws.K[l], units = (K >> 3) * C;
+            if (u < units) {
+                const int k8 = u / C, c = u % C;
+                float* th = reinterpret_cast<float*>(theta); float* v2 = reinterpret_cast<float*>(g2);
+                const float* gr = reinterpret_cast<const float*>(grads);
+                float gv[8], vv[8], tv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int at = ws.off[l] + (k8 * 8 + j) * C + c;
+                    gv[j] = gr[at]; vv[j] = v2[at]; tv[j] = th[at];
+                }
+                unsigned hi[4], mid[4], lo[4];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int at = ws.off[l] + (k8 * 8 + j) * C + c;
+                    const float g = gv[j] * scale;
+                    vv[j] = alpha * vv[j] + oma * g * g;
+                    tv[j] -= lr * g / sqrtf(vv[j] + eps);
+                    v2[at] = vv[j]; th[at] = tv[j];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) split3_pack(tv[2 * j], tv[2 * j + 1], hi[j], mid[j], lo[j]);
+                const int plane = ws.plane(l);
+                bf16_t* d = ws.dst[l] + (size_t)((((c >> 5) * (K >> 4) + (k8 >> 1)) * 64 + (k8 & 1) * 32 + (c & 31)) * 8);
+                *reinterpret_cast<uint4*>(d) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                *reinterpret_cast<uint4*>(d + plane) = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+                *reinterpret_cast<uint4*>(d + 2 * plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                break;
+            }
+            u -= units;
+        }
+        return;
+    }
     auto update = [&](int i, float4 g, float4 v, float4 t) __attribute__((always_inline)) {
+        for (int l = 0; l < ws.n; ++l) {                           // offsets and sizes are multiples of 4
+            const int e0 = i * 4 - ws.off[l];
+            if (e0 >= 0 && e0 < ws.K[l] * ws.C[l]) return;         // updated above
+        }
         g.x *= scale; g.y *= scale; g.z *= scale; g.w *= scale;
         v.x = alpha * v.x + oma * g.x * g.x; v.y = alpha * v.y + oma * g.y * g.y;
         v.z = alpha * v.z + oma * g.z * g.z; v.w = alpha * v.w + oma * g.w * g.w;
         t.x -= lr * g.x / sqrtf(v.x + eps); t.y -= lr * g.y / sqrtf(v.y + eps);
         t.z -= lr * g.z / sqrtf(v.z + eps); t.w -= lr * g.w / sqrtf(v.w + eps);
         g2[i] = v; theta[i] = t;
-        const int e0 = i * 4 - w1_off;
-        if (w1_parts && e0 >= 0 && e0 < 256 * w1_cout) {           // w1_off and 256 w1_cout are multiples of 4
-            const float tv[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) store_split3(tv[e], (e0 + e) % w1_cout, (e0 + e) / w1_cout, w1_parts);
-        }
     };
-    const int stride = gridDim.x * 256;
-    int i = blockIdx.x * 256 + threadIdx.x;
+    const int stride = (gridDim.x - ws_blocks) * 256;
+    int i = (blockIdx.x - ws_blocks) * 256 + threadIdx.x;
     for (; i + stride < n4; i += 2 * stride) {                    // two elements' loads in flight
         const float4 ga = grads[i], va = g2[i], ta = theta[i];
         const float4 gb = grads[i + stride], vb = g2[i + stride], tb = theta[i + stride];
@@ -572,7 +634,7 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
         update(i + stride, gb, vb, tb);
     }
     if (i < n4) update(i, grads[i], g2[i], theta[i]);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if ((int)blockIdx.x == ws_blocks && threadIdx.x == 0) {
         float pl = 0.f, en = 0.f, vl = 0.f;
         for (int b = 0; b < n_loss_blocks; ++b) { pl += loss_partials[b * 4]; en += loss_partials[b * 4 + 1]; vl += loss_partials[b * 4 + 2]; }
         StatsOut st;
@@ -588,13 +650,16 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
 
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads, const float* block_ss,
                           int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b,
-                          bf16_t* w1_parts, int w1_off, int w1_cout) {
+                          const WeightSplits& ws) {
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 512) blocks = 512;       // grid-stride loop: fewer, longer-lived workgroups
-    launch_k(rmsprop_update_kernel, dim3(blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
+    int units = 0;
+    for (int l = 0; l < ws.n; ++l) units += (ws.K[l] / 8) * ws.C[l];
+    const int ws_blocks = (units + 255) / 256;
+    launch_k(rmsprop_update_kernel, dim3(ws_blocks + blocks), dim3(256), s, n4, (float4*)theta, (float4*)g2,
                        (const float4*)grads, block_ss, n_ss, hp, loss_partials, n_loss_blocks, stats_a, stats_b,
-                       w1_parts, w1_off, w1_cout);
+                       ws, ws_blocks);
     return hipGetLastError();
 }
 
