@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256, 1) void conv_fwd_exact_kernel(const float* __r
     int s = blockIdx.x;
     if (s >= ns) return;
     prefetch_in(s);
+    __builtin_amdgcn_sched_barrier(0);                 // keep the sample's loads ahead of the weights'
     // requested after the first sample and in the order of use: the weights arrive while the sample is
     // split and written to LDS, and the first k-steps need not wait for the last weights
     bf16x8 bw[3][KPW];
