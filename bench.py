@@ -41,6 +41,8 @@ def kernel_work(net, n_e, t_max):
         w[f"train.conv{l + 1}_wgrad"] = ("flop", f * B)
         if l > 0:
             w[f"train.conv{l + 1}_dgrad"] = ("flop", f * B)
+    w["select.convs_fwd"] = ("flop", sum(conv) * n_e)    # all convolutions of a sample in one workgroup
+    w["train.convs_fwd"] = ("flop", sum(conv) * Bp)
     w["select.fc_fwd"] = ("flop", fc * n_e)
     w["train.fc_fwd"] = ("flop", fc * Bp)
     w["train.fc_wgrad"] = ("flop", fc * B)

@@ -177,14 +177,16 @@ enum KernelId {
     K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
     K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_BWD,
     K_TRN_FC_WG, K_TRN_FC_DG, K_TRN_CONV3_WG, K_TRN_CONV3_DG, K_TRN_CONV2_WG, K_TRN_CONV2_DG, K_TRN_CONV1_WG,
-    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_TRN_FC_BWD, K_TRN_CONV3_BWD, K_TRN_CONV2_BWD, K_COUNT
+    K_TRN_GRAD_REDUCE, K_TRN_RMSPROP, K_TRN_BF16W, K_TRN_FC_BWD, K_TRN_CONV3_BWD, K_TRN_CONV2_BWD,
+    K_SEL_TRUNK, K_TRN_TRUNK, K_COUNT
 };
 const char* const kKernelNames[K_COUNT] = {
     "select.conv1_fwd", "select.conv2_fwd", "select.conv3_fwd", "select.fc_fwd", "select.heads_sample",
     "train.conv1_fwd", "train.conv2_fwd", "train.conv3_fwd", "train.fc_fwd", "train.heads_fwd", "train.returns_loss",
     "train.heads_bwd", "train.fc_wgrad", "train.fc_dgrad", "train.conv3_wgrad",
     "train.conv3_dgrad", "train.conv2_wgrad", "train.conv2_dgrad", "train.conv1_wgrad", "train.grad_reduce_norm",
-    "train.clip_rmsprop", "train.bf16_weight_copies", "train.fc_bwd", "train.conv3_bwd", "train.conv2_bwd"};
+    "train.clip_rmsprop", "train.bf16_weight_copies", "train.fc_bwd", "train.conv3_bwd", "train.conv2_bwd",
+    "select.convs_fwd", "train.convs_fwd"};
 
 struct GraphKey {
     int kind;                 // 0 select, 1 train
@@ -303,6 +305,13 @@ void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Spli
         const size_t per = (size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout * (bf16 ? 2 : 4);
         return static_cast<char*>(b.act[l]) + (size_t)row0 * per;
     };
+    if (!bf16 && ns >= kExactMinSamples && ns <= trunk_fwd_exact_max()) {
+        // one workgroup per sample runs all convolutions (exact bf16 parts)
+        const bf16_t* w[3] = {}; const float* bs[3] = {}; float* outs[3] = {};
+        for (int l = 0; l < n.n_conv; ++l) { w[l] = b.splits.dst[l]; bs[l] = b.theta + a.conv_b[l]; outs[l] = (float*)act_at(l); }
+        L.run(id0 == K_SEL_CONV1 ? K_SEL_TRUNK : K_TRN_TRUNK, [&] { return trunk_fwd_exact(L.s, n.arch, states, w, bs, outs, ns); });
+        in = outs[n.n_conv - 1];
+    } else
     for (int l = 0; l < n.n_conv; ++l) {
         void* out = act_at(l);
         if (bf16) L.run(id0 + l, [&] { return conv_fwd_bf16(L.s, n.arch, l, in, b.wt[l], b.theta + a.conv_b[l], (bf16_t*)out, ns); });

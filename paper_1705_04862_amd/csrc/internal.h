@@ -101,6 +101,9 @@ hipError_t split_weights(hipStream_t s, const WeightSplits& ws, const float* the
 hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* w_parts, const float* b, float* out, int ns);
 // layers 1.. of the fp32 path, one sample per workgroup, from the parts of weights and activations
 hipError_t conv_fwd_exact(hipStream_t s, int arch, int layer, const float* in, const bf16_t* w_parts, const float* b, float* out, int ns);
+// all convolutions of the fp32 path in one launch, one workgroup per sample; ns <= trunk_fwd_exact_max()
+int trunk_fwd_exact_max();
+hipError_t trunk_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* const* w_parts, const float* const* b, float* const* out, int ns);
 // first convolution's weight gradient from the image; dy fp32 (exact) or bf16; writes n_wgs partials [256][cout] / [cout]
 hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs);
 hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);

@@ -51,6 +51,14 @@ hipError_t conv_fwd_exact(hipStream_t s, int arch, int layer, const float* in, c
     return hipErrorInvalidValue;
 }
 
+// All convolutions of the fp32 path in one launch, one workgroup per sample (see trunk_fwd_exact_kernel);
+// w[l], b[l], out[l]: weight parts, bias and fp32 NHWC output of layer l.  ns <= trunk_fwd_exact_max().
+int trunk_fwd_exact_max() { return device_cus(); }
+hipError_t trunk_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* const* w, const float* const* b, float* const* out, int ns) {
+    if (arch == 0) return launch_trunk_fwd_exact<NipsC1, NipsC2, NoLayer>(s, x, w[0], b[0], out[0], w[1], b[1], out[1], nullptr, nullptr, nullptr, ns);
+    return launch_trunk_fwd_exact<NatC1, NatC2, NatC3>(s, x, w[0], b[0], out[0], w[1], b[1], out[1], w[2], b[2], out[2], ns);
+}
+
 // First convolution's weight gradient straight from the image (see conv1_wgrad_direct_kernel): dy is
 // fp32 when exact (fp32 path) and bf16 otherwise; n_wgs partials are written.
 hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs) {
