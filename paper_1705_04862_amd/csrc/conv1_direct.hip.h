@@ -221,6 +221,114 @@ __global__ __launch_bounds__(256, 1) void conv1_exact_kernel(const uint8_t* __re
     }
 }
 
+// The same for small batches (a quarter of a sample per workgroup, one item each): a wave that takes
+// whole fragments needs all 48 KB of weight parts for 48 MFMAs, and loading them is what the kernel
+// then waits for.  Here wave c takes input channel c (a quarter of the k-steps, 12 KB of weights) for
+// all four fragments of the band; the four partial sums of a fragment meet in LDS, wave f finishing
+// fragment f (own share first, then the others by wave: a fixed order).
+template <class G>
+__global__ __launch_bounds__(256, 1) void conv1_exact_ksplit_kernel(const uint8_t* __restrict__ x, const bf16_t* __restrict__ Wp,
+                                                                    const float* __restrict__ bias, float* __restrict__ out, int ns,
+                                                                    float scale) {
+    static_assert(G::CIN == 4 && G::H == 84 && G::W == 84 && G::KS == 8 && G::ST == 4 && G::COUT <= 32, "first layer");
+    constexpr int PARTS = 4;
+    static_assert(G::HO % PARTS == 0, "bands of whole output rows");
+    constexpr int SAMPLE = G::CIN * G::H * G::W, PLANE = G::H * G::W;
+    constexpr int BR = G::HO / PARTS, IR = 4 * BR + 4;
+    constexpr int CPC = IR * G::W / 16, CHUNKS = 4 * CPC, IT = (CHUNKS + 255) / 256;
+    constexpr int ROWS = BR * G::WO, FRAGS = (ROWS + 31) / 32;
+    static_assert(FRAGS == 4, "one fragment per wave to finish");
+    static_assert((IR * G::W) % 16 == 0 && (G::ST * G::W * BR) % 16 == 0 && PLANE % 16 == 0, "whole 16-byte chunks");
+    __shared__ __attribute__((aligned(16))) bf16_t img[4 * IR * G::W];
+    __shared__ float red[FRAGS * 3 * 16 * 64];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fidx = lane & 31, kg = lane >> 5;
+    const int p = blockIdx.x;
+    if (p >= ns * PARTS) return;
+    const float bias_r = fidx < G::COUT ? bias[fidx] : 0.f;
+
+    // the band's image (threads past the last chunk repeat it: no load is used under a condition only)
+    const size_t base = (size_t)(p / PARTS) * SAMPLE + (size_t)(p % PARTS) * (BR * G::ST * G::W);
+    uint4 pre[IT];
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        const int cc = min(tid + i * 256, CHUNKS - 1);
+        pre[i] = *reinterpret_cast<const uint4*>(x + base + (size_t)(cc / CPC) * PLANE + (size_t)(cc % CPC) * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 w[3][4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+            w[q][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Wp + q * 8192 + ((wave * 4 + ks) * 64 + lane) * 8));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        uint4* dst = reinterpret_cast<uint4*>(img + min(tid + i * 256, CHUNKS - 1) * 16);
+        dst[0] = u8x8_to_bf16(make_uint2(pre[i].x, pre[i].y));
+        dst[1] = u8x8_to_bf16(make_uint2(pre[i].z, pre[i].w));
+    }
+    __syncthreads();
+
+    const bf16_t* a0[FRAGS];
+    f32x16 acc[FRAGS];
+#pragma unroll
+    for (int f = 0; f < FRAGS; ++f) {
+        const int r = min(f * 32 + fidx, ROWS - 1);               // rows past the band: a valid address, never stored
+        a0[f] = img + wave * (IR * G::W) + ((r / G::WO) * G::ST + kg) * G::W + (r % G::WO) * G::ST;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 a[FRAGS];
+#pragma unroll
+        for (int f = 0; f < FRAGS; ++f) {
+            const uint2* ap = reinterpret_cast<const uint2*>(a0[f] + ks * 2 * G::W);   // 8-byte aligned
+            const uint2 lo = ap[0], hi = ap[1];
+            a[f] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+        }
+#pragma unroll
+        for (int q = 2; q >= 0; --q)
+#pragma unroll
+            for (int f = 0; f < FRAGS; ++f) acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], w[q][ks], acc[f], 0, 0, 0);
+    }
+    // one copy of the exchange per wave keeps every accumulator index a constant
+    auto per_wave = [&](auto&& fn) __attribute__((always_inline)) {
+        if (wave == 0) fn(std::integral_constant<int, 0>());
+        if (wave == 1) fn(std::integral_constant<int, 1>());
+        if (wave == 2) fn(std::integral_constant<int, 2>());
+        if (wave == 3) fn(std::integral_constant<int, 3>());
+    };
+    auto slot = [&](int dst, int src, int q) { return ((dst * 3 + (src < dst ? src : src - 1)) * 16 + q) * 64 + lane; };
+    per_wave([&](auto WV) __attribute__((always_inline)) {
+        constexpr int wv = decltype(WV)::value;
+#pragma unroll
+        for (int f = 0; f < FRAGS; ++f)
+            if (f != wv) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) red[slot(f, wv, q)] = acc[f][q];
+            }
+    });
+    __syncthreads();
+    const size_t orow0 = (size_t)(p / PARTS) * (G::HO * G::WO) + (size_t)(p % PARTS) * ROWS;
+    per_wave([&](auto WV) __attribute__((always_inline)) {
+        constexpr int wv = decltype(WV)::value;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            float v = acc[wv][q];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                if (g != wv) v += red[slot(wv, g, q)];
+            const int lr = wv * 32 + Mma<32>::row(q, lane);
+            if (fidx < G::COUT && lr < ROWS) out[(orow0 + lr) * G::COUT + fidx] = fmaxf(v * scale + bias_r, 0.f);
+        }
+    });
+}
+
 template <class G, int PARTS>
 inline void launch_conv1_exact_p(hipStream_t s, int cus, const uint8_t* x, const bf16_t* Wk, const float* bias, float* out, int ns) {
     launch_k((conv1_exact_kernel<G, PARTS>), dim3(std::min(ns * PARTS, 2 * cus)), dim3(256), s, x, Wk, bias, out, ns, 1.0f / 255.0f);
@@ -237,7 +345,7 @@ inline hipError_t launch_conv1_exact(hipStream_t s, const uint8_t* x, const bf16
     // one workgroup per compute unit (its registers allow no more): split samples into bands while
     // that still gives every workgroup a compute unit of its own
     const int parts = ns * 4 <= cus ? 4 : (ns * 2 <= cus ? 2 : 1);
-    if (parts == 4) launch_conv1_exact_p<G, 4>(s, cus, x, Wk, bias, out, ns);
+    if (parts == 4) launch_k((conv1_exact_ksplit_kernel<G>), dim3(ns * 4), dim3(256), s, x, Wk, bias, out, ns, 1.0f / 255.0f);
     else if (parts == 2) launch_conv1_exact_p<G, 2>(s, cus, x, Wk, bias, out, ns);
     else launch_conv1_exact_p<G, 1>(s, cus, x, Wk, bias, out, ns);
     return hipGetLastError();
