@@ -131,8 +131,10 @@ def test_select_actions_configs(paac, oracle, ci):
         check_select(oracle, cfg.net, params, ro.states[t], ro.uniforms[t], got)
 
 
-@pytest.mark.parametrize("net,n_e", [(I.nips_net(2), 1), (I.nature_net(32), 5), (I.nips_net(7), 67), (I.nature_net(4), 33)],
-                         ids=["nips_A2_ne1", "nature_A32_ne5", "nips_A7_ne67", "nature_A4_ne33"])
+@pytest.mark.parametrize("net,n_e", [(I.nips_net(2), 1), (I.nature_net(32), 5), (I.nips_net(7), 67), (I.nature_net(4), 33),
+                                     (I.nature_net(6), 100), (I.nature_net(6), 270)],
+                         ids=["nips_A2_ne1", "nature_A32_ne5", "nips_A7_ne67", "nature_A4_ne33",
+                              "nature_A6_ne100_one_workgroup_per_sample", "nature_A6_ne270_per_layer_exact"])
 def test_select_ragged_shapes(paac, oracle, net, n_e):
     ctx = make_ctx(paac, net, n_e, 1)
     params = I.make_params(8, net, bias_range=0.1)
@@ -181,6 +183,17 @@ def test_train_ragged_and_degenerate(paac, oracle, net, n_e, t_max, p_done):
     # clip inactive and active
     check_train(oracle, net, ctx, params, rms, ro, I.HParams(clip_norm=1e6), "noclip")
     check_train(oracle, net, ctx, params, rms, ro, I.HParams(clip_norm=0.01, lr=0.003), "clip")
+
+
+def test_train_nature_above_one_sample_per_compute_unit(paac, oracle):
+    """312 forward rows: more than one sample per compute unit, so the fp32 forward pass of layers 2-3
+    runs in the per-layer kernels on exact bf16 parts (a workgroup walks over several samples)."""
+    net = I.nature_net(6)
+    ctx = make_ctx(paac, net, 52, 5)
+    params = I.make_params(29, net, bias_range=0.05)
+    rms = I.make_rms(29, net, hi=0.01)
+    ro = I.make_rollout(29, net, 52, 5, 0.05)
+    check_train(oracle, net, ctx, params, rms, ro, I.HParams(lr=0.002), "nature_52x5")
 
 
 def test_train_first_step_from_zero_state_and_paper_hparams(paac, oracle):
