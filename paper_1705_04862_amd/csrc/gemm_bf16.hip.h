@@ -358,7 +358,11 @@ __global__ __launch_bounds__(256, T::MINW) void gemm_bf16_kernel(const AL al, co
     constexpr bool LOUT = EpiTraits<EP>::kEntry;
     constexpr int LDO = BN + 8, CPR = BN / 8, C_IT = LOUT ? BM * CPR / 256 : 1;
     static_assert(!LOUT || (BM * CPR) % 256 == 0, "whole chunks per thread");
-    __shared__ __attribute__((aligned(16))) bf16_t outT[LOUT ? BM * LDO : 8];
+    // the output tile reuses the operand buffers when it fits (the k loop ends with a barrier, and a
+    // barrier after the tile's stores keeps the next tile's operands from overwriting it too early)
+    constexpr bool OUT_ALIAS = LOUT && BM * LDO <= 2 * A_BUF + 2 * B_BUF;
+    __shared__ __attribute__((aligned(16))) bf16_t outT_own[LOUT && !OUT_ALIAS ? BM * LDO : 8];
+    bf16_t* const outT = OUT_ALIAS ? smem : outT_own;
     int cent[C_IT];
     uint4 caux[C_IT];
     float ebias[TN];
@@ -430,6 +434,7 @@ __global__ __launch_bounds__(256, T::MINW) void gemm_bf16_kernel(const AL al, co
                 }
                 if (cent[c] >= 0) *reinterpret_cast<uint4*>(ep.dst() + cent[c]) = v;
             }
+            if constexpr (OUT_ALIAS) __syncthreads();
         }
         zero_acc();
     };

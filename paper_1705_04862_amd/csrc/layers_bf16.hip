@@ -18,6 +18,9 @@ typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
 // 128 rows, four waves along m; 32 or 64 columns (a 16-wide output uses the 32-wide tile)
 typedef TileB<128, 32, 64, 4, 1, 3, 3> B128x32;
 typedef TileB<128, 64, 64, 4, 1, 3> B128x64;
+// plain fc GEMMs: 2 x 2 fragments per wave, so that two LDS fragment reads feed two MFMAs each
+// (the 128x64 tile with four waves along m reads three fragments for two MFMAs and is bound by LDS reads)
+typedef TileB<128, 128, 32, 2, 2, 3> B128x128;
 template <int N> struct TileBForN { typedef B128x64 type; };
 template <> struct TileBForN<16> { typedef B128x32 type; };
 template <> struct TileBForN<32> { typedef B128x32 type; };
@@ -115,9 +118,11 @@ static void fc_dims(int arch, int& flat, int& fc) {
     if (arch == 0) { flat = 2592; fc = 256; } else { flat = 3136; fc = 512; }
 }
 
+// up to 1024 rows (select calls) the narrower tile gives more workgroups and is faster
+static bool fc_fwd_wide(int ns) { return ns > 1024; }
 int fc_fwd_tiles_bf16(int arch, int ns) {
     int flat, fc; fc_dims(arch, flat, fc);
-    return ((ns + 127) / 128) * (fc / 64);
+    return ((ns + 127) / 128) * (fc / (fc_fwd_wide(ns) ? 128 : 64));
 }
 
 // partial[split][ns][fc] (fp32) = x[ns][flat] . Wt[fc][flat]^T
@@ -126,6 +131,7 @@ hipError_t fc_fwd_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* W
     DenseRowsK8 al{x, ns, flat};
     DenseRowsK8 bl{Wt, fc, flat};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
+    if (fc_fwd_wide(ns)) return launch_gemm_bf16<B128x128>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
     return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
 }
 
@@ -135,12 +141,14 @@ hipError_t fc_dgrad_bf16(hipStream_t s, int arch, const bf16_t* dh, const bf16_t
     DenseRowsK8 al{dh, ns, fc};
     DenseRowsK8 bl{Wc, flat, fc};
     EpiDenseMaskB ep{dx, act, flat, nullptr};
+    // a small batch gives too few of the wide tiles
+    if (ns >= 4096) return launch_gemm_bf16<B128x128>(s, al, bl, ep, ns, flat, fc, 1, 0);
     return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, flat, fc, 1, 0);
 }
 
 int fc_wgrad_tiles_bf16(int arch) {
     int flat, fc; fc_dims(arch, flat, fc);
-    return ((flat + 127) / 128) * (fc / 64);
+    return ((flat + 127) / 128) * (fc / 128);
 }
 
 hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* dh, float* pw, float* pb, int ns, Split sp) {
@@ -148,7 +156,7 @@ hipError_t fc_wgrad_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t*
     DenseKCols8 al{x, flat, flat};
     DenseKCols8 bl{dh, fc, fc};
     EpiPartial<true> ep{pw, (size_t)flat * fc, fc, pb, fc};
-    return launch_gemm_bf16<B128x64>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per, 1);
+    return launch_gemm_bf16<B128x128>(s, al, bl, ep, flat, fc, ns, sp.n, sp.k_per, 1);
 }
 
 // ---------------------------------------------------------------------------------- bf16 weight copies
