@@ -75,6 +75,14 @@ template <class G> struct ExactConv {
                     Wp + (size_t)p * WPLANE + ((size_t)(nb * KSTEPS + kg * KPW + i) * 64 + lane) * 8));
     }
 
+    // the three parts of k-step i of this wave's share
+    static __device__ __forceinline__ void load_weights_step(const bf16_t* __restrict__ Wp, int nb, int kg, int lane, int i, bf16x8 (&bw)[3][KPW]) {
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+            bw[p][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                Wp + (size_t)p * WPLANE + ((size_t)(nb * KSTEPS + kg * KPW + i) * 64 + lane) * 8));
+    }
+
     static __device__ __forceinline__ void row_offsets(int lane, int (&a_off)[FRAGS]) {
         const int m = lane & 31, half = lane >> 5;
 #pragma unroll
@@ -98,8 +106,12 @@ template <class G> struct ExactConv {
 
     // acc += this wave's k-steps of (images) x (weights); the fragments of step i + 1 are read while
     // those of i are multiplied
+    // `between(i)` runs after the MFMAs of step i have been issued (requests for later phases go there:
+    // the matrix pipe is busy for hundreds of cycles, the memory instructions issue in its shadow).
+    struct Nothing { __device__ __forceinline__ void operator()(int) const {} };
+    template <class F = Nothing>
     static __device__ __forceinline__ void mfma(const bf16_t* img, const int (&a_off)[FRAGS], int kg, const bf16x8 (&bw)[3][KPW],
-                                                f32x16 (&acc)[FRAGS]) {
+                                                f32x16 (&acc)[FRAGS], F&& between = F()) {
         u32x4 a_cur[3][FRAGS], a_nxt[3][FRAGS];
         const int k0 = koff(kg * KPW);
 #pragma unroll
@@ -123,6 +135,8 @@ template <class G> struct ExactConv {
                     acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_cur[pa][f]), bw[pw][i], acc[f], 0, 0, 0);
             };
             mul(2, 0); mul(0, 2); mul(1, 1); mul(1, 0); mul(0, 1); mul(0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            between(i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int p = 0; p < 3; ++p)
@@ -346,8 +360,9 @@ __global__ __launch_bounds__(256, 1) void trunk_fwd_exact_kernel(const uint8_t* 
     __syncthreads();
     // Fragments wave, wave + 4, .. of the 32-position fragments, all at once (k-steps outside, fragments
     // inside: four independent accumulators per weight fragment; a fragment index past the map repeats
-    // the last position and is not stored).  Half way through, the second layer's weights are
-    // requested: before the stores of this layer's epilogue, so that waiting for them never waits for a store.
+    // the last position and is not stored).  The second layer's weights are requested on the way, a
+    // k-step's worth after each k-step: in the shadow of the MFMAs, and before the stores of this
+    // layer's epilogue, so that waiting for them never waits for a store.
     constexpr int FPW = (FRAGS1 + 3) / 4;
     const bf16_t* a0[FPW];
     f32x16 acc1[FPW];
@@ -374,11 +389,12 @@ __global__ __launch_bounds__(256, 1) void trunk_fwd_exact_kernel(const uint8_t* 
             for (int p = 2; p >= 0; --p)
 #pragma unroll
                 for (int j = 0; j < FPW; ++j) acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], w1[p][c * 4 + ks], acc1[j], 0, 0, 0);
-            if (c * 4 + ks == 7) {
-                __builtin_amdgcn_sched_barrier(0);
-                S2::load_weights(W2p, nb2, kg2, lane, w2);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            // the second layer's weights, a few per k-step, in the shadow of the MFMAs just issued
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = (c * 4 + ks) * S2::KPW / 16; i < (c * 4 + ks + 1) * S2::KPW / 16; ++i)
+                S2::load_weights_step(W2p, nb2, kg2, lane, i, w2);
+            __builtin_amdgcn_sched_barrier(0);
         }
     // bias + ReLU, split into layer 2's images.  Lanes m and m ^ 1 hold neighbouring channels of one
     // position: one word per pair and part.
@@ -437,11 +453,16 @@ __global__ __launch_bounds__(256, 1) void trunk_fwd_exact_kernel(const uint8_t* 
     for (int f = 0; f < S2::FRAGS; ++f)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc2[f][q] = 0.f;
-    S2::mfma(img2, a_off2, kg2, w2, acc2);
-    __builtin_amdgcn_sched_barrier(0);
-    // the third layer's weights arrive during the second's epilogue
+    // the third layer's weights are requested k-step by k-step while the second layer multiplies
+    // (its own weights' registers become free at the same rate)
     bf16x8 w3[3][S3::KPW];
-    if constexpr (T::L3) S3::load_weights(W3p, nb3, kg3, lane, w3);
+    S2::mfma(img2, a_off2, kg2, w2, acc2, [&](int i) __attribute__((always_inline)) {
+        if constexpr (T::L3) {
+#pragma unroll
+            for (int j = 0; j < S3::KPW; ++j)
+                if (j * S2::KPW / S3::KPW == i) S3::load_weights_step(W3p, nb3, kg3, lane, j, w3);
+        }
+    });
     __builtin_amdgcn_sched_barrier(0);
     S2::finish(acc2, red, oimg2, nb2, kg2, lane, bias2);
     float* const o2 = out2 + (size_t)s * (S2::ROWS * S2::COUT);
