@@ -113,6 +113,7 @@ struct Buffers {
     bf16_t *wt[3], *wd[3], *fc_t, *fc_c;   // bf16 weight copies (bf16 configuration only)
     WeightSplits splits;    // fp32 configuration: conv weights as three bf16 parts each
     WeightCopies copies;
+    WeightMirrors mirrors;  // what the optimiser keeps up to date: the splits or the copies
     float *pw[3], *pb[3], *fc_pw, *fc_pb, *hd_pw, *hd_pb;
     size_t bytes;
 };
@@ -168,6 +169,21 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
         }
         copy(b.fc_t, a.fc_w, n.flat, n.fc, 1, 0);
         copy(b.fc_c, a.fc_w, n.flat, n.fc, 1, 1);
+    }
+    // the optimiser rewrites splits / copies together with theta
+    WeightMirrors& m = b.mirrors;
+    auto mirror_of = [&](int off_, int K, int C, int cin) -> int {
+        for (int i = 0; i < m.n; ++i) if (m.off[i] == off_) return i;
+        const int i = m.n++;
+        m.off[i] = off_; m.K[i] = K; m.C[i] = C; m.cin[i] = cin;
+        return i;
+    };
+    for (int l = 0; l < b.splits.n; ++l) m.split[mirror_of(b.splits.off[l], b.splits.K[l], b.splits.C[l], n.conv[l].cin)] = b.splits.dst[l];
+    for (int q = 0; q < b.copies.n; ++q) {
+        const WeightCopies& w = b.copies;
+        const int i = mirror_of(w.src_off[q], w.K[q], w.C[q], w.cin[q]);
+        const int d = m.copy[i][0] ? 1 : 0;
+        m.copy[i][d] = w.dst[q]; m.mode[i][d] = w.mode[q];
     }
     b.bytes = off;
     return b;
@@ -432,9 +448,8 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     L.run(K_TRN_GRAD_REDUCE, [&] { return grad_reduce_norm(L.s, g, b.grads, b.block_ss); });
     L.run(K_TRN_RMSPROP, [&] {
         return rmsprop_update(L.s, a.p_int, b.theta, b.g2, b.grads, b.block_ss, n_ss, b.hp, b.loss_partials, p.n_loss_blocks,
-                              b.stats, reinterpret_cast<StatsOut*>(x.stats), b.splits);
+                              b.stats, reinterpret_cast<StatsOut*>(x.stats), b.mirrors);
     });
-    if (bf16) L.run(K_TRN_BF16W, [&] { return make_bf16_weights(L.s, b.copies, b.theta); });
     *err_id = L.err_id;
     return L.err;
 }

@@ -97,6 +97,18 @@ struct WeightSplits {
     __host__ __device__ int plane(int l) const { return (C[l] + 31) / 32 * 32 * K[l]; }
 };
 hipError_t split_weights(hipStream_t s, const WeightSplits& ws, const float* theta);
+// What the optimiser writes besides theta when it updates weight matrix W[K][C] (K a multiple of 8):
+// the three bf16 parts (fp32 configuration) and / or up to two bf16 copies in the layouts of
+// make_bf16_weights_kernel (bf16 configuration), so that no separate pass over the weights follows.
+constexpr int kMaxMirrors = 4;
+struct WeightMirrors {
+    int n;
+    int off[kMaxMirrors], K[kMaxMirrors], C[kMaxMirrors], cin[kMaxMirrors];
+    bf16_t* split[kMaxMirrors];                 // parts in fragment order (see WeightSplits), or null
+    bf16_t* copy[kMaxMirrors][2];               // bf16 copies, or null
+    int mode[kMaxMirrors][2];
+    __host__ __device__ int plane(int l) const { return (C[l] + 31) / 32 * 32 * K[l]; }
+};
 // first convolution of the fp32 path from the three bf16 parts of its weights, fp32 NHWC output
 hipError_t conv1_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16_t* w_parts, const float* b, float* out, int ns);
 // layers 1.. of the fp32 path, one sample per workgroup, from the parts of weights and activations
@@ -173,7 +185,7 @@ hipError_t grad_reduce_norm(hipStream_t s, const GradSegments& seg, float* grads
 struct StatsOut { float policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale; int32_t nonfinite; };
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads,
                           const float* block_ss, int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks,
-                          StatsOut* stats_a, StatsOut* stats_b, const WeightSplits& ws);
+                          StatsOut* stats_a, StatsOut* stats_b, const WeightMirrors& ws);
 hipError_t fill_uniforms(hipStream_t s, uint64_t seed, uint64_t offset, float* out, size_t n);
 
 hipError_t delay_us(hipStream_t s, unsigned us);

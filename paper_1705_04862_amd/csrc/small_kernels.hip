@@ -559,13 +559,13 @@ hipError_t split_weights(hipStream_t s, const WeightSplits& ws, const float* the
 // Global-norm clip (scale = min(1, c/||g||)) fused with RMSProp, epsilon inside the root:
 //   g2 <- alpha g2 + (1-alpha) (s g)^2 ;  theta <- theta - lr (s g) / sqrt(g2 + eps).
 // Every block re-derives the norm from the per-block partial sums (same order everywhere).
-// The updated weights of the matrices listed in ws (fp32 configuration; ws.n = 0 otherwise) are also
-// written as their three bf16 parts for the next forward pass.
+// The updated weights of the matrices listed in ws are also written in the forms the next forward and
+// backward pass read (three bf16 parts in the fp32 configuration, bf16 copies in the bf16 one).
 __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* theta, float4* g2, const float4* grads,
                                                              const float* block_ss, int n_ss, const float* hp,
                                                              const float* loss_partials, int n_loss_blocks,
                                                              StatsOut* stats_a, StatsOut* stats_b,
-                                                             const WeightSplits ws, int ws_blocks) {
+                                                             const WeightMirrors ws, int ws_blocks) {
     __shared__ float red[256];
     float part = 0.f;
     for (int q = threadIdx.x; q < n_ss; q += 256) part += block_ss[q];
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
     const float oma = 1.0f - alpha;
     // The matrices of ws are updated by the first ws_blocks workgroups, one thread per (eight
     // consecutive k, column): lanes along the columns read and write whole rows, and a thread holds
-    // exactly the eight values of one 16-byte fragment slot of each part.
+    // exactly the eight values of one 16-byte slot of a part buffer or of a k-contiguous bf16 copy.
     if ((int)blockIdx.x < ws_blocks) {
         int u = blockIdx.x * 256 + threadIdx.x;
         for (int l = 0; l < ws.n; ++l) {
@@ -600,13 +600,34 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
                     tv[j] -= lr * g / sqrtf(vv[j] + eps);
                     v2[at] = vv[j]; th[at] = tv[j];
                 }
+                if (ws.split[l]) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) split3_pack(tv[2 * j], tv[2 * j + 1], hi[j], mid[j], lo[j]);
-                const int plane = ws.plane(l);
-                bf16_t* d = ws.dst[l] + (size_t)((((c >> 5) * (K >> 4) + (k8 >> 1)) * 64 + (k8 & 1) * 32 + (c & 31)) * 8);
-                *reinterpret_cast<uint4*>(d) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-                *reinterpret_cast<uint4*>(d + plane) = make_uint4(mid[0], mid[1], mid[2], mid[3]);
-                *reinterpret_cast<uint4*>(d + 2 * plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    for (int j = 0; j < 4; ++j) split3_pack(tv[2 * j], tv[2 * j + 1], hi[j], mid[j], lo[j]);
+                    const int plane = ws.plane(l);
+                    bf16_t* d = ws.split[l] + (size_t)((((c >> 5) * (K >> 4) + (k8 >> 1)) * 64 + (k8 & 1) * 32 + (c & 31)) * 8);
+                    *reinterpret_cast<uint4*>(d) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                    *reinterpret_cast<uint4*>(d + plane) = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+                    *reinterpret_cast<uint4*>(d + 2 * plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                }
+                auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
+                for (int d = 0; d < 2; ++d) {
+                    bf16_t* dst = ws.copy[l][d];
+                    if (!dst) continue;
+                    const int mode = ws.mode[l][d];
+                    if (mode == 0 || mode == 3) {          // k-contiguous: one 16-byte store
+                        const uint4 w = make_uint4(bf(tv[0]) | (bf(tv[1]) << 16), bf(tv[2]) | (bf(tv[3]) << 16),
+                                                   bf(tv[4]) | (bf(tv[5]) << 16), bf(tv[6]) | (bf(tv[7]) << 16));
+                        const size_t at = mode == 0 ? (size_t)c * K + k8 * 8 : (size_t)k8 * 256 + c * 8;
+                        *reinterpret_cast<uint4*>(dst + at) = w;
+                    } else if (mode == 1) {                // the matrix as it is: lanes write consecutive columns
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) dst[(size_t)(k8 * 8 + j) * C + c] = (bf16_t)bf(tv[j]);
+                    } else {                               // [ci][tap][co]: eight consecutive k are eight channels of one tap
+                        const int cin = ws.cin[l], T = K / cin, tap = (k8 * 8) / cin, ci0 = (k8 * 8) % cin;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) dst[((size_t)(ci0 + j) * T + tap) * C + c] = (bf16_t)bf(tv[j]);
+                    }
+                }
                 break;
             }
             u -= units;
@@ -650,7 +671,7 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
 
 hipError_t rmsprop_update(hipStream_t s, int p_int, float* theta, float* g2, const float* grads, const float* block_ss,
                           int n_ss, const float* hp, const float* loss_partials, int n_loss_blocks, StatsOut* stats_a, StatsOut* stats_b,
-                          const WeightSplits& ws) {
+                          const WeightMirrors& ws) {
     const int n4 = p_int / 4;
     int blocks = (n4 + 255) / 256;
     if (blocks > 512) blocks = 512;       // grid-stride loop: fewer, longer-lived workgroups
