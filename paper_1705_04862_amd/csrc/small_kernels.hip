@@ -338,21 +338,36 @@ hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
 //   blocks [0, n_dh):  dh[row][j] = 1[h > 0] * (sum_a dz[row][a] pi_w[a][j] + dv[row] v_w[j])
 //   the others:        partial_w[chunk][a][j] = sum over the chunk's rows of coef(row, a) * h[row][j],
 //                      coef = dz (a < A) or dv (a == A); partial_b[chunk][a] = sum of coef.
-__global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, int n_dh, int rows_per_chunk, const float* dz,
-                                                        const float* dv, const float* pi_w, const float* v_w, const float* h,
-                                                        float* dh, bf16_t* dh_b, float* pw, float* pb) {
-    if ((int)blockIdx.x < n_dh) {
+// dh blocks of both head-backward kernels
+__device__ __forceinline__ void heads_dh_block(int F, int A, int rows, const float* dz, const float* dv, const float* pi_w,
+                                               const float* v_w, const float* h, float* dh, bf16_t* dh_b) {
+    {
         const int F4 = F / 4;
         const int idx = blockIdx.x * 256 + threadIdx.x;
         if (idx >= rows * F4) return;
         const int row = idx / F4, j = (idx % F4) * 4;
-        const float d = dv[row];
         const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
-        float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
-        for (int k = 0; k < A; ++k) {
-            const float g = dz[(size_t)row * A + k];
-            const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
-            acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+        float4 acc;
+        if (F4 % 64 == 0) {
+            // a wave works on one row: its A + 1 coefficients are one load (lane k fetches coefficient
+            // k) and broadcasts instead of A + 1 loads of the same address by every lane
+            const int lane = threadIdx.x & 63, rowu = __builtin_amdgcn_readfirstlane(row);
+            const float cv = lane < A ? dz[(size_t)rowu * A + lane] : (lane == A ? dv[rowu] : 0.f);
+            const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), A));
+            acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
+            for (int k = 0; k < A; ++k) {
+                const float g = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), k));
+                const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
+                acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+            }
+        } else {
+            const float d = dv[row];
+            acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
+            for (int k = 0; k < A; ++k) {
+                const float g = dz[(size_t)row * A + k];
+                const float4 w = *reinterpret_cast<const float4*>(pi_w + (size_t)k * F + j);
+                acc.x += g * w.x; acc.y += g * w.y; acc.z += g * w.z; acc.w += g * w.w;
+            }
         }
         const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
         acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
@@ -363,6 +378,14 @@ __global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, 
         } else {
             *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
         }
+    }
+}
+
+__global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, int n_dh, int rows_per_chunk, const float* dz,
+                                                        const float* dv, const float* pi_w, const float* v_w, const float* h,
+                                                        float* dh, bf16_t* dh_b, float* pw, float* pb) {
+    if ((int)blockIdx.x < n_dh) {
+        heads_dh_block(F, A, rows, dz, dv, pi_w, v_w, h, dh, dh_b);
         return;
     }
     // weight-gradient block (x: 256 hidden units, k: output, c: chunk of rows)
@@ -387,11 +410,105 @@ __global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, 
     if (j == 0) pb[c * (A + 1) + k] = accb;
 }
 
+// The same for long chunks of rows (large batches).  With one output per block the A + 1 blocks of a
+// chunk read the same rows of h again and again (6.7 times the bytes, measured); here a block owns 64
+// hidden units of a chunk for all outputs, its four waves take every fourth row, and their sums meet
+// in LDS in wave order.
+template <int AMAX>
+__global__ __launch_bounds__(256) void heads_bwd_rows_kernel(int F, int A, int rows, int n_dh, int rows_per_dh, int rows_per_chunk, const float* dz,
+                                                             const float* dv, const float* pi_w, const float* v_w, const float* h,
+                                                             float* dh, bf16_t* dh_b, float* pw, float* pb) {
+    if ((int)blockIdx.x < n_dh) {
+        // dh for rows_per_dh rows: a thread keeps the head weights of its four hidden units in
+        // registers for all of them (one row at a time they are fetched again for every row: 20 KB per
+        // wave from L2), a wave works on one row at a time, so dz and dv are scalar loads
+        const int F4 = F / 4, quad = threadIdx.x % F4, rpi = 256 / F4, j = quad * 4;
+        const int sub = __builtin_amdgcn_readfirstlane(threadIdx.x / F4);      // F4 is a multiple of 64: uniform in a wave
+        float4 w[AMAX];
+#pragma unroll
+        for (int k = 0; k < AMAX; ++k) w[k] = *reinterpret_cast<const float4*>(pi_w + (size_t)min(k, A - 1) * F + j);
+        const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
+        const int row_end = min(rows, ((int)blockIdx.x + 1) * rows_per_dh);
+#pragma unroll 4
+        for (int row = blockIdx.x * rows_per_dh + sub; row < row_end; row += rpi) {
+            const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
+            // the row's A + 1 coefficients: one load (lane k fetches coefficient k), then broadcasts
+            const int lane = threadIdx.x & 63;
+            const float cv = lane < A ? dz[(size_t)row * A + lane] : (lane == A ? dv[row] : 0.f);
+            const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), A));
+            float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
+#pragma unroll
+            for (int k = 0; k < AMAX; ++k)
+                if (k < A) {
+                    const float g = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), k));
+                    acc.x += g * w[k].x; acc.y += g * w[k].y; acc.z += g * w[k].z; acc.w += g * w[k].w;
+                }
+            acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
+            acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
+            if (dh_b) {
+                auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
+                *reinterpret_cast<uint2*>(dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
+            } else {
+                *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+            }
+        }
+        return;
+    }
+    __shared__ float part[4][AMAX + 1][64];
+    __shared__ float partb[4][AMAX + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wb = blockIdx.x - n_dh, fx = F / 64, fxi = wb % fx, c = wb / fx, K1 = A + 1;
+    const int j = fxi * 64 + lane;
+    const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);      // a trailing chunk may be empty: zeros
+    float acc[AMAX + 1], accb[AMAX + 1];
+#pragma unroll
+    for (int k = 0; k <= AMAX; ++k) { acc[k] = 0.f; accb[k] = 0.f; }
+    for (int r = r0 + wave; r < r1; r += 32) {         // eight of this wave's rows in flight
+        float hv[8], cv[8];                            // cv: lane k holds coefficient k of the row (zero past the chunk)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int rr = r + 4 * q;
+            hv[q] = h[(size_t)min(rr, r1 - 1) * F + j];
+            cv[q] = (rr < r1 && lane < K1) ? (lane < A ? dz[(size_t)rr * A + lane] : dv[rr]) : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+#pragma unroll
+            for (int k = 0; k <= AMAX; ++k)
+                if (k < K1) {
+                    const float g = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv[q]), k));
+                    acc[k] += g * hv[q]; accb[k] += g;
+                }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k <= AMAX; ++k)
+        if (k < K1) { part[wave][k][lane] = acc[k]; if (lane == 0) partb[wave][k] = accb[k]; }
+    __syncthreads();
+    for (int e = tid; e < K1 * 64; e += 256) {
+        const int k = e / 64, l = e % 64;
+        pw[((size_t)c * K1 + k) * F + fxi * 64 + l] = ((part[0][k][l] + part[1][k][l]) + part[2][k][l]) + part[3][k][l];
+    }
+    if (fxi == 0 && tid < K1) pb[c * K1 + tid] = ((partb[0][tid] + partb[1][tid]) + partb[2][tid]) + partb[3][tid];
+}
+
 hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv, const float* pi_w,
                      const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* pw, float* pb) {
     if (rows <= 0 || n_chunk <= 0 || F % 256 != 0) return hipErrorInvalidValue;
     const int n_dh = (rows * (F / 4) + 255) / 256;
     const int rpc = (rows + n_chunk - 1) / n_chunk;
+    if (rows >= 1024 && A <= 32 && (F / 4) % 64 == 0 && 256 % (F / 4) == 0) {            // large batches: h is read once
+        const int rpi = 256 / (F / 4);                       // rows a dh block works on at once
+        int rpd = rows / 512;                                // enough dh blocks to fill the chip, at most 32 rows each
+        rpd = rpd > 32 ? 32 : rpd;
+        rpd = (rpd + rpi - 1) / rpi * rpi;
+        const int n_dh = (rows + rpd - 1) / rpd;
+        const dim3 grid(n_dh + (F / 64) * n_chunk);
+        if (A <= 8) launch_k(heads_bwd_rows_kernel<8>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
+        else if (A <= 18) launch_k(heads_bwd_rows_kernel<18>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
+        else launch_k(heads_bwd_rows_kernel<32>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
+        return hipGetLastError();
+    }
     launch_k(heads_bwd_kernel, dim3(n_dh + (F / 256) * (A + 1) * n_chunk), dim3(256), s, F, A, rows, n_dh, rpc, dz, dv, pi_w, v_w, h,
              dh, dh_b, pw, pb);
     return hipGetLastError();

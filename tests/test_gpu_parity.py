@@ -534,7 +534,7 @@ def test_bf16_config4_full_size_sampled(paac, oracle):
         assert np.abs(grads[sl]).max() > 0, name
 
 
-@pytest.mark.parametrize("n_e", [16, 64, 128])
+@pytest.mark.parametrize("n_e", [16, 64, 128, 256])
 def test_ne_sweep_sizes_with_scaled_learning_rate(paac, oracle, n_e):
     """Sizes of the paper's n_e study (Experiments, the n_e / learning-rate figure): lr = 0.0007 n_e,
     one select slab and one train step each, on the smaller network so the oracle stays quick."""
