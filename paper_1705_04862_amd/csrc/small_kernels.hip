@@ -136,10 +136,9 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const HeadsArgs a) {
 // head weights of this wave's outputs) are issued at once; thread t owns F/256 hidden units, wave w
 // the outputs w, w+4, ...; the element-to-lane assignment and the reduction order of a dot product
 // are those of heads_fwd_kernel, so both kernels produce the same bits.
-template <int F, int KMAX>
+template <int F, int KMAX, int SMAX>        // SMAX: splits held in registers at once (loads issued per round, clamped)
 __global__ __launch_bounds__(256) void heads_fwd_row_kernel(const HeadsArgs a) {
     constexpr int C = F / 256, U = F / 256, KW = (KMAX + 3) / 4;      // chunks per lane, units per thread, outputs per wave
-    constexpr int SMAX = 32;                                          // splits held in registers at once
     __shared__ __attribute__((aligned(16))) float hs[F];
     __shared__ float outs[KMAX + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -205,7 +204,11 @@ __global__ __launch_bounds__(256) void heads_fwd_row_kernel(const HeadsArgs a) {
 }
 
 template <int F, int KMAX> static void launch_heads(hipStream_t s, const HeadsArgs& a) {
-    if (a.rows <= 512) launch_k((heads_fwd_row_kernel<F, KMAX>), dim3(a.rows), dim3(256), s, a);
+    if (a.rows <= 512) {
+        if (a.n_split <= 8) launch_k((heads_fwd_row_kernel<F, KMAX, 8>), dim3(a.rows), dim3(256), s, a);
+        else if (a.n_split <= 16) launch_k((heads_fwd_row_kernel<F, KMAX, 16>), dim3(a.rows), dim3(256), s, a);
+        else launch_k((heads_fwd_row_kernel<F, KMAX, 32>), dim3(a.rows), dim3(256), s, a);
+    }
     else launch_k((heads_fwd_kernel<F, KMAX>), dim3((a.rows + 3) / 4), dim3(256), s, a);
 }
 
