@@ -518,15 +518,13 @@ hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const f
 }
 
 // ------------------------------------------------------------------------------------ gradient reduction + norm
+// Sum over the 256 threads of a block (every thread gets it): within the waves with DPP moves, then
+// the four wave sums through LDS in wave order; two barriers (a tree through LDS took nine).
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
-    const int tid = threadIdx.x;
-    red[tid] = v;
+    const float w = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) red[tid] += red[tid + o];
-        __syncthreads();
-    }
-    const float r = red[0];
+    const float r = (red[0] + red[1]) + (red[2] + red[3]);
     __syncthreads();
     return r;
 }
