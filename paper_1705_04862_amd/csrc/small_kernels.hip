@@ -317,14 +317,12 @@ __global__ __launch_bounds__(256) void returns_loss_kernel(const LossArgs a) {
         }
         a.dv[i] = 2.f * cv * (V - R) * invB;
     }
-    __shared__ float red[3][256];
-    red[0][tid] = s_pl * invB; red[1][tid] = s_h * invB; red[2][tid] = s_vl * invB;   // means over the batch
+    // means over the batch: wave sums, then the four waves in order
+    __shared__ float red[3][4];
+    const float w0 = wave_sum(s_pl * invB), w1 = wave_sum(s_h * invB), w2 = wave_sum(s_vl * invB);
+    if ((tid & 63) == 0) { red[0][tid >> 6] = w0; red[1][tid >> 6] = w1; red[2][tid >> 6] = w2; }
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) { red[0][tid] += red[0][tid + o]; red[1][tid] += red[1][tid + o]; red[2][tid] += red[2][tid + o]; }
-        __syncthreads();
-    }
-    if (tid < 3) a.loss_partials[blockIdx.x * 4 + tid] = red[tid][0];
+    if (tid < 3) a.loss_partials[blockIdx.x * 4 + tid] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
 }
 
 hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
