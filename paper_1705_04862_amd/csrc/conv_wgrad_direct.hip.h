@@ -1,0 +1,237 @@
+// Weight gradient of the second and third convolution with bf16 operands, one sample at a time from LDS.
+//
+//   dW[(ky,kx,ci)][co] = sum over samples and output positions (oy,ox) of X[ST oy + ky][ST ox + kx][ci] * dY[oy][ox][co]
+//
+// The reduction runs over output positions, and an MFMA lane must hold eight consecutive reduction
+// indices of its row or column: both operands are position-major in memory, so both are transposed on
+// their way into LDS.  As a tiled GEMM the im2col operand is gathered from global memory again for
+// every tap (and the dY tile for every block of taps): 2.4 to 4 times the algorithmic bytes, and the
+// compute units' L1 fill rate bounds the kernel.  Here a workgroup reads a sample once.
+//
+// Reduction index = (oy, slot t of 16): one 16-deep MFMA step per output row.
+//   X^T  [ci][row = (y, parity of x)][16]   element e of a row is x = ST e + parity      (ST = 2)
+//        [ci][y][16]                        element e is x = e                           (ST = 1)
+//   dY^T [shift s][co][oy][16]              slot t holds ox = t - s, zero outside the map
+// For tap (ky,kx) the input element that meets ox is e = ox + s with s = kx / 2 (ST = 2) or kx (ST = 1):
+// with the dY copy shifted by s, slot t meets element e = t, so every fragment is an aligned 16-byte
+// read: A = X^T[ci][row(ST oy + ky, kx)][8 half ..], B = dY^T[s][co][oy][8 half ..].  Channel and
+// column pitches are odd multiples of 16 bytes (32 lanes read 32 different rows).
+// The transposition: a thread takes four positions (elements e .. e+3, or slots t .. t+3) of eight
+// channels (four 16-byte loads), transposes the 4 x 8 block in registers with byte permutes and writes
+// eight 8-byte LDS words.  Waves own the MFMA row blocks (tap, 32-channel group) round robin and both
+// 32-wide column blocks of each; a workgroup walks over samples and writes one partial dW and db.
+#pragma once
+#include "gemm_bf16.hip.h"
+
+namespace paac {
+
+template <class G> struct ConvWgradDirectShape {
+    static constexpr int CIN = G::CIN, COUT = G::COUT, KS = G::KS, ST = G::ST;
+    static_assert((ST == 1 || ST == 2) && CIN % 32 == 0 && COUT == 64, "layer shape");
+    static constexpr int NPAR = ST, EPR = (G::W + NPAR - 1) / NPAR;       // parity planes, elements per transposed row
+    static_assert(EPR <= 12 && G::WO + (ST == 2 ? 1 : KS - 1) <= 12, "three groups of four cover a row");
+    static constexpr int XROWS = G::H * NPAR, CP = XROWS * 16 + 8;        // channel pitch (elements)
+    static constexpr int NS = ST == 2 ? 2 : KS;                           // shifted copies of dY^T
+    static constexpr int DP = G::HO * 16 + 8;                             // column pitch of dY^T
+    static_assert((CP / 8) % 2 == 1 && (DP / 8) % 2 == 1, "pitches are odd multiples of 16 bytes");
+    static constexpr int XT = CIN * CP, DYT = NS * COUT * DP;
+    static constexpr int CF = CIN / 32, MF = KS * KS * CF, MPW = (MF + 3) / 4;      // MFMA row blocks, per wave
+    static constexpr int XU = XROWS * (CIN / 8) * 3, DU = G::HO * (COUT / 8) * NS * 3;    // transposition units
+    static constexpr int UIT = (XU + DU + 255) / 256;
+    static constexpr int LDS_BYTES = (XT + DYT) * 2 + 4 * COUT * 4;
+    static_assert(LDS_BYTES <= 160 * 1024, "fits the LDS of a compute unit");
+};
+
+template <class G>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
+                                                                   float* __restrict__ pw, float* __restrict__ pb, int ns) {
+    typedef ConvWgradDirectShape<G> S;
+    constexpr int CIN = S::CIN, COUT = S::COUT, KS = S::KS, ST = S::ST, NPAR = S::NPAR, CP = S::CP, NS = S::NS, DP = S::DP;
+    constexpr int CF = S::CF, MF = S::MF, MPW = S::MPW, XU = S::XU, DU = S::DU, UIT = S::UIT;
+    constexpr int IN_POS = G::H * G::W, ROWS = G::HO * G::WO;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    bf16_t* const xt = reinterpret_cast<bf16_t*>(lds_raw);
+    bf16_t* const dyt = xt + S::XT;
+    float* const dbs = reinterpret_cast<float*>(dyt + S::DYT);          // [4 waves][COUT]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m = lane & 31, half = lane >> 5;
+
+    // ---- this thread's transposition units: source offsets (elements within a sample, -1 = zero) and LDS target
+    int src[UIT][4], dst[UIT];
+    bool from_dy[UIT];
+#pragma unroll
+    for (int i = 0; i < UIT; ++i) {
+        const int u = tid + i * 256;
+        from_dy[i] = u >= XU;
+        dst[i] = -1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) src[i][q] = -1;
+        if (u < XU) {
+            const int g = u % 3, cg = (u / 3) % (CIN / 8), row = u / (3 * (CIN / 8));
+            const int y = row / NPAR, par = row % NPAR;
+            dst[i] = (cg * 8) * CP + row * 16 + g * 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int xx = (g * 4 + q) * NPAR + par;
+                if (xx < G::W) src[i][q] = (y * G::W + xx) * CIN + cg * 8;
+            }
+        } else if (u < XU + DU) {
+            const int v = u - XU;
+            const int g = v % 3, s = (v / 3) % NS, cg = (v / (3 * NS)) % (COUT / 8), oy = v / (3 * NS * (COUT / 8));
+            dst[i] = S::XT + (s * COUT + cg * 8) * DP + oy * 16 + g * 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ox = g * 4 + q - s;
+                if (ox >= 0 && ox < G::WO) src[i][q] = (oy * G::WO + ox) * COUT + cg * 8;
+            }
+        }
+    }
+    // Two register sets: the sample after next is requested as soon as this one's registers are free, so
+    // a request has two whole samples' time to arrive (with one workgroup per compute unit nothing else
+    // covers the latency; one sample ahead it was waited for, 1.5 us per sample).
+    u32x4 raw[2][UIT][4];
+    auto prefetch = [&](int smp, auto SET) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+        const bf16_t* xs = x + (size_t)smp * (IN_POS * CIN);
+        const bf16_t* ds = dy + (size_t)smp * (ROWS * COUT);
+#pragma unroll
+        for (int i = 0; i < UIT; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                raw[set][i][q] = *reinterpret_cast<const u32x4*>((from_dy[i] ? ds : xs) + max(src[i][q], 0));     // clamped: masked below
+    };
+    int smp = blockIdx.x;
+    if (smp >= ns) return;
+    prefetch(smp, std::integral_constant<int, 0>());
+    if (smp + (int)gridDim.x < ns) prefetch(smp + gridDim.x, std::integral_constant<int, 1>());
+    // everything that no unit writes (row padding, slots outside the map) stays zero
+    for (int i = tid; i < (S::XT + S::DYT) / 8; i += 256) reinterpret_cast<uint4*>(lds_raw)[i] = zero_u4();
+
+    f32x16 acc[MPW][2];
+#pragma unroll
+    for (int i = 0; i < MPW; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) { acc[i][0][q] = 0.f; acc[i][1][q] = 0.f; }
+    float db[2] = {0.f, 0.f};
+
+    // one copy of the MFMA phase per wave keeps taps, shifts and accumulator indices constants
+    auto per_wave = [&](auto&& fn) __attribute__((always_inline)) {
+        if (wave == 0) fn(std::integral_constant<int, 0>());
+        if (wave == 1) fn(std::integral_constant<int, 1>());
+        if (wave == 2) fn(std::integral_constant<int, 2>());
+        if (wave == 3) fn(std::integral_constant<int, 3>());
+    };
+
+    auto one_sample = [&](auto SET) __attribute__((always_inline)) {
+        constexpr int set = decltype(SET)::value;
+        __syncthreads();                               // the previous sample's fragments have been read (first pass: the zeros are written)
+#pragma unroll
+        for (int i = 0; i < UIT; ++i) {
+            if (dst[i] >= 0) {
+                uint32_t w[4][4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool ok = src[i][q] >= 0;
+                    w[q][0] = ok ? raw[set][i][q].x : 0u; w[q][1] = ok ? raw[set][i][q].y : 0u;
+                    w[q][2] = ok ? raw[set][i][q].z : 0u; w[q][3] = ok ? raw[set][i][q].w : 0u;
+                }
+                bf16_t* d = xt + dst[i];                // dY^T follows X^T
+                const int pitch = from_dy[i] ? DP : CP;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {          // channel j of the eight: positions 0..3 as one 8-byte word
+                    const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                    uint2 o;
+                    o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
+                    o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
+                    *reinterpret_cast<uint2*>(d + j * pitch) = o;
+                }
+            }
+        }
+        if (smp + 2 * (int)gridDim.x < ns) prefetch(smp + 2 * gridDim.x, SET);
+        __syncthreads();
+        per_wave([&](auto WV) __attribute__((always_inline)) {
+            constexpr int wv = decltype(WV)::value;
+#pragma unroll
+            for (int oy = 0; oy < G::HO; ++oy) {
+                bf16x8 b[NS][2];
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb)
+                        b[s][cb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dyt + (s * COUT + cb * 32 + m) * DP + oy * 16 + half * 8));
+                if (oy % 4 == wv) {                    // bias gradient: the unshifted copy's slots, spread over the waves
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb) {
+                        const u32x4 v = __builtin_bit_cast(u32x4, b[0][cb]);
+                        db[cb] = dot2_ones(v.w, dot2_ones(v.z, dot2_ones(v.y, dot2_ones(v.x, db[cb]))));
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < MPW; ++i) {
+                    const int mf = wv + 4 * i;
+                    if (mf < MF) {
+                        const int tap = mf / CF, cf = mf % CF, ky = tap / KS, kx = tap % KS;
+                        const int s = ST == 2 ? kx >> 1 : kx, par = ST == 2 ? (kx & 1) : 0;
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                            xt + (cf * 32 + m) * CP + ((ST * oy + ky) * NPAR + par) * 16 + half * 8));
+                        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[s][0], acc[i][0], 0, 0, 0);
+                        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[s][1], acc[i][1], 0, 0, 0);
+                    }
+                }
+            }
+        });
+    };
+    for (;;) {
+        one_sample(std::integral_constant<int, 0>());
+        smp += gridDim.x;
+        if (smp >= ns) break;
+        one_sample(std::integral_constant<int, 1>());
+        smp += gridDim.x;
+        if (smp >= ns) break;
+    }
+
+    // ---- one partial per workgroup: dW[k = tap * CIN + ci][co], db[co]
+    float* out = pw + (size_t)blockIdx.x * (G::KK * COUT);
+    per_wave([&](auto WV) __attribute__((always_inline)) {
+        constexpr int wv = decltype(WV)::value;
+#pragma unroll
+        for (int i = 0; i < MPW; ++i) {
+            const int mf = wv + 4 * i;
+            if (mf < MF) {
+                const int tap = mf / CF, cf = mf % CF;
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        out[(size_t)(tap * CIN + cf * 32 + Mma<32>::row(q, lane)) * COUT + cb * 32 + m] = acc[i][cb][q];
+            }
+        }
+    });
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const float t = db[cb] + __shfl_xor(db[cb], 32);
+        if (half == 0) dbs[wave * COUT + cb * 32 + m] = t;
+    }
+    __syncthreads();
+    if (tid < COUT) pb[(size_t)blockIdx.x * COUT + tid] = ((dbs[tid] + dbs[COUT + tid]) + dbs[2 * COUT + tid]) + dbs[3 * COUT + tid];
+}
+
+// n_wgs partials are written: pw [n_wgs][KK][COUT], pb [n_wgs][COUT]; 1 <= n_wgs <= ns.
+template <class G>
+inline hipError_t launch_conv_wgrad_direct(hipStream_t s, const bf16_t* x, const bf16_t* dy, float* pw, float* pb, int ns, int n_wgs) {
+    if (ns <= 0 || n_wgs < 1 || n_wgs > ns) return hipErrorInvalidValue;
+    constexpr int LDS = ConvWgradDirectShape<G>::LDS_BYTES;
+    static bool ready = false;
+    if (!ready) {                       // more LDS than a kernel gets by default
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_wgrad_direct_kernel<G>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        ready = true;
+    }
+    launch_k_lds((conv_wgrad_direct_kernel<G>), dim3(n_wgs), dim3(256), LDS, s, x, dy, pw, pb, ns);
+    return hipGetLastError();
+}
+
+}  // namespace paac

@@ -119,6 +119,9 @@ hipError_t trunk_fwd_exact(hipStream_t s, int arch, const uint8_t* x, const bf16
 // first convolution's weight gradient from the image; dy fp32 (exact) or bf16; writes n_wgs partials [256][cout] / [cout]
 hipError_t conv1_wgrad_direct(hipStream_t s, int arch, bool exact, const uint8_t* x, const void* dy, float* pw, float* pb, int ns, int n_wgs);
 hipError_t make_bf16_weights(hipStream_t s, const WeightCopies& w, const float* theta);
+// bf16 configuration: partial sums (= workgroups) of the per-sample weight-gradient kernel of a layer,
+// 0 where the tiled GEMM with its split plan is used; conv_wgrad_bf16 takes them as Split{n, 0}
+int conv_wgrad_direct_wgs(int arch, int layer, int ns);
 
 // ---- small kernels (small_kernels.hip) ----
 struct HeadsArgs {

@@ -5,6 +5,7 @@
 #include "conv_dgrad_direct.hip.h"
 #include "conv_fwd_direct.hip.h"
 #include "conv_fwd_exact.hip.h"
+#include "conv_wgrad_direct.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -102,8 +103,20 @@ static hipError_t conv_wgrad_t(hipStream_t s, const void* in, const bf16_t* dy, 
     return launch_gemm_bf16<T>(s, al, bl, ep, G::KK, G::COUT, R, sp.n, sp.k_per);
 }
 
+// Workgroups (= partial sums) of the per-sample weight-gradient kernel, 0 where the tiled GEMM is used.
+// From 2048 samples on: below, a workgroup has too few samples to pay for one partial sum per
+// compute unit (256 partial sums per tensor for the reduction to add), and the GEMMs are as fast.
+int conv_wgrad_direct_wgs(int arch, int layer, int ns) {
+    if (arch != 1 || layer < 1 || ns < 2048) return 0;
+    return std::min(ns, device_cus());
+}
+
 hipError_t conv_wgrad_bf16(hipStream_t s, int arch, int layer, const void* in, const bf16_t* dy, float* pw, float* pb,
                            int ns, Split sp) {
+    if (arch == 1 && sp.k_per == 0) {                  // one sample at a time from LDS, sp.n workgroups
+        if (layer == 1) return launch_conv_wgrad_direct<NatC2>(s, (const bf16_t*)in, dy, pw, pb, ns, sp.n);
+        if (layer == 2) return launch_conv_wgrad_direct<NatC3>(s, (const bf16_t*)in, dy, pw, pb, ns, sp.n);
+    }
     if (arch == 0) {
         if (layer == 1) return conv_wgrad_t<NipsC2>(s, in, dy, pw, pb, ns, sp);
     } else {

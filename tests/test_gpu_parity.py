@@ -456,6 +456,20 @@ def test_bf16_config3_full_size(paac, oracle):
     check_train_bf16(oracle, cfg.net, ctx, params, rms, ro, cfg.hp, cfg.name)
 
 
+def test_bf16_large_batch_per_sample_weight_gradients(paac, oracle):
+    """2048 transitions (n_e=128, t_max=16, Nature net): from this batch on the weight gradients of
+    layers 2-3 run in the per-sample kernel (operands transposed into LDS) instead of the tiled GEMM;
+    the whole step against the oracle."""
+    net = I.nature_net(6)
+    n_e, t_max = 128, 16
+    ctx = make_ctx(paac, net, n_e, t_max, precision=1)
+    params = I.make_params(77, net, bias_range=0.05)
+    rms = I.make_rms(77, net, hi=0.01)
+    ro = I.make_rollout(77, net, n_e, t_max, 0.02)
+    ctx.set_state(params, rms)
+    check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16_128x16")
+
+
 def test_bf16_graph_replay_deterministic(paac):
     cfg = I.CONFIGS[3]
     net = cfg.net
