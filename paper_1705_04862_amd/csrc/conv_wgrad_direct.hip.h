@@ -37,7 +37,7 @@ template <class G> struct ConvWgradDirectShape {
     static constexpr int XT = CIN * CP, DYT = NS * COUT * DP;
     static constexpr int CF = CIN / 32, MF = KS * KS * CF, MPW = (MF + 3) / 4;      // MFMA row blocks, per wave
     static constexpr int XU = XROWS * (CIN / 8) * 3, DU = G::HO * (COUT / 8) * NS * 3;    // transposition units
-    static constexpr int UIT = (XU + DU + 255) / 256;
+    static constexpr int XIT = (XU + 255) / 256, DIT = (DU + 255) / 256, UIT = XIT + DIT;  // rounds of 256: first X, then dY
     static constexpr int LDS_BYTES = (XT + DYT) * 2 + 4 * COUT * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "fits the LDS of a compute unit");
 };
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
                                                                    float* __restrict__ pw, float* __restrict__ pb, int ns) {
     typedef ConvWgradDirectShape<G> S;
     constexpr int CIN = S::CIN, COUT = S::COUT, KS = S::KS, ST = S::ST, NPAR = S::NPAR, CP = S::CP, NS = S::NS, DP = S::DP;
-    constexpr int CF = S::CF, MF = S::MF, MPW = S::MPW, XU = S::XU, DU = S::DU, UIT = S::UIT;
+    constexpr int CF = S::CF, MF = S::MF, MPW = S::MPW, XU = S::XU, DU = S::DU, XIT = S::XIT, UIT = S::UIT;
     constexpr int IN_POS = G::H * G::W, ROWS = G::HO * G::WO;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* const xt = reinterpret_cast<bf16_t*>(lds_raw);
@@ -59,16 +59,15 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
     const int m = lane & 31, half = lane >> 5;
 
     // ---- this thread's transposition units: source offsets (elements within a sample, -1 = zero) and LDS target
+    // (round i holds X units for i < XIT and dY units after that, so the operand of a round is a constant)
     int src[UIT][4], dst[UIT];
-    bool from_dy[UIT];
 #pragma unroll
     for (int i = 0; i < UIT; ++i) {
-        const int u = tid + i * 256;
-        from_dy[i] = u >= XU;
+        const int u = i < XIT ? tid + i * 256 : XU + tid + (i - XIT) * 256;
         dst[i] = -1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) src[i][q] = -1;
-        if (u < XU) {
+        if (i < XIT && u < XU) {
             const int g = u % 3, cg = (u / 3) % (CIN / 8), row = u / (3 * (CIN / 8));
             const int y = row / NPAR, par = row % NPAR;
             dst[i] = (cg * 8) * CP + row * 16 + g * 4;
@@ -77,7 +76,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
                 const int xx = (g * 4 + q) * NPAR + par;
                 if (xx < G::W) src[i][q] = (y * G::W + xx) * CIN + cg * 8;
             }
-        } else if (u < XU + DU) {
+        } else if (i >= XIT && u < XU + DU) {
             const int v = u - XU;
             const int g = v % 3, s = (v / 3) % NS, cg = (v / (3 * NS)) % (COUT / 8), oy = v / (3 * NS * (COUT / 8));
             dst[i] = S::XT + (s * COUT + cg * 8) * DP + oy * 16 + g * 4;
@@ -100,7 +99,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
         for (int i = 0; i < UIT; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                raw[set][i][q] = *reinterpret_cast<const u32x4*>((from_dy[i] ? ds : xs) + max(src[i][q], 0));     // clamped: masked below
+                raw[set][i][q] = *reinterpret_cast<const u32x4*>((i >= XIT ? ds : xs) + max(src[i][q], 0));     // clamped: masked below
     };
     int smp = blockIdx.x;
     if (smp >= ns) return;
@@ -138,14 +137,14 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
                     w[q][2] = ok ? raw[set][i][q].z : 0u; w[q][3] = ok ? raw[set][i][q].w : 0u;
                 }
                 bf16_t* d = xt + dst[i];                // dY^T follows X^T
-                const int pitch = from_dy[i] ? DP : CP;
+                const int pitch_i = i >= XIT ? DP : CP;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {          // channel j of the eight: positions 0..3 as one 8-byte word
                     const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
                     uint2 o;
                     o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
                     o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
-                    *reinterpret_cast<uint2*>(d + j * pitch) = o;
+                    *reinterpret_cast<uint2*>(d + j * pitch_i) = o;
                 }
             }
         }
