@@ -38,7 +38,10 @@ template <class G> struct ConvWgradDirectShape {
     static constexpr int CF = CIN / 32, MF = KS * KS * CF, MPW = (MF + 3) / 4;      // MFMA row blocks, per wave
     static constexpr int XU = XROWS * (CIN / 8) * 3, DU = G::HO * (COUT / 8) * NS * 3;    // transposition units
     static constexpr int XIT = (XU + 255) / 256, DIT = (DU + 255) / 256, UIT = XIT + DIT;  // rounds of 256: first X, then dY
-    static constexpr int LDS_BYTES = (XT + DYT) * 2 + 4 * COUT * 4;
+    // two images where they fit: a sample is then transposed while the previous one is multiplied
+    static constexpr bool DB = 2 * (XT + DYT) * 2 + 4 * COUT * 4 <= 160 * 1024;
+    static constexpr int IMG = XT + DYT;
+    static constexpr int LDS_BYTES = (DB ? 2 : 1) * IMG * 2 + 4 * COUT * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "fits the LDS of a compute unit");
 };
 
@@ -52,7 +55,9 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     bf16_t* const xt = reinterpret_cast<bf16_t*>(lds_raw);
     bf16_t* const dyt = xt + S::XT;
-    float* const dbs = reinterpret_cast<float*>(dyt + S::DYT);          // [4 waves][COUT]
+    float* const dbs = reinterpret_cast<float*>(xt + (S::DB ? 2 : 1) * S::IMG);          // [4 waves][COUT]
+    constexpr bool DB = S::DB;
+    constexpr int IMG = S::IMG;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
     prefetch(smp, std::integral_constant<int, 0>());
     if (smp + (int)gridDim.x < ns) prefetch(smp + gridDim.x, std::integral_constant<int, 1>());
     // everything that no unit writes (row padding, slots outside the map) stays zero
-    for (int i = tid; i < (S::XT + S::DYT) / 8; i += 256) reinterpret_cast<uint4*>(lds_raw)[i] = zero_u4();
+    for (int i = tid; i < (DB ? 2 : 1) * IMG / 8; i += 256) reinterpret_cast<uint4*>(lds_raw)[i] = zero_u4();
 
     f32x16 acc[MPW][2];
 #pragma unroll
@@ -123,72 +128,138 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_direct_kernel(const bf16_t*
         if (wave == 3) fn(std::integral_constant<int, 3>());
     };
 
-    auto one_sample = [&](auto SET) __attribute__((always_inline)) {
-        constexpr int set = decltype(SET)::value;
-        __syncthreads();                               // the previous sample's fragments have been read (first pass: the zeros are written)
+    // round i of the transposition of the sample in register set SET, into image `buf`
+    auto transpose_round = [&](auto RI, auto SET, int buf) __attribute__((always_inline)) {
+        constexpr int i = decltype(RI)::value, set = decltype(SET)::value;
+        if (dst[i] >= 0) {
+            uint32_t w[4][4];
 #pragma unroll
-        for (int i = 0; i < UIT; ++i) {
-            if (dst[i] >= 0) {
-                uint32_t w[4][4];
+            for (int q = 0; q < 4; ++q) {
+                const bool ok = src[i][q] >= 0;
+                w[q][0] = ok ? raw[set][i][q].x : 0u; w[q][1] = ok ? raw[set][i][q].y : 0u;
+                w[q][2] = ok ? raw[set][i][q].z : 0u; w[q][3] = ok ? raw[set][i][q].w : 0u;
+            }
+            bf16_t* d = xt + buf * IMG + dst[i];       // dY^T follows X^T
+            constexpr int pitch_i = i >= XIT ? DP : CP;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const bool ok = src[i][q] >= 0;
-                    w[q][0] = ok ? raw[set][i][q].x : 0u; w[q][1] = ok ? raw[set][i][q].y : 0u;
-                    w[q][2] = ok ? raw[set][i][q].z : 0u; w[q][3] = ok ? raw[set][i][q].w : 0u;
-                }
-                bf16_t* d = xt + dst[i];                // dY^T follows X^T
-                const int pitch_i = i >= XIT ? DP : CP;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {          // channel j of the eight: positions 0..3 as one 8-byte word
-                    const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                    uint2 o;
-                    o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
-                    o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
-                    *reinterpret_cast<uint2*>(d + j * pitch_i) = o;
-                }
+            for (int j = 0; j < 8; ++j) {              // channel j of the eight: positions 0..3 as one 8-byte word
+                const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                uint2 o;
+                o.x = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
+                o.y = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
+                *reinterpret_cast<uint2*>(d + j * pitch_i) = o;
             }
         }
-        if (smp + 2 * (int)gridDim.x < ns) prefetch(smp + 2 * gridDim.x, SET);
-        __syncthreads();
+    };
+    auto transpose_all = [&](auto SET, int buf) __attribute__((always_inline)) {
+        [&]<int... I>(std::integer_sequence<int, I...>) {
+            (transpose_round(std::integral_constant<int, I>(), SET, buf), ...);
+        }(std::make_integer_sequence<int, UIT>());
+    };
+    // MFMA phase on image `buf`; between(oy) runs after the MFMAs of output row oy have been issued
+    auto mfma_phase = [&](int buf, auto&& between) __attribute__((always_inline)) {
+        const bf16_t* const xb = xt + buf * IMG;
+        const bf16_t* const db_ = xb + S::XT;
         per_wave([&](auto WV) __attribute__((always_inline)) {
             constexpr int wv = decltype(WV)::value;
-#pragma unroll
-            for (int oy = 0; oy < G::HO; ++oy) {
-                bf16x8 b[NS][2];
+            // fragments of output row oy + 1 are read before the MFMAs of row oy are issued
+            u32x4 bq[2][NS][2], aq[2][MPW];
+            auto read_frags = [&](auto OY, auto SLOT) __attribute__((always_inline)) {
+                constexpr int oy = decltype(OY)::value, sl = decltype(SLOT)::value;
 #pragma unroll
                 for (int s = 0; s < NS; ++s)
 #pragma unroll
                     for (int cb = 0; cb < 2; ++cb)
-                        b[s][cb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(dyt + (s * COUT + cb * 32 + m) * DP + oy * 16 + half * 8));
-                if (oy % 4 == wv) {                    // bias gradient: the unshifted copy's slots, spread over the waves
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) {
-                        const u32x4 v = __builtin_bit_cast(u32x4, b[0][cb]);
-                        db[cb] = dot2_ones(v.w, dot2_ones(v.z, dot2_ones(v.y, dot2_ones(v.x, db[cb]))));
-                    }
-                }
+                        bq[sl][s][cb] = *reinterpret_cast<const u32x4*>(db_ + (s * COUT + cb * 32 + m) * DP + oy * 16 + half * 8);
 #pragma unroll
                 for (int i = 0; i < MPW; ++i) {
                     const int mf = wv + 4 * i;
                     if (mf < MF) {
                         const int tap = mf / CF, cf = mf % CF, ky = tap / KS, kx = tap % KS;
-                        const int s = ST == 2 ? kx >> 1 : kx, par = ST == 2 ? (kx & 1) : 0;
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                            xt + (cf * 32 + m) * CP + ((ST * oy + ky) * NPAR + par) * 16 + half * 8));
-                        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[s][0], acc[i][0], 0, 0, 0);
-                        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[s][1], acc[i][1], 0, 0, 0);
+                        const int par = ST == 2 ? (kx & 1) : 0;
+                        aq[sl][i] = *reinterpret_cast<const u32x4*>(xb + (cf * 32 + m) * CP + ((ST * oy + ky) * NPAR + par) * 16 + half * 8);
                     }
                 }
-            }
+            };
+            read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, 0>());
+            [&]<int... OY>(std::integer_sequence<int, OY...>) {
+                ([&] {
+                    constexpr int oy = OY, sl = OY & 1;
+                    if constexpr (oy + 1 < G::HO) read_frags(std::integral_constant<int, oy + 1>(), std::integral_constant<int, sl ^ 1>());
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (oy % 4 == wv) {                // bias gradient: the unshifted copy's slots, spread over the waves
+#pragma unroll
+                        for (int cb = 0; cb < 2; ++cb) {
+                            const u32x4 v = bq[sl][0][cb];
+                            db[cb] = dot2_ones(v.w, dot2_ones(v.z, dot2_ones(v.y, dot2_ones(v.x, db[cb]))));
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < MPW; ++i) {
+                        const int mf = wv + 4 * i;
+                        if (mf < MF) {
+                            const int tap = mf / CF, kx = tap % KS;
+                            const int s = ST == 2 ? kx >> 1 : kx;
+                            const bf16x8 a = __builtin_bit_cast(bf16x8, aq[sl][i]);
+                            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bq[sl][s][0]), acc[i][0], 0, 0, 0);
+                            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bq[sl][s][1]), acc[i][1], 0, 0, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    between(std::integral_constant<int, oy>());
+                }(), ...);
+            }(std::make_integer_sequence<int, G::HO>());
         });
     };
-    for (;;) {
-        one_sample(std::integral_constant<int, 0>());
-        smp += gridDim.x;
-        if (smp >= ns) break;
-        one_sample(std::integral_constant<int, 1>());
-        smp += gridDim.x;
-        if (smp >= ns) break;
+    const int g = gridDim.x;
+    if constexpr (!DB) {
+        auto one_sample = [&](auto SET) __attribute__((always_inline)) {
+            __syncthreads();                           // the previous sample's fragments have been read (first pass: the zeros are written)
+            transpose_all(SET, 0);
+            if (smp + 2 * g < ns) prefetch(smp + 2 * g, SET);
+            __syncthreads();
+            mfma_phase(0, [](auto) {});
+        };
+        for (;;) {
+            one_sample(std::integral_constant<int, 0>());
+            smp += g;
+            if (smp >= ns) break;
+            one_sample(std::integral_constant<int, 1>());
+            smp += g;
+            if (smp >= ns) break;
+        }
+    } else {
+        // Two images: while the waves multiply sample k from image k % 2, they transpose sample k + 1
+        // (register set (k + 1) % 2) into the other image, a round after every few output rows, in the
+        // shadow of the MFMAs; one barrier per sample.
+        __syncthreads();                               // the zeros are written
+        transpose_all(std::integral_constant<int, 0>(), 0);
+        if (smp + 2 * g < ns) prefetch(smp + 2 * g, std::integral_constant<int, 0>());
+        auto one_sample = [&](int buf, auto NEXT) __attribute__((always_inline)) {
+            __syncthreads();                           // image `buf` is complete, the other one is no longer read
+            const bool has_next = smp + g < ns;
+            mfma_phase(buf, [&](auto OY) __attribute__((always_inline)) {
+                constexpr int oy = decltype(OY)::value;
+                [&]<int... I>(std::integer_sequence<int, I...>) {
+                    ([&] {
+                        if constexpr (I * G::HO / UIT == oy) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (has_next) transpose_round(std::integral_constant<int, I>(), NEXT, buf ^ 1);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }(), ...);
+                }(std::make_integer_sequence<int, UIT>());
+            });
+            if (smp + 3 * g < ns) prefetch(smp + 3 * g, NEXT);
+        };
+        for (;;) {
+            one_sample(0, std::integral_constant<int, 1>());
+            smp += g;
+            if (smp >= ns) break;
+            one_sample(1, std::integral_constant<int, 0>());
+            smp += g;
+            if (smp >= ns) break;
+        }
     }
 
     // ---- one partial per workgroup: dW[k = tap * CIN + ci][co], db[co]
