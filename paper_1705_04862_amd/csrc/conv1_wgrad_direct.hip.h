@@ -137,19 +137,30 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
         }
         __syncthreads();
         if (item + (int)gridDim.x < items) prefetch(item + gridDim.x);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        // the fragments of step t + 1 are read before the MFMAs of step t are issued
+        u32x4 fa[2][2], fb[2][NPART];
+        auto read_frags = [&](int t, int sl) __attribute__((always_inline)) {
             const int gi = min(2 * t + half, 14);                 // group 15 is all zero in dY: any valid image address
             const int oy = gi / 3, g = gi % 3;
             const bf16_t* ap = img + a_row + ((wave * IR + oy * G::ST) * 4) * PW + g * 8;
-            const bf16x8 a0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ap));                  // ky = ky_l
-            const bf16x8 a1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ap + 4 * 4 * PW));     // ky = 4 + ky_l
+            fa[sl][0] = *reinterpret_cast<const u32x4*>(ap);                  // ky = ky_l
+            fa[sl][1] = *reinterpret_cast<const u32x4*>(ap + 4 * 4 * PW);     // ky = 4 + ky_l
+#pragma unroll
+            for (int part = 0; part < NPART; ++part)
+                fb[sl][part] = *reinterpret_cast<const u32x4*>(dyt + (part * 32 + m) * SP + t * 16 + half * 8);
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (t + 1 < 8) read_frags(t + 1, (t + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int part = NPART - 1; part >= 0; --part) {
-                const bf16x8 bfr = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(dyt + (part * 32 + m) * SP + t * 16 + half * 8));
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfr, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfr, acc[1], 0, 0, 0);
+                const bf16x8 bfr = __builtin_bit_cast(bf16x8, fb[t & 1][part]);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[t & 1][0]), bfr, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[t & 1][1]), bfr, acc[1], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
