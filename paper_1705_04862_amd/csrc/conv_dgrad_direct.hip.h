@@ -108,6 +108,8 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
             for (int f = 0; f < FRAGS; ++f) a_cur[f] = a_nxt[f];
         }
         {                                              // the mask: in flight while the accumulators go to the dX image
+            // (requested before the MFMA phase it competes with the next sample's dY for the memory
+            // pipe of a kernel that is bound by HBM: measured 6 % slower)
             const bf16_t* base = act_in + (size_t)s * (G::H * G::W * CIN);
 #pragma unroll
             for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const u32x4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
@@ -222,6 +224,11 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
         }
         __syncthreads();                               // also: the previous sample's dX image has been read
         if (s + (int)gridDim.x < ns) PAAC_PREFETCH_DY(s + gridDim.x);
+        {                                              // the mask of this sample: in flight during the whole MFMA phase
+            const bf16_t* base = act_in + (size_t)s * (ROWS * CIN);
+#pragma unroll
+            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const u32x4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
+        }
 
         f32x16 acc[FRAGS];
 #pragma unroll
@@ -252,11 +259,6 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int f = 0; f < FRAGS; ++f) a_cur[f] = a_nxt[f];
-        }
-        {                                              // the mask: in flight during the reduction
-            const bf16_t* base = act_in + (size_t)s * (ROWS * CIN);
-#pragma unroll
-            for (int i = 0; i < DX_IT; ++i) pact[i] = *reinterpret_cast<const u32x4*>(base + (size_t)min(tid + i * 256, DX_CH - 1) * 8);
         }
         if (kh == 1) {
 #pragma unroll
