@@ -133,8 +133,8 @@ inline hipError_t launch_conv1_direct(hipStream_t s, const uint8_t* x, const bf1
 // the fp32 MFMA path.  16 k per 32-cycle instruction x 3 parts against 2 k per 64-cycle fp32
 // instruction: 5.3 times fewer matrix-core cycles, and no im2col gather.
 // A workgroup takes one band of HO / PARTS output rows of one sample: its 4 x (4 BR + 4) image
-// rows are four contiguous pieces of global memory.  The weights arrive as W[k][COUT] (fp32, the
-// layout of the parameter arena) and are cut into their three parts in registers once.
+// rows are four contiguous pieces of global memory.  The weights arrive as their three bf16 parts in
+// fragment order (WeightSplits: the optimiser writes them with every update), 16 bytes per lane and k-step.
 template <class G, int PARTS>
 __global__ __launch_bounds__(256, 1) void conv1_exact_kernel(const uint8_t* __restrict__ x, const bf16_t* __restrict__ Wp,
                                                           const float* __restrict__ bias, float* __restrict__ out, int ns,
