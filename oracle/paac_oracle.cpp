@@ -24,6 +24,12 @@
 //  * ReLU'(0) = 0.  No epsilon inside any logarithm (log-softmax is evaluated stably instead).
 //  * The categorical draw is the inverse CDF of the fp32 probabilities accumulated in ascending
 //    action order in fp32 (the precision of the kernel that takes the same decision).
+//  * ReLU'(pre) = 1[pre > 0] is a binary decision taken by floating point.  A caller may hand in the
+//    decisions another implementation took (one byte per unit); the oracle then uses those instead
+//    of its own sign test, in the forward pass (unit passes its pre-activation or is zero) and in
+//    the backward pass, and reports how many differ from its own and how close to zero its own
+//    pre-activation was where they differ.  Nothing else changes.  Without masks every decision is
+//    the oracle's own.
 //
 // Canonical parameter order: for each conv layer W[c_out][c_in][k][k] then b[c_out]; fc W[fc][flat]
 // (flat index = c*H*W + y*W + x), fc b; pi W[A][fc], pi b[A]; v W[fc], v b[1].
@@ -57,6 +63,15 @@ struct OracleHParams {
 struct OracleStats {
     double policy_loss, entropy, value_loss, total_loss, grad_norm, clip_scale;
     int32_t nonfinite;
+};
+
+// Where supplied ReLU decisions differ from the oracle's own (per layer: conv 1.., then fc).
+struct OracleFlipReport {
+    int64_t units[5];        // units looked at
+    int64_t flips[5];        // units whose supplied decision differs from 1[pre > 0]
+    double max_abs_pre[5];   // largest |pre-activation| (the oracle's) among those
+    double act_abs_max[5];   // largest |pre-activation| of the layer, for scale
+    double act_rms[5];       // root mean square of the layer's pre-activations
 };
 
 }  // extern "C"
@@ -130,8 +145,27 @@ std::vector<double> used_params(const Shapes& S, const double* th) {
 
 // Forward pass of one sample.  x: uint8 [C][H][W].  act: post-ReLU outputs of every conv layer
 // and of the fc layer, laid out per Shapes::act_off.  logits[A], *value.
+// mask (may be null): one byte per unit of `act`; non-zero = the unit is active.  With a mask the
+// unit's output is its pre-activation where the mask says active (whatever its sign) and zero
+// elsewhere.  rep (may be null) collects the comparison with the oracle's own sign test.
+struct FlipAcc { int64_t units[5], flips[5]; double max_abs_pre[5], abs_max[5], sum_sq[5]; };
+
+inline bool relu_on(const uint8_t* mask, size_t idx, double pre, int layer, FlipAcc* rep) {
+    const bool own = pre > 0.0;
+    if (!mask) return own;
+    const bool given = mask[idx] != 0;
+    if (rep) {
+        rep->units[layer] += 1;
+        const double a = std::fabs(pre);
+        if (a > rep->abs_max[layer]) rep->abs_max[layer] = a;
+        rep->sum_sq[layer] += pre * pre;
+        if (given != own) { rep->flips[layer] += 1; if (a > rep->max_abs_pre[layer]) rep->max_abs_pre[layer] = a; }
+    }
+    return given;
+}
+
 void forward_sample(const Shapes& S, const double* th, const uint8_t* x, double* act,
-                    double* logits, double* value) {
+                    double* logits, double* value, const uint8_t* mask = nullptr, FlipAcc* rep = nullptr) {
     std::vector<double> in0((size_t)S.cin[0] * S.hin[0] * S.win[0]);
     for (size_t i = 0; i < in0.size(); ++i) in0[i] = (double)x[i] / 255.0;
     const double* in = in0.data();
@@ -149,7 +183,8 @@ void forward_sample(const Shapes& S, const double* th, const uint8_t* x, double*
                             for (int kx = 0; kx < K; ++kx)
                                 acc += W[(((size_t)co * S.cin[l] + ci) * K + ky) * K + kx] *
                                        in[((size_t)ci * Hi + (oy * st + ky)) * Wi + (ox * st + kx)];
-                    out[((size_t)co * S.hout[l] + oy) * S.wout[l] + ox] = acc > 0.0 ? q(S, acc) : 0.0;
+                    const size_t o = ((size_t)co * S.hout[l] + oy) * S.wout[l] + ox;
+                    out[o] = relu_on(mask, S.act_off[l] + o, acc, l, rep) ? q(S, acc) : 0.0;
                 }
         in = out;
     }
@@ -157,7 +192,7 @@ void forward_sample(const Shapes& S, const double* th, const uint8_t* x, double*
     for (int j = 0; j < S.fc; ++j) {
         double acc = th[S.fcb_off + j];
         for (int i = 0; i < S.flat; ++i) acc += th[S.fcw_off + (size_t)j * S.flat + i] * in[i];
-        h[j] = acc > 0.0 ? acc : 0.0;
+        h[j] = relu_on(mask, S.act_off[S.n_conv] + j, acc, S.n_conv, rep) ? acc : 0.0;
     }
     for (int a = 0; a < S.A; ++a) {
         double acc = th[S.pib_off + a];
@@ -184,8 +219,9 @@ void softmax(const double* z, int A, double* p, double* logp) {
 
 // Backward pass of one sample: adds this sample's parameter gradient into g (size P).
 // dz[A] = dL/dlogits, dv = dL/dV for this sample.
+// mask (may be null): the ReLU decisions to use instead of the sign of the stored output.
 void backward_sample(const Shapes& S, const double* th, const uint8_t* x, const double* act,
-                     const double* dz, double dv, double* g) {
+                     const double* dz, double dv, double* g, const uint8_t* mask = nullptr) {
     const double* h = act + S.act_off[S.n_conv];
     std::vector<double> dh(S.fc, 0.0);
     for (int a = 0; a < S.A; ++a) {
@@ -205,7 +241,8 @@ void backward_sample(const Shapes& S, const double* th, const uint8_t* x, const 
     const double* last = act + S.act_off[L - 1];
     std::vector<double> dcur(S.flat, 0.0);
     for (int j = 0; j < S.fc; ++j) {
-        if (!(h[j] > 0.0)) continue;            // ReLU'(pre) = 1[pre > 0]; post > 0 iff pre > 0
+        // ReLU'(pre) = 1[pre > 0]; post > 0 iff pre > 0
+        if (!(mask ? mask[S.act_off[L] + j] != 0 : h[j] > 0.0)) continue;
         const double d = q(S, dh[j]);
         g[S.fcb_off + j] += d;
         for (int i = 0; i < S.flat; ++i) {
@@ -230,7 +267,7 @@ void backward_sample(const Shapes& S, const double* th, const uint8_t* x, const 
             for (int oy = 0; oy < S.hout[l]; ++oy)
                 for (int ox = 0; ox < S.wout[l]; ++ox) {
                     const size_t o = ((size_t)co * S.hout[l] + oy) * S.wout[l] + ox;
-                    if (!(out[o] > 0.0)) continue;
+                    if (!(mask ? mask[S.act_off[l] + o] != 0 : out[o] > 0.0)) continue;
                     const double d = q(S, dcur[o]);
                     g[S.b_off[l] + co] += d;
                     for (int ci = 0; ci < S.cin[l]; ++ci)
@@ -255,20 +292,38 @@ int n_threads() {
 }
 
 // Forward over N samples; acts may be null (then activations are discarded per sample).
+// masks (may be null): [N][act_per_sample] supplied ReLU decisions; rep (may be null) receives the
+// comparison with the oracle's own decisions, summed over the samples.
 void forward_batch(const Shapes& S, const double* th_master, const uint8_t* states, int N,
-                   double* acts, double* logits, double* values) {
+                   double* acts, double* logits, double* values,
+                   const uint8_t* masks = nullptr, OracleFlipReport* rep = nullptr) {
     const std::vector<double> used = used_params(S, th_master);
     const double* th = used.data();
     const size_t in_sz = (size_t)S.cin[0] * S.hin[0] * S.win[0];
+    FlipAcc total{};
 #pragma omp parallel
     {
         std::vector<double> local(acts ? 0 : S.act_per_sample);
+        FlipAcc mine{};
 #pragma omp for schedule(static)
         for (int n = 0; n < N; ++n) {
             double* a = acts ? acts + (size_t)n * S.act_per_sample : local.data();
-            forward_sample(S, th, states + (size_t)n * in_sz, a, logits + (size_t)n * S.A, values + n);
+            forward_sample(S, th, states + (size_t)n * in_sz, a, logits + (size_t)n * S.A, values + n,
+                           masks ? masks + (size_t)n * S.act_per_sample : nullptr, rep ? &mine : nullptr);
+        }
+#pragma omp critical
+        for (int l = 0; l < 5; ++l) {
+            total.units[l] += mine.units[l]; total.flips[l] += mine.flips[l]; total.sum_sq[l] += mine.sum_sq[l];
+            total.max_abs_pre[l] = std::max(total.max_abs_pre[l], mine.max_abs_pre[l]);
+            total.abs_max[l] = std::max(total.abs_max[l], mine.abs_max[l]);
         }
     }
+    if (rep)
+        for (int l = 0; l < 5; ++l) {
+            rep->units[l] = total.units[l]; rep->flips[l] = total.flips[l];
+            rep->max_abs_pre[l] = total.max_abs_pre[l]; rep->act_abs_max[l] = total.abs_max[l];
+            rep->act_rms[l] = total.units[l] ? std::sqrt(total.sum_sq[l] / (double)total.units[l]) : 0.0;
+        }
 }
 
 // Returns (Algorithm 1, bootstrap + backward recursion, with the done mask).
@@ -314,7 +369,7 @@ void loss_and_grads(const double* logits, const double* values, const double* R,
 
 // Gradient of the loss over B samples given dz/dv; deterministic reduction over per-thread buffers.
 void backward_batch(const Shapes& S, const double* th_master, const uint8_t* states, const double* acts,
-                    const double* dz, const double* dv, int B, double* g) {
+                    const double* dz, const double* dv, int B, double* g, const uint8_t* masks = nullptr) {
     const std::vector<double> used = used_params(S, th_master);
     const double* th = used.data();
     const size_t in_sz = (size_t)S.cin[0] * S.hin[0] * S.win[0];
@@ -325,7 +380,8 @@ void backward_batch(const Shapes& S, const double* th_master, const uint8_t* sta
         const int lo = (int)((long long)B * tix / nt), hi = (int)((long long)B * (tix + 1) / nt);
         for (int n = lo; n < hi; ++n)
             backward_sample(S, th, states + (size_t)n * in_sz, acts + (size_t)n * S.act_per_sample,
-                            dz + (size_t)n * S.A, dv[n], gl[tix].data());
+                            dz + (size_t)n * S.A, dv[n], gl[tix].data(),
+                            masks ? masks + (size_t)n * S.act_per_sample : nullptr);
     }
     for (size_t i = 0; i < S.P; ++i) {
         double s = 0.0;
@@ -466,23 +522,41 @@ void oracle_select_actions(const OracleNet* net, const float* params, const uint
 // actions/rewards/dones [T][n_e] time-major.  Optional double outputs (may be null):
 // grads_out[P] = gradient before clipping, logits_out[(T+1) n_e A], values_out[(T+1) n_e],
 // returns_out[T n_e].
+// masks (may be null): uint8 [(T+1) n_e][act_per_sample], ReLU decisions to use instead of the
+// oracle's own (conv outputs in NCHW order followed by the fc units, as in the activation record);
+// flips (may be null) reports how they differ from the oracle's own.
+void oracle_train_step_masked(const OracleNet* net, float* params, float* rms, const uint8_t* states,
+                              const int32_t* actions, const float* rewards, const uint8_t* dones,
+                              const OracleHParams* hp, int T, int n_e, const uint8_t* masks,
+                              OracleStats* stats, double* grads_out, double* logits_out,
+                              double* values_out, double* returns_out, OracleFlipReport* flips);
+
 void oracle_train_step(const OracleNet* net, float* params, float* rms, const uint8_t* states,
                        const int32_t* actions, const float* rewards, const uint8_t* dones,
                        const OracleHParams* hp, int T, int n_e, OracleStats* stats,
                        double* grads_out, double* logits_out, double* values_out, double* returns_out) {
+    oracle_train_step_masked(net, params, rms, states, actions, rewards, dones, hp, T, n_e, nullptr, stats,
+                             grads_out, logits_out, values_out, returns_out, nullptr);
+}
+
+void oracle_train_step_masked(const OracleNet* net, float* params, float* rms, const uint8_t* states,
+                              const int32_t* actions, const float* rewards, const uint8_t* dones,
+                              const OracleHParams* hp, int T, int n_e, const uint8_t* masks,
+                              OracleStats* stats, double* grads_out, double* logits_out,
+                              double* values_out, double* returns_out, OracleFlipReport* flips) {
     const Shapes S = make_shapes(*net);
     const int B = T * n_e, Bp = (T + 1) * n_e;
     std::vector<double> th(S.P), g2(S.P);
     for (size_t i = 0; i < S.P; ++i) { th[i] = params[i]; g2[i] = rms[i]; }
     std::vector<double> logits((size_t)Bp * S.A), values(Bp), acts((size_t)Bp * S.act_per_sample);
-    forward_batch(S, th.data(), states, Bp, acts.data(), logits.data(), values.data());
+    forward_batch(S, th.data(), states, Bp, acts.data(), logits.data(), values.data(), masks, flips);
     std::vector<double> R(B);
     returns_scan(rewards, dones, values.data() + B, hp->gamma, T, n_e, R.data());
     std::vector<double> dz((size_t)B * S.A), dv(B), g(S.P);
     double pl, ent, vl;
     loss_and_grads(logits.data(), values.data(), R.data(), nullptr, actions, B, S.A, hp->beta,
                    hp->value_coef, &pl, &ent, &vl, dz.data(), dv.data());
-    backward_batch(S, th.data(), states, acts.data(), dz.data(), dv.data(), B, g.data());
+    backward_batch(S, th.data(), states, acts.data(), dz.data(), dv.data(), B, g.data(), masks);
     if (grads_out) std::memcpy(grads_out, g.data(), S.P * sizeof(double));
     double norm = 0.0;
     const double scale = oracle_clip_f64(g.data(), S.P, hp->clip_norm, &norm);

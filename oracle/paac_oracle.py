@@ -40,6 +40,11 @@ class _HP(C.Structure):
                 ("gamma", "beta", "value_coef", "lr", "rms_alpha", "rms_eps", "clip_norm")]
 
 
+class _Flips(C.Structure):
+    _fields_ = [("units", C.c_int64 * 5), ("flips", C.c_int64 * 5), ("max_abs_pre", C.c_double * 5),
+                ("act_abs_max", C.c_double * 5), ("act_rms", C.c_double * 5)]
+
+
 class _Stats(C.Structure):
     _fields_ = [(n, C.c_double) for n in
                 ("policy_loss", "entropy", "value_loss", "total_loss", "grad_norm", "clip_scale")] + \
@@ -245,10 +250,14 @@ class TrainResult:
     values: np.ndarray      # float64 [(T+1) n_e]
     returns: np.ndarray     # float64 [T, n_e]
     stats: dict
+    flips: dict | None = None   # masked runs: per layer (conv 1.., fc) units, flips, max_abs_pre, act_abs_max, act_rms
 
 
-def train_step(net, params, rms, states, actions, rewards, dones, hp) -> TrainResult:
-    """One PAAC update.  hp: object with gamma, beta, value_coef, lr, rms_alpha, rms_eps, clip_norm."""
+def train_step(net, params, rms, states, actions, rewards, dones, hp, masks=None) -> TrainResult:
+    """One PAAC update.  hp: object with gamma, beta, value_coef, lr, rms_alpha, rms_eps, clip_norm.
+    masks (optional): uint8 [(T+1) n_e, act_per_sample] ReLU decisions taken elsewhere, used instead of
+    the oracle's own sign tests (conv outputs in NCHW order, then the fc units); the result then
+    carries `flips`, the comparison with the oracle's own decisions."""
     L = _load()
     params = np.array(params, dtype=np.float32, copy=True)
     rms = np.array(rms, dtype=np.float32, copy=True)
@@ -265,13 +274,26 @@ def train_step(net, params, rms, states, actions, rewards, dones, hp) -> TrainRe
     logits = np.empty(((T + 1) * n_e, net.n_actions), np.float64)
     values = np.empty((T + 1) * n_e, np.float64)
     returns = np.empty((T, n_e), np.float64)
-    L.oracle_train_step(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
-                        _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
-                        _p(dones, C.c_uint8), C.byref(h), T, n_e, C.byref(st),
-                        _p(grads, C.c_double), _p(logits, C.c_double), _p(values, C.c_double),
-                        _p(returns, C.c_double))
+    flips = None
+    if masks is None:
+        L.oracle_train_step(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
+                            _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
+                            _p(dones, C.c_uint8), C.byref(h), T, n_e, C.byref(st),
+                            _p(grads, C.c_double), _p(logits, C.c_double), _p(values, C.c_double),
+                            _p(returns, C.c_double))
+    else:
+        masks = _c(masks, np.uint8)
+        assert masks.shape == ((T + 1) * n_e, act_per_sample(net)), masks.shape
+        fr = _Flips()
+        L.oracle_train_step_masked(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
+                                   _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
+                                   _p(dones, C.c_uint8), C.byref(h), T, n_e, _p(masks, C.c_uint8), C.byref(st),
+                                   _p(grads, C.c_double), _p(logits, C.c_double), _p(values, C.c_double),
+                                   _p(returns, C.c_double), C.byref(fr))
+        nl = len(net.conv) + 1
+        flips = {k: np.array(list(getattr(fr, k))[:nl]) for k, _ in _Flips._fields_}
     stats = {n: getattr(st, n) for n, _ in _Stats._fields_}
-    return TrainResult(params, rms, grads, logits, values, returns, stats)
+    return TrainResult(params, rms, grads, logits, values, returns, stats, flips)
 
 
 def philox4x32_10(ctr, key):

@@ -468,3 +468,164 @@ def test_bf16_storage_mode_of_the_oracle(oracle):
     hh = F.relu(F.linear(x.flatten(1), q(P["fc.W"]), P["fc.b"]))
     lt = F.linear(hh, P["pi.W"], P["pi.b"]).numpy()
     assert np.abs(lq - lt).max() < 2e-3 * np.abs(lt).max()        # same roundings up to ties met from either side
+
+
+# ---------------------------------------------------------------- bf16 storage emulation, backward
+class _RoundGrad(torch.autograd.Function):
+    """Identity whose incoming gradient is rounded to bf16 (a gradient stored in bf16 between layers)."""
+
+    @staticmethod
+    def forward(ctx, x):
+        return x.view_as(x)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+class _RoundValue(torch.autograd.Function):
+    """Rounds the value to bf16 and passes the gradient through (a tensor stored in bf16; the master
+    copy it was rounded from receives the gradient unchanged)."""
+
+    @staticmethod
+    def forward(ctx, x):
+        return x.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g
+
+
+def _torch_bf16_storage_step(net, params, ro, hp, round_conv_grads=True, round_fc_grad=True):
+    """Section 4's loss on a network with bf16 storage points, by torch float64 autograd: conv and fc
+    weights as used and conv outputs rounded to bf16; the gradient entering every ReLU layer (conv
+    layers and the fc layer) rounded to bf16 after the ReLU mask; everything else in double."""
+    T, n_e = ro.actions.shape
+    B = T * n_e
+    tp = {k: torch.tensor(v.astype(np.float64), requires_grad=True) for k, v in _split(net, params).items()}
+    x = torch.tensor(ro.states.reshape(-1, net.in_c, net.in_h, net.in_w).astype(np.float64)) / 255.0
+    for i, (co, k, s) in enumerate(net.conv):
+        pre = F.conv2d(x, _RoundValue.apply(tp[f"conv{i + 1}.W"]), tp[f"conv{i + 1}.b"], stride=s)
+        if round_conv_grads:
+            pre = _RoundGrad.apply(pre)
+        x = _RoundValue.apply(F.relu(pre))
+    pre = F.linear(x.flatten(1), _RoundValue.apply(tp["fc.W"]), tp["fc.b"])
+    if round_fc_grad:
+        pre = _RoundGrad.apply(pre)
+    h = F.relu(pre)
+    logits = F.linear(h, tp["pi.W"], tp["pi.b"])
+    v = F.linear(h, tp["v.W"][None], tp["v.b"])[:, 0]
+    vd = v.detach().numpy()
+    R = np.zeros((T, n_e))
+    nxt = vd[B:].copy()
+    for t in range(T - 1, -1, -1):
+        nxt = ro.rewards[t].astype(np.float64) + hp.gamma * (1 - ro.dones[t]) * nxt
+        R[t] = nxt
+    Rt = torch.tensor(R.ravel())
+    lp = F.log_softmax(logits[:B], dim=1)
+    act = torch.tensor(ro.actions.ravel(), dtype=torch.long)
+    loss = (-((Rt - v[:B].detach()) * lp[torch.arange(B), act]).mean() + hp.beta * (lp.exp() * lp).sum(1).mean()
+            + hp.value_coef * ((Rt - v[:B]) ** 2).mean())
+    loss.backward()
+    return np.concatenate([tp[name].grad.numpy().ravel() for name, _ in net.param_shapes()]), logits.detach().numpy()
+
+
+@pytest.mark.parametrize("net,n_e,T", [(I.tiny_net(3), 4, 3), (I.nature_net(18), 2, 1)], ids=["tiny", "nature"])
+def test_bf16_storage_backward_of_the_oracle(oracle, net, n_e, T):
+    """The backward pass of the storage-emulating mode: the gradient handed from layer to layer is
+    rounded to bf16 where it enters a ReLU layer (after the mask), weights as used are the rounded
+    ones, their gradient goes to the master copy.  Rebuilt with torch float64 autograd and explicit
+    rounding hooks; moving or dropping a rounding point is detected."""
+    import dataclasses
+    qnet = dataclasses.replace(net, bf16=1)
+    ro = I.make_rollout(91, net, n_e, T, p_done=0.2)
+    params = I.make_params(91, net, bias_range=0.1)
+    hp = I.HParams(clip_norm=1e9)
+    res = oracle.train_step(qnet, params, I.make_rms(0, net), ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    want, logits = _torch_bf16_storage_step(net, params, ro, hp)
+    # forward first: only then is the backward comparison meaningful (no rounding tie met from the other side)
+    np.testing.assert_allclose(res.logits, logits, rtol=1e-9, atol=1e-12)
+    scale = np.abs(want).max()
+    np.testing.assert_allclose(res.grads, want, rtol=1e-8, atol=1e-11 * scale)
+    for name, sl in net.param_slices().items():
+        assert np.abs(want[sl]).max() > 0, name
+    # the rounding points matter at the 2^-9 level and the pin sees each of them
+    for kw in (dict(round_conv_grads=False), dict(round_fc_grad=False)):
+        other, _ = _torch_bf16_storage_step(net, params, ro, hp, **kw)
+        rel = np.linalg.norm(other - res.grads) / np.linalg.norm(res.grads)
+        assert 1e-5 < rel < 2e-2, (kw, rel)
+    plain = oracle.train_step(net, params, I.make_rms(0, net), ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    assert np.linalg.norm(plain.grads - res.grads) > 1e-5 * np.linalg.norm(res.grads)
+
+
+# ---------------------------------------------------------------- supplied ReLU decisions
+def _own_masks(oracle, net, params, states):
+    _, _, acts = oracle.forward_f64(net, params.astype(np.float64), states.reshape(-1, net.in_c, net.in_h, net.in_w),
+                                    want_acts=True)
+    return (acts > 0).astype(np.uint8)
+
+
+def test_supplied_relu_decisions_equal_to_own_change_nothing(oracle):
+    net = I.nips_net(6)
+    ro = I.make_rollout(13, net, 3, 2, p_done=0.3)
+    params = I.make_params(13, net, bias_range=0.1)
+    rms = I.make_rms(13, net, hi=0.02)
+    hp = I.HParams()
+    a = oracle.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    m = _own_masks(oracle, net, params, ro.states)
+    b = oracle.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp, masks=m)
+    for x, y in ((a.grads, b.grads), (a.logits, b.logits), (a.values, b.values), (a.returns, b.returns),
+                 (a.params, b.params), (a.rms, b.rms)):
+        np.testing.assert_array_equal(x, y)
+    assert a.stats == b.stats
+    assert (b.flips["flips"] == 0).all()
+    shapes = net.conv_out_shapes()
+    assert list(b.flips["units"]) == [9 * c * h * w for c, h, w in shapes] + [9 * net.fc]
+    assert (b.flips["act_rms"] > 0).all() and (b.flips["act_abs_max"] >= b.flips["act_rms"]).all()
+
+
+def test_supplied_relu_decisions_against_torch_autograd(oracle):
+    """Arbitrary (random) decisions: the network becomes x -> m * pre per layer, whose gradient torch's
+    float64 autograd gives directly; the flip report counts the units that differ from the sign test
+    and the largest pre-activation among them."""
+    net = I.tiny_net(3)
+    T, n_e = 2, 3
+    B, Bp = T * n_e, (T + 1) * n_e
+    ro = I.make_rollout(55, net, n_e, T, p_done=0.2)
+    params = I.make_params(55, net, bias_range=0.2)
+    hp = I.HParams(clip_norm=1e9)
+    g = np.random.default_rng(55)
+    masks = (g.random((Bp, oracle.act_per_sample(net))) < 0.6).astype(np.uint8)
+    res = oracle.train_step(net, params, I.make_rms(0, net), ro.states, ro.actions, ro.rewards, ro.dones, hp, masks=masks)
+
+    tp = {k: torch.tensor(v.astype(np.float64), requires_grad=True) for k, v in _split(net, params).items()}
+    x = torch.tensor(ro.states.reshape(-1, net.in_c, net.in_h, net.in_w).astype(np.float64)) / 255.0
+    off, n_flip, max_pre = 0, [], []
+    for i, (co, k, s) in enumerate(net.conv):
+        pre = F.conv2d(x, tp[f"conv{i + 1}.W"], tp[f"conv{i + 1}.b"], stride=s)
+        n = pre[0].numel()
+        m = torch.tensor(masks[:, off:off + n].reshape(pre.shape).astype(np.float64))
+        off += n
+        d = (m.numpy() > 0) != (pre.detach().numpy() > 0)
+        n_flip.append(int(d.sum()))
+        max_pre.append(float(np.abs(pre.detach().numpy())[d].max()))
+        x = m * pre
+    pre = F.linear(x.flatten(1), tp["fc.W"], tp["fc.b"])
+    m = torch.tensor(masks[:, off:].astype(np.float64))
+    d = (m.numpy() > 0) != (pre.detach().numpy() > 0)
+    n_flip.append(int(d.sum()))
+    max_pre.append(float(np.abs(pre.detach().numpy())[d].max()))
+    h = m * pre
+    logits = F.linear(h, tp["pi.W"], tp["pi.b"])
+    v = F.linear(h, tp["v.W"][None], tp["v.b"])[:, 0]
+    np.testing.assert_allclose(res.logits, logits.detach().numpy(), rtol=1e-10, atol=1e-12)
+    R = torch.tensor(res.returns.ravel())
+    lp = F.log_softmax(logits[:B], dim=1)
+    act = torch.tensor(ro.actions.ravel(), dtype=torch.long)
+    loss = (-((R - v[:B].detach()) * lp[torch.arange(B), act]).mean() + hp.beta * (lp.exp() * lp).sum(1).mean()
+            + hp.value_coef * ((R - v[:B]) ** 2).mean())
+    loss.backward()
+    want = np.concatenate([tp[name].grad.numpy().ravel() for name, _ in net.param_shapes()])
+    np.testing.assert_allclose(res.grads, want, rtol=1e-9, atol=1e-13)
+    assert list(res.flips["flips"]) == n_flip and min(n_flip) > 0
+    np.testing.assert_allclose(res.flips["max_abs_pre"], max_pre, rtol=1e-10)
