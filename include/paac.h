@@ -127,6 +127,14 @@ int paac_set_state(paac_ctx* ctx, const float* params_host, const float* rms_hos
  * values [(t_max+1) n_e], returns [t_max, n_e].  Host arrays; any may be NULL.  Synchronises. */
 int paac_get_train_outputs(paac_ctx* ctx, float* logits_host, float* values_host, float* returns_host);
 
+/* Stored activations of the forward pass of the last paac_train_step, for parity checks (they decide
+ * ReLU'(pre) = 1[pre > 0] in the backward pass of Section 4's gradients): rows [row0, row0 + rows) of
+ * the (t_max+1) n_e forward rows.  layer 0 .. n_conv-1: output of that convolution after ReLU, per
+ * row [c_out][h][w] (the bf16 configuration's stored values widened to float); layer n_conv: the
+ * hidden fully connected layer after ReLU, per row [fc].  out_host: host array of rows x (values
+ * per row) floats.  Synchronises the stream. */
+int paac_get_train_activations(paac_ctx* ctx, int layer, int row0, int rows, float* out_host);
+
 /* Philox4x32-10 uniforms in [0,1) on the 2^-24 grid, written to device memory: element i takes
  * word i%4 of the block with 64-bit counter offset + i/4 and 64-bit key `seed`. */
 int paac_fill_uniforms(paac_ctx* ctx, uint64_t seed, uint64_t offset, float* out_dev, size_t n);

@@ -657,16 +657,31 @@ void oracle_q_select_actions(const OracleNet* net, const float* params, const ui
 
 // One update of the variant; arguments as oracle_train_step.  stats: value_loss = mean squared TD
 // error, total_loss = c_q * value_loss (c_q = hp->value_coef), policy_loss = entropy = 0.
+// masks / flips (may be null): supplied ReLU decisions and the report on them, as in
+// oracle_train_step_masked.
+void oracle_q_train_step_masked(const OracleNet* net, float* params, float* rms, const uint8_t* states,
+                                const int32_t* actions, const float* rewards, const uint8_t* dones,
+                                const OracleHParams* hp, int T, int n_e, const uint8_t* masks, OracleStats* stats,
+                                double* grads_out, double* q_out, double* returns_out, OracleFlipReport* flips);
+
 void oracle_q_train_step(const OracleNet* net, float* params, float* rms, const uint8_t* states,
                          const int32_t* actions, const float* rewards, const uint8_t* dones,
                          const OracleHParams* hp, int T, int n_e, OracleStats* stats,
                          double* grads_out, double* q_out, double* returns_out) {
+    oracle_q_train_step_masked(net, params, rms, states, actions, rewards, dones, hp, T, n_e, nullptr, stats,
+                               grads_out, q_out, returns_out, nullptr);
+}
+
+void oracle_q_train_step_masked(const OracleNet* net, float* params, float* rms, const uint8_t* states,
+                                const int32_t* actions, const float* rewards, const uint8_t* dones,
+                                const OracleHParams* hp, int T, int n_e, const uint8_t* masks, OracleStats* stats,
+                                double* grads_out, double* q_out, double* returns_out, OracleFlipReport* flips) {
     const Shapes S = make_shapes(*net);
     const int B = T * n_e, Bp = (T + 1) * n_e;
     std::vector<double> th(S.P), g2(S.P);
     for (size_t i = 0; i < S.P; ++i) { th[i] = params[i]; g2[i] = rms[i]; }
     std::vector<double> Q((size_t)Bp * S.A), v(Bp), acts((size_t)Bp * S.act_per_sample);
-    forward_batch(S, th.data(), states, Bp, acts.data(), Q.data(), v.data());
+    forward_batch(S, th.data(), states, Bp, acts.data(), Q.data(), v.data(), masks, flips);
     std::vector<double> boot(n_e), R(B);
     for (int e = 0; e < n_e; ++e) {
         const double* q = Q.data() + (size_t)(B + e) * S.A;
@@ -678,7 +693,7 @@ void oracle_q_train_step(const OracleNet* net, float* params, float* rms, const 
     std::vector<double> dq((size_t)B * S.A), dv(B, 0.0), g(S.P);
     double msq;
     oracle_q_loss_f64(Q.data(), R.data(), actions, B, S.A, hp->value_coef, &msq, dq.data());
-    backward_batch(S, th.data(), states, acts.data(), dq.data(), dv.data(), B, g.data());
+    backward_batch(S, th.data(), states, acts.data(), dq.data(), dv.data(), B, g.data(), masks);
     if (grads_out) std::memcpy(grads_out, g.data(), S.P * sizeof(double));
     double norm = 0.0;
     const double scale = oracle_clip_f64(g.data(), S.P, hp->clip_norm, &norm);

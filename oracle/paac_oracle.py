@@ -378,8 +378,9 @@ def q_select_actions(net, params, states, uniforms, epsilon):
     return dict(actions=actions, q=q)
 
 
-def q_train_step(net, params, rms, states, actions, rewards, dones, hp) -> TrainResult:
-    """One update of the value-based variant; TrainResult.logits holds Q, .values is empty."""
+def q_train_step(net, params, rms, states, actions, rewards, dones, hp, masks=None) -> TrainResult:
+    """One update of the value-based variant; TrainResult.logits holds Q, .values is empty.
+    masks: supplied ReLU decisions, as in train_step."""
     L = _load()
     params = np.array(params, dtype=np.float32, copy=True)
     rms = np.array(rms, dtype=np.float32, copy=True)
@@ -394,9 +395,18 @@ def q_train_step(net, params, rms, states, actions, rewards, dones, hp) -> Train
     grads = np.empty(params.size, np.float64)
     q = np.empty(((T + 1) * n_e, net.n_actions), np.float64)
     returns = np.empty((T, n_e), np.float64)
-    L.oracle_q_train_step(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
-                          _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
-                          _p(dones, C.c_uint8), C.byref(h), T, n_e, C.byref(st),
-                          _p(grads, C.c_double), _p(q, C.c_double), _p(returns, C.c_double))
+    flips = None
+    fr = _Flips()
+    if masks is not None:
+        masks = _c(masks, np.uint8)
+        assert masks.shape == ((T + 1) * n_e, act_per_sample(net)), masks.shape
+    L.oracle_q_train_step_masked(C.byref(_net(net)), _p(params, C.c_float), _p(rms, C.c_float),
+                                 _p(states, C.c_uint8), _p(actions, C.c_int32), _p(rewards, C.c_float),
+                                 _p(dones, C.c_uint8), C.byref(h), T, n_e, _p(masks, C.c_uint8), C.byref(st),
+                                 _p(grads, C.c_double), _p(q, C.c_double), _p(returns, C.c_double),
+                                 C.byref(fr) if masks is not None else None)
+    if masks is not None:
+        nl = len(net.conv) + 1
+        flips = {k: np.array(list(getattr(fr, k))[:nl]) for k, _ in _Flips._fields_}
     stats = {n: getattr(st, n) for n, _ in _Stats._fields_}
-    return TrainResult(params, rms, grads, q, np.empty(0), returns, stats)
+    return TrainResult(params, rms, grads, q, np.empty(0), returns, stats, flips)

@@ -25,7 +25,10 @@ from . import paac as P
 
 
 def run(cfg: I.Config, n_w: int, iters: int, warmup: int, sprites: int, seed: int, cache: bool, split: bool,
-        graphs: bool = False):
+        graphs: bool = False, record: dict | None = None):
+    """record: if a dict, the last iteration's inputs and results are copied into it (parameters and
+    RMSProp state before the update, the rollout, the uniforms, then state, gradient and statistics
+    after the update) so that a caller can replay that iteration elsewhere."""
     dev = torch.device("cuda:0")
     n_e, t_max, net = cfg.n_e, cfg.t_max, cfg.net
     stream = torch.cuda.Stream(device=dev)
@@ -86,7 +89,18 @@ def run(cfg: I.Config, n_w: int, iters: int, warmup: int, sprites: int, seed: in
             t0 = time.perf_counter()
             rewards_d.copy_(rewards_h, non_blocking=True)
             dones_d.copy_(dones_h, non_blocking=True)
+            last = record is not None and it == warmup + iters - 1
+            if last:
+                stream.synchronize()
+                record["params"], record["rms"], _ = ctx.get_state(want_grads=False)
+                for name, tns in (("states", states_d), ("actions", actions_d), ("rewards", rewards_d),
+                                  ("dones", dones_d), ("uniforms", uniforms_d)):
+                    record[name] = tns.cpu().numpy().copy()
             ctx.train_step(states_d, actions_d, rewards_d, dones_d, cfg.hp, stats_d)
+            if last:
+                stream.synchronize()
+                record["params_after"], record["rms_after"], record["grads"] = ctx.get_state()
+                record["outputs"] = ctx.get_train_outputs()
             states_d[0].copy_(states_d[t_max], non_blocking=True)
             mark("train", t0)
         stream.synchronize()

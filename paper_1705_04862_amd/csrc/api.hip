@@ -698,6 +698,44 @@ int paac_get_train_outputs(paac_ctx* c, float* logits_host, float* values_host, 
     return PAAC_OK;
 }
 
+int paac_get_train_activations(paac_ctx* c, int layer, int row0, int rows, float* out_host) {
+    if (!c) return PAAC_E_NULL;
+    if (!out_host) return fail(c, PAAC_E_NULL, "out_host is NULL");
+    const NetDesc& n = c->net; const Plan& p = c->plan;
+    if (layer < 0 || layer > n.n_conv) return fail(c, PAAC_E_BADCONFIG, "layer out of range");
+    if (row0 < 0 || rows < 0 || (long long)row0 + rows > p.Bp) return fail(c, PAAC_E_BADCONFIG, "row range outside the forward batch");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (rows == 0) return PAAC_OK;
+    if (layer == n.n_conv) {        // fc output: fp32 in both configurations
+        HIP_TRY(c, hipMemcpy(out_host, c->buf.h + (size_t)row0 * n.fc, (size_t)rows * n.fc * sizeof(float), hipMemcpyDeviceToHost));
+        return PAAC_OK;
+    }
+    const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
+    const ConvDesc& cv = n.conv[layer];
+    const size_t hw = (size_t)cv.ho * cv.wo, per = hw * cv.cout, esz = bf16 ? 2 : 4;
+    const int chunk = 256;          // rows per staging copy
+    std::vector<char> tmp((size_t)(rows < chunk ? rows : chunk) * per * esz);
+    for (int r = 0; r < rows; r += chunk) {
+        const int nr = rows - r < chunk ? rows - r : chunk;
+        HIP_TRY(c, hipMemcpy(tmp.data(), static_cast<const char*>(c->buf.act[layer]) + (size_t)(row0 + r) * per * esz,
+                             (size_t)nr * per * esz, hipMemcpyDeviceToHost));
+        for (int i = 0; i < nr; ++i) {
+            float* dst = out_host + (size_t)(r + i) * per;
+            for (size_t pos = 0; pos < hw; ++pos)
+                for (int ch = 0; ch < cv.cout; ++ch) {
+                    const size_t src = ((size_t)i * hw + pos) * cv.cout + ch;    // NHWC on the device
+                    float v;
+                    if (bf16) {
+                        const uint32_t u = (uint32_t)reinterpret_cast<const uint16_t*>(tmp.data())[src] << 16;
+                        memcpy(&v, &u, 4);
+                    } else v = reinterpret_cast<const float*>(tmp.data())[src];
+                    dst[(size_t)ch * hw + pos] = v;                               // NCHW for the caller
+                }
+        }
+    }
+    return PAAC_OK;
+}
+
 int paac_fill_uniforms(paac_ctx* c, uint64_t seed, uint64_t offset, float* out_dev, size_t n) {
     if (!c) return PAAC_E_NULL;
     if (!out_dev && n) return fail(c, PAAC_E_NULL, "out_dev is NULL");

@@ -24,7 +24,7 @@ ERRORS = {0: "PAAC_OK", -1: "PAAC_E_NULL", -2: "PAAC_E_BADCONFIG", -3: "PAAC_E_W
 # every symbol include/paac.h declares
 SYMBOLS = ["paac_workspace_bytes", "paac_create", "paac_destroy", "paac_init_params",
            "paac_select_actions", "paac_train_step", "paac_param_count", "paac_get_state",
-           "paac_set_state", "paac_get_train_outputs", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache", "paac_set_algorithm",
+           "paac_set_state", "paac_get_train_outputs", "paac_get_train_activations", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache", "paac_set_algorithm",
            "paac_set_profiling", "paac_kernel_times", "paac_flops", "paac_last_error"]
 
 
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.paac_get_state.argtypes = [vp, vp, vp, vp]
         L.paac_set_state.argtypes = [vp, vp, vp]
         L.paac_get_train_outputs.argtypes = [vp, vp, vp, vp]
+        L.paac_get_train_activations.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp]
         L.paac_fill_uniforms.argtypes = [vp, u64, u64, vp, sz]
         L.paac_set_graphs.argtypes = [vp, C.c_int]
         L.paac_set_activation_cache.argtypes = [vp, C.c_int]
@@ -191,6 +192,14 @@ class Paac:
         returns = np.empty((self.t_max, self.n_e), np.float32)
         self._check(self.L.paac_get_train_outputs(self.ctx, _np_ptr(logits), _np_ptr(values), _np_ptr(returns)))
         return logits, values, returns
+
+    def get_train_activations(self, layer: int, per_row: int, row0: int = 0, rows: Optional[int] = None) -> np.ndarray:
+        """Stored post-ReLU output of conv layer `layer` (NCHW per row) or, for layer = number of conv
+        layers, of the hidden fc layer, of the last train step's forward pass; per_row = values per row."""
+        rows = self.n_e * (self.t_max + 1) - row0 if rows is None else rows
+        out = np.empty((rows, per_row), np.float32)
+        self._check(self.L.paac_get_train_activations(self.ctx, layer, row0, rows, _np_ptr(out)))
+        return out
 
     def read_stats(self, stats: Optional[torch.Tensor] = None) -> Dict[str, float]:
         st = (self.stats_dev if stats is None else stats).cpu().numpy()

@@ -1,11 +1,15 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 
 Tolerances (fp32 path): logits, values, probabilities, returns and losses within 1e-4 of the
-oracle relative to the tensor's largest magnitude; gradients, updated parameters and RMSProp
-state within 1e-3 relative L2 (whole vector and every tensor).  Sampled actions must be equal
-unless the uniform lies within 1e-5 of a CDF boundary.  Integer/bit work (Philox, parameter
-initialisation, state round trips) is compared bit for bit.
+oracle element by element (|got - want| <= 1e-4 max(|want|, 0.05 max|want|): relative to the
+element, with an absolute floor of a twentieth of the tensor's largest magnitude); gradients,
+updated parameters and RMSProp state within 1e-3 relative L2 (whole vector and every tensor).
+Sampled actions must be equal unless the uniform lies within 1e-5 of a CDF boundary.  Integer/bit
+work (Philox, parameter initialisation, state round trips) is compared bit for bit.
+bf16 path: 2e-2 everywhere (see check_train_bf16).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -29,8 +33,29 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
+FLOOR = 0.05       # absolute floor of the element-wise check, as a fraction of the tensor's largest magnitude
+
+
 def relmax(a, b):
+    """Largest element-wise error relative to max(|want|, FLOOR * max|want|)."""
+    b = np.asarray(b, np.float64)
+    den = np.maximum(np.abs(b), FLOOR * max(np.abs(b).max(), 1e-30))
+    return float((np.abs(np.asarray(a, np.float64) - b) / den).max())
+
+
+def relmax_tensor(a, b):
+    """Largest error relative to the tensor's largest magnitude (used where errors are absolute in
+    nature: sums of many rounded bf16 terms)."""
     return float(np.abs(np.asarray(a, np.float64) - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+def report(line):
+    """Measured figures go to the file PAAC_PARITY_REPORT names (if set) and to stdout."""
+    print(line, flush=True)
+    path = os.environ.get("PAAC_PARITY_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
 
 
 def rel_l2(a, b):
@@ -352,25 +377,57 @@ def test_profiling_mode_matches_and_reports(paac):
 
 
 # ------------------------------------------------------------------ bf16 MFMA path (precision = 1)
-# bf16 operands (8 significand bits) with fp32 accumulation: see check_train_bf16 for what is held to
-# 2e-2 and why the trunk gradients carry a wider bound.
+# bf16 operands (8 significand bits) with fp32 accumulation: everything within 2e-2 of the oracle.
 TOL_BF16 = 2e-2
+TOL_BF16_SAME_STORAGE = 2e-3     # forward against the oracle mode that rounds the same tensors to bf16
+TOL_BF16_SAME_STORAGE_GRAD = 5e-3   # gradients against that mode with shared ReLU decisions (measured: <= 2.8e-3 at 6 samples, 1e-4..1e-3 from 100 samples on)
 
 
-TOL_BF16_FLIP = 6e-2
+def hip_relu_masks(ctx, net, chunk=2048):
+    """The ReLU decisions the HIP path took in its last train step: stored activation > 0, as uint8
+    [(t_max+1) n_e, act_per_sample] in the oracle's order (conv outputs NCHW, then the fc units)."""
+    Bp = ctx.n_e * (ctx.t_max + 1)
+    per = [c * h * w for c, h, w in net.conv_out_shapes()] + [net.fc]
+    masks = np.empty((Bp, sum(per)), np.uint8)
+    off = 0
+    for layer, n in enumerate(per):
+        for r in range(0, Bp, chunk):
+            rows = min(chunk, Bp - r)
+            masks[r:r + rows, off:off + n] = ctx.get_train_activations(layer, n, r, rows) > 0
+        off += n
+    return masks
 
 
-def check_train_bf16(oracle, net, ctx, params, rms, ro, hp, label=""):
-    """Two references.
-    (a) The plain fp64 oracle: logits, values, returns and losses within 2e-2.
-    (b) The oracle with the same bf16 STORAGE points (conv/fc weights as used, conv activations and the
-    layer-to-layer gradients rounded to bf16; sums in double): forward within 2e-3.
-    Gradients: a ReLU unit whose pre-activation is within accumulation error of zero can take a
-    different side in fp32 accumulation (the kernel) and in double (the oracle); each such flip moves a
-    whole per-sample term, and on this synthetic data (per-sample gradients uncorrelated) a handful of
-    flips per step is worth 2-4 % in relative L2 whatever the batch size.  So: tensors that no mask
-    touches (both heads) within 2e-2; every tensor within 6e-2 relative L2 and with its median
-    element error within 2e-2 of the tensor's largest magnitude."""
+TENSOR_FLOOR = 0.05     # a tensor's error is measured against at least this fraction of the whole gradient's norm
+
+
+def tensor_errors(net, g, ref, floor=TENSOR_FLOOR):
+    """Per tensor: L2 error of g against ref relative to max(norm of the tensor, floor * norm of the
+    whole gradient).  The floor matters for tensors that are sums with cancellation (the value head's
+    bias gradient is sum_i (V_i - R_i) / B: forward errors inside the 2e-2 bar on V add up in it while
+    the sum itself can be small)."""
+    out = {}
+    whole = np.linalg.norm(ref)
+    for name, sl in net.param_slices().items():
+        out[name] = float(np.linalg.norm(g[sl].astype(np.float64) - ref[sl]) / max(np.linalg.norm(ref[sl]), floor * whole, 1e-30))
+    return out
+
+
+def check_train_bf16(oracle, net, ctx, params, rms, ro, hp, label="", unconditioned=True, plain_masked=True):
+    """One train step of the bf16 path against the oracle, everything within 2e-2.
+
+    ReLU'(pre) = 1[pre > 0] is a binary decision taken in floating point: a unit whose pre-activation
+    lies within rounding of zero can fall on either side, and one such flip moves a whole per-sample
+    term of the gradient (not a rounding-sized change).  Both sides therefore take that decision in
+    the same precision, the kernel's: the oracle is given the decisions the HIP path took (its stored
+    activations > 0) and everything else stays the oracle's own arithmetic.  Held to 2e-2, per tensor:
+      (a) forward outputs, returns and losses against the plain fp64 oracle (no masks involved);
+      (b) gradients, update and RMSProp state against the fp64 oracle with the shared decisions
+          (plain mode, and the mode that rounds the same tensors to bf16 as the kernels do);
+      (c) every decision that differs from the oracle's own belongs to a unit whose oracle
+          pre-activation is within the forward tolerance of zero (so it is a rounding flip, not an error).
+    The comparison without shared decisions is reported, and bounded by what the flips themselves are
+    worth in the oracle (own decisions vs supplied decisions, both computed on the CPU) plus 2e-2."""
     import dataclasses
     ctx.set_state(params, rms)
     ctx.train_step(dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones), hp)
@@ -378,43 +435,64 @@ def check_train_bf16(oracle, net, ctx, params, rms, ro, hp, label=""):
     st = ctx.read_stats()
     logits, values, returns = ctx.get_train_outputs()
     p2, r2, g = ctx.get_state()
-    want = oracle.train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
-    assert relmax(logits, want.logits) < TOL_BF16, label
-    assert relmax(values, want.values) < TOL_BF16, label
-    assert relmax(returns, want.returns) < TOL_BF16, label
+    masks = hip_relu_masks(ctx, net)
+    B = ro.actions.size
+    args = (ro.states, ro.actions, ro.rewards, ro.dones, hp)
+    qnet = dataclasses.replace(net, bf16=1)
+
+    # (a) forward and losses against the plain oracle
+    want = oracle.train_step(net, params, rms, *args)
+    assert relmax_tensor(logits, want.logits) < TOL_BF16, label
+    assert relmax_tensor(values, want.values) < TOL_BF16, label
+    assert relmax_tensor(returns, want.returns) < TOL_BF16, label
     scale = abs(want.stats["policy_loss"]) + hp.beta * abs(want.stats["entropy"]) + hp.value_coef * want.stats["value_loss"]
     for k in ("policy_loss", "entropy", "value_loss"):
         assert abs(st[k] - want.stats[k]) <= TOL_BF16 * max(abs(want.stats[k]), 0.05), (label, k, st[k], want.stats[k])
     assert abs(st["total_loss"] - want.stats["total_loss"]) <= TOL_BF16 * max(scale, 0.05), label
     assert st["nonfinite"] == 0
-    assert rel_l2(g, want.grads) < 0.2, (label, rel_l2(g, want.grads))
-    # (b) same storage precision on both sides
-    qnet = dataclasses.replace(net, bf16=1)
-    wq = oracle.train_step(qnet, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
-    assert relmax(logits, wq.logits) < 2e-3, label
-    assert relmax(values, wq.values) < 2e-3, label
-    for k in ("policy_loss", "entropy", "value_loss"):
-        assert abs(st[k] - wq.stats[k]) <= 2e-3 * max(abs(wq.stats[k]), 0.05), (label, k, st[k], wq.stats[k])
-    assert abs(st["grad_norm"] - wq.stats["grad_norm"]) <= TOL_BF16 * wq.stats["grad_norm"], label
-    assert rel_l2(g, wq.grads) < max(TOL_BF16_FLIP, 0.25 / np.sqrt(ro.actions.size)), (label, rel_l2(g, wq.grads))
-    for name, sl in net.param_slices().items():
-        ref = wq.grads[sl]
-        err = np.abs(g[sl].astype(np.float64) - ref)
-        # one flip weighs more in a tiny batch: 0.25/sqrt(B) per tensor below B = 17
-        tol = TOL_BF16 if name.startswith(("pi.", "v.")) else max(TOL_BF16_FLIP, 0.25 / np.sqrt(ro.actions.size))
-        assert np.linalg.norm(err) <= tol * max(np.linalg.norm(ref), 0.05 * np.linalg.norm(wq.grads)), (label, name)
-        assert np.median(err) <= TOL_BF16 * np.abs(ref).max(), (label, name)
-    assert rel_l2(p2 - params, wq.params.astype(np.float64) - params) < 2 * TOL_BF16_FLIP, label
-    assert rel_l2(r2, wq.rms.astype(np.float64)) < 2 * TOL_BF16_FLIP, label
+
+    # (b) shared ReLU decisions
+    refs = [("bf16-storage oracle", oracle.train_step(qnet, params, rms, *args, masks=masks), TOL_BF16_SAME_STORAGE, TOL_BF16_SAME_STORAGE_GRAD)]
+    if plain_masked:
+        refs.append(("plain oracle", oracle.train_step(net, params, rms, *args, masks=masks), TOL_BF16, TOL_BF16))
+    for mode, wm, tol_fwd, tol_g in refs:
+        assert relmax_tensor(logits, wm.logits) < tol_fwd, (label, mode)
+        assert relmax_tensor(values, wm.values) < tol_fwd, (label, mode)
+        errs = tensor_errors(net, g, wm.grads)
+        whole = rel_l2(g, wm.grads)
+        report(f"[bf16 {label}] B={B} vs {mode}, shared ReLU decisions: whole {whole:.2e}; " +
+               ", ".join(f"{k} {v:.2e}" for k, v in tensor_errors(net, g, wm.grads, 0.0).items()) + " (no floor)")
+        assert whole < tol_g, (label, mode, whole)
+        for name, e in errs.items():
+            assert e < tol_g, (label, mode, name, e)
+        assert abs(st["grad_norm"] - wm.stats["grad_norm"]) <= TOL_BF16 * wm.stats["grad_norm"], (label, mode)
+        assert rel_l2(p2 - params, wm.params.astype(np.float64) - params) < TOL_BF16, (label, mode)
+        assert rel_l2(r2, wm.rms.astype(np.float64)) < TOL_BF16, (label, mode)
+        # (c) flips are rounding flips
+        f = wm.flips
+        report(f"[bf16 {label}] vs {mode}: flipped units per layer {[int(x) for x in f['flips']]} of {[int(x) for x in f['units']]}; "
+               f"largest |pre| among them / largest |pre| of the layer "
+               f"{[float('%.2e' % (m / a)) for m, a in zip(f['max_abs_pre'], f['act_abs_max'])]}")
+        assert (f["max_abs_pre"] <= tol_fwd * f["act_abs_max"]).all(), (label, mode, f)
+        assert (f["flips"] <= 0.01 * f["units"]).all(), (label, mode, f)
     # master weights stay fp32: the update is not rounded to bf16
-    assert np.abs(p2 - params).max() > 0 and rel_l2(p2, wq.params.astype(np.float64)) < 1e-3
+    assert np.abs(p2 - params).max() > 0 and rel_l2(p2, refs[0][1].params.astype(np.float64)) < 1e-3
+
+    # the comparison without shared decisions: what the flips are worth, measured in the oracle itself
+    if unconditioned:
+        for (mode, wm, _, _), own in zip(refs, (oracle.train_step(qnet, params, rms, *args), want)):
+            budget = rel_l2(wm.grads, own.grads)
+            got = rel_l2(g, own.grads)
+            report(f"[bf16 {label}] vs {mode}, own decisions: {got:.2e} (the flips alone are worth {budget:.2e} in the oracle)")
+            assert got <= budget + TOL_BF16, (label, mode, got, budget)
+    return refs[0][1]
 
 
 def check_select_bf16(oracle, net, params, states, uniforms, got):
     acts, vals, probs = got
     want = oracle.select_actions(net, params, states, uniforms)
-    assert relmax(vals, want["values"].astype(np.float64)) < TOL_BF16
-    assert relmax(probs, want["probs"].astype(np.float64)) < TOL_BF16
+    assert relmax_tensor(vals, want["values"].astype(np.float64)) < TOL_BF16
+    assert relmax_tensor(probs, want["probs"].astype(np.float64)) < TOL_BF16
     np.testing.assert_allclose(probs.sum(1), 1.0, atol=1e-5)
     # the draw itself is exact given the kernel's own probabilities (same fp32 CDF rule)
     for e in range(states.shape[0]):
@@ -470,6 +548,20 @@ def test_bf16_large_batch_per_sample_weight_gradients(paac, oracle):
     check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16_128x16")
 
 
+def test_bf16_backward_at_4096_transitions(paac, oracle):
+    """4096 transitions (n_e=256, t_max=16, Nature net): the batch from which the fc data gradient runs
+    on 128x128 tiles with a ragged last column tile (3136 columns) and the tiled GEMMs walk over more
+    tiles than are resident at once -- the launch shapes of the largest configuration.  The whole step,
+    every tensor, against the oracle."""
+    net = I.nature_net(6)
+    n_e, t_max = 256, 16
+    ctx = make_ctx(paac, net, n_e, t_max, precision=1)
+    params = I.make_params(83, net, bias_range=0.05)
+    rms = I.make_rms(83, net, hi=0.01)
+    ro = I.make_rollout(83, net, n_e, t_max, 0.02)
+    check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16_256x16", unconditioned=False)
+
+
 def test_bf16_graph_replay_deterministic(paac):
     cfg = I.CONFIGS[3]
     net = cfg.net
@@ -489,11 +581,12 @@ def test_bf16_graph_replay_deterministic(paac):
         np.testing.assert_array_equal(x, y)
 
 
-def test_bf16_config4_full_size_sampled(paac, oracle):
+def test_bf16_config4_full_size(paac, oracle):
     """Configuration 4 (n_e=1024, t_max=20: 21504 forward rows, 20480 transitions) in the launch
-    configuration bench.py times.  The whole oracle step would take minutes, so: forward outputs and
-    returns are compared on sampled rows / environments the oracle computes one by one, and the
-    reduction, clip and update are checked through properties that hold at any size."""
+    configuration bench.py times.  Select: sampled environments against the oracle.  Train step: the
+    WHOLE oracle step once (bf16-storage mode, the ReLU decisions of the HIP path shared: about half
+    a minute on the host's cores), every tensor of the gradient, the update and the RMSProp state at
+    2e-2; forward outputs and returns additionally against the plain oracle on sampled rows."""
     import dataclasses
     cfg = I.CONFIGS[4]
     net, n_e, T = cfg.net, cfg.n_e, cfg.t_max
@@ -509,8 +602,8 @@ def test_bf16_config4_full_size_sampled(paac, oracle):
     es = np.sort(g.choice(n_e, 48, replace=False))
     wq = oracle.select_actions(qnet, params, ro.states[3][es], ro.uniforms[3][es])
     w0 = oracle.select_actions(net, params, ro.states[3][es], ro.uniforms[3][es])
-    assert relmax(vals[es], wq["values"].astype(np.float64)) < 2e-3 and relmax(probs[es], wq["probs"].astype(np.float64)) < 2e-3
-    assert relmax(vals[es], w0["values"].astype(np.float64)) < TOL_BF16 and relmax(probs[es], w0["probs"].astype(np.float64)) < TOL_BF16
+    assert relmax_tensor(vals[es], wq["values"].astype(np.float64)) < 2e-3 and relmax_tensor(probs[es], wq["probs"].astype(np.float64)) < 2e-3
+    assert relmax_tensor(vals[es], w0["values"].astype(np.float64)) < TOL_BF16 and relmax_tensor(probs[es], w0["probs"].astype(np.float64)) < TOL_BF16
     check_select_bf16(oracle, net, params, ro.states[3][es], ro.uniforms[3][es], (acts[es], vals[es], probs[es]))
     assert ((acts >= 0) & (acts < net.n_actions)).all()
     # train step at full size
@@ -519,33 +612,40 @@ def test_bf16_config4_full_size_sampled(paac, oracle):
     st = ctx.read_stats()
     logits, values, returns = ctx.get_train_outputs()
     p2, r2, grads = ctx.get_state()
+    masks = hip_relu_masks(ctx, net)
+    report(f"[bf16 {cfg.name}] oracle step over {T * n_e} transitions on {oracle.threads()} threads ...")
+    wm = oracle.train_step(qnet, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp, masks=masks)
+    del masks
+    assert relmax_tensor(logits, wm.logits) < TOL_BF16_SAME_STORAGE and relmax_tensor(values, wm.values) < TOL_BF16_SAME_STORAGE
+    assert ro.dones.any() and relmax_tensor(returns, wm.returns) < TOL_BF16_SAME_STORAGE
+    for k in ("policy_loss", "entropy", "value_loss"):
+        assert abs(st[k] - wm.stats[k]) <= TOL_BF16_SAME_STORAGE * max(abs(wm.stats[k]), 0.05), (k, st[k], wm.stats[k])
+    errs = tensor_errors(net, grads, wm.grads)
+    whole = rel_l2(grads, wm.grads)
+    report(f"[bf16 {cfg.name}] B={T * n_e} vs bf16-storage oracle, shared ReLU decisions: whole {whole:.2e}; " +
+           ", ".join(f"{k} {v:.2e}" for k, v in tensor_errors(net, grads, wm.grads, 0.0).items()) + " (no floor)")
+    f = wm.flips
+    report(f"[bf16 {cfg.name}] flipped units per layer {[int(x) for x in f['flips']]} of {[int(x) for x in f['units']]}; largest |pre| among them / "
+           f"largest |pre| of the layer {[float('%.2e' % (m / a)) for m, a in zip(f['max_abs_pre'], f['act_abs_max'])]}")
+    assert whole < TOL_BF16_SAME_STORAGE_GRAD
+    for name, e in errs.items():
+        assert e < TOL_BF16_SAME_STORAGE_GRAD, (name, e)
+    assert (f["max_abs_pre"] <= TOL_BF16_SAME_STORAGE * f["act_abs_max"]).all() and (f["flips"] <= 0.01 * f["units"]).all(), f
+    assert abs(st["grad_norm"] - wm.stats["grad_norm"]) <= TOL_BF16 * wm.stats["grad_norm"]
+    assert abs(st["clip_scale"] - wm.stats["clip_scale"]) <= TOL_BF16 * wm.stats["clip_scale"]
+    assert rel_l2(p2 - params, wm.params.astype(np.float64) - params) < TOL_BF16
+    assert rel_l2(r2, wm.rms.astype(np.float64)) < TOL_BF16
+    assert st["nonfinite"] == 0
+    # forward outputs and returns against the plain oracle, on rows it computes one by one
     flat_states = ro.states.reshape(-1, 4, 84, 84)
     rows = np.sort(g.choice((T + 1) * n_e, 64, replace=False))
-    lq, vq, _ = oracle.forward_f64(qnet, params.astype(np.float64), flat_states[rows])
     l0, v0, _ = oracle.forward_f64(net, params.astype(np.float64), flat_states[rows])
-    assert relmax(logits[rows], lq) < 2e-3 and relmax(values[rows], vq) < 2e-3
-    assert relmax(logits[rows], l0) < TOL_BF16 and relmax(values[rows], v0) < TOL_BF16
-    # returns of 32 sampled environments: bootstrap and V from the oracle, scan by the oracle
+    assert relmax_tensor(logits[rows], l0) < TOL_BF16 and relmax_tensor(values[rows], v0) < TOL_BF16
     envs = np.sort(g.choice(n_e, 32, replace=False))
     _, vboot, _ = oracle.forward_f64(net, params.astype(np.float64), ro.states[T][envs])
     R = oracle.returns_f64(ro.rewards[:, envs], ro.dones[:, envs], vboot, cfg.hp.gamma)
     assert ro.dones[:, envs].any()
     assert np.abs(returns[:, envs] - R).max() < TOL_BF16 * max(np.abs(R).max(), 1.0)
-    # properties of the reduction, the clip and the update at full size
-    assert st["nonfinite"] == 0 and np.isfinite(grads).all()
-    n = np.linalg.norm(grads.astype(np.float64))
-    assert abs(st["grad_norm"] - n) < 1e-4 * n
-    scale = min(1.0, cfg.hp.clip_norm / n)
-    assert abs(st["clip_scale"] - scale) < 1e-4
-    gc = grads.astype(np.float64) * scale
-    g2 = cfg.hp.rms_alpha * rms.astype(np.float64) + (1 - cfg.hp.rms_alpha) * gc * gc
-    th = params.astype(np.float64) - cfg.hp.lr * gc / np.sqrt(g2 + cfg.hp.rms_eps)
-    assert rel_l2(r2, g2) < 1e-5 and rel_l2(p2 - params, th - params) < 1e-4
-    assert abs(st["total_loss"] - (st["policy_loss"] - cfg.hp.beta * st["entropy"] + cfg.hp.value_coef * st["value_loss"])) < 1e-5
-    assert 0 < st["entropy"] <= np.log(net.n_actions) + 1e-5
-    # every tensor received a gradient
-    for name, sl in net.param_slices().items():
-        assert np.abs(grads[sl]).max() > 0, name
 
 
 @pytest.mark.parametrize("n_e", [16, 64, 128, 256])
@@ -579,8 +679,8 @@ def test_heads_kernels_agree_across_the_batch_threshold(paac, oracle):
     assert np.array_equal(got_small[0], got_big[0][:40])
     # the conv/fc GEMMs pick other tiles and k-splits at the other batch size, so values agree to
     # rounding, not to the bit
-    assert relmax(got_small[1], got_big[1][:40].astype(np.float64)) < 1e-5
-    assert relmax(got_small[2], got_big[2][:40].astype(np.float64)) < 1e-5
+    assert relmax_tensor(got_small[1], got_big[1][:40].astype(np.float64)) < 1e-5
+    assert relmax_tensor(got_small[2], got_big[2][:40].astype(np.float64)) < 1e-5
 
 
 @pytest.mark.parametrize("precision", [0, 1], ids=["fp32", "bf16"])
@@ -612,7 +712,9 @@ def test_rollout_activation_cache(paac, oracle, precision):
 
     ctx = make_ctx(paac, net, n_e, t_max, precision=precision)
     ctx.set_activation_cache(True)
-    tol_g, tol_o = (1e-5, 1e-5) if precision == 0 else (TOL_BF16_FLIP, 5e-3)
+    # bf16: other tiles at the smaller batch move sums by fp32 rounding, which can move a stored bf16
+    # value by one step and a ReLU decision with it: HIP against HIP is held to the bf16 bar only
+    tol_g, tol_o = (1e-5, 1e-5) if precision == 0 else (TOL_BF16, 5e-3)
     for n_select in (t_max, t_max - 1, t_max + 2, t_max):      # cached, two fallbacks, cached again
         ctx.set_state(params, rms)
         rollout(ctx, n_select)
@@ -620,7 +722,7 @@ def test_rollout_activation_cache(paac, oracle, precision):
         assert rel_l2(g, g_ref) < tol_g, n_select
         assert rel_l2(p2 - params, p_ref - params) < max(tol_g, 1e-4), n_select
         for a, b in zip(out, out_ref):
-            assert relmax(a, b.astype(np.float64)) < tol_o, n_select
+            assert relmax_tensor(a, b.astype(np.float64)) < tol_o, n_select
         if n_select != t_max and precision == 0:
             assert np.array_equal(g, g_ref)                     # the fallback is the uncached path, bit for bit
     # against the oracle, cached
@@ -634,6 +736,18 @@ def test_rollout_activation_cache(paac, oracle, precision):
         assert rel_l2(g, want.grads) < TOL_L2 and rel_l2(p2, want.params) < TOL_L2
         lg, vl, rt = ctx.get_train_outputs()
         assert relmax(lg, want.logits) < TOL_VAL and relmax(vl, want.values) < TOL_VAL and relmax(rt, want.returns) < TOL_VAL
+    else:
+        # the cached bf16 step against the oracle (train_step inside the check consumes the cache)
+        class Cached:
+            n_e, t_max = ctx.n_e, ctx.t_max
+
+            def set_state(self, p, r):
+                ctx.set_state(p, r)
+                rollout(ctx, t_max)
+
+            def __getattr__(self, name):
+                return getattr(ctx, name)
+        check_train_bf16(oracle, net, Cached(), params, rms, ro, hp, "bf16_cached_6x4")
 
 
 @pytest.mark.gpu
@@ -643,13 +757,32 @@ def test_actor_loop_runs_algorithm_1_with_the_worker_pool():
     activation cache beyond rounding."""
     from paper_1705_04862_amd import actor_loop as AL
     cfg = I.CONFIGS[0]
-    _, _, s1 = AL.run(cfg, 1, 6, 0, 6, 5, False, False)
+    rec = {}
+    _, _, s1 = AL.run(cfg, 1, 6, 0, 6, 5, False, False, record=rec)
     _, _, s4 = AL.run(cfg, 4, 6, 0, 6, 5, False, True)
     _, _, sc = AL.run(cfg, 2, 6, 0, 6, 5, True, False)
     assert s1["nonfinite"] == 0 and np.isfinite(s1["total_loss"]) and s1["grad_norm"] > 0
     assert s1 == s4
     for k in ("policy_loss", "entropy", "value_loss", "grad_norm"):
         assert abs(s1[k] - sc[k]) <= 1e-4 * max(1.0, abs(s1[k])), (k, s1[k], sc[k])
+    # the last iteration of the loop, replayed through the oracle: the actions the loop sampled from
+    # the states the workers produced, then the update on that rollout
+    from oracle import paac_oracle as O
+    net = cfg.net
+    assert rec["dones"].shape == (cfg.t_max, cfg.n_e) and rec["states"][1:].any()
+    for t in range(cfg.t_max):
+        sel = O.select_actions(net, rec["params"], rec["states"][t], rec["uniforms"][t])
+        cdf = np.cumsum(sel["probs"].astype(np.float64), axis=1)
+        for e in range(cfg.n_e):
+            assert rec["actions"][t, e] == sel["actions"][e] or np.abs(cdf[e] - float(rec["uniforms"][t, e])).min() < 1e-5
+    want = O.train_step(net, rec["params"], rec["rms"], rec["states"], rec["actions"], rec["rewards"], rec["dones"], cfg.hp)
+    lg, vl, rt = rec["outputs"]
+    assert relmax(lg, want.logits) < TOL_VAL and relmax(vl, want.values) < TOL_VAL and relmax(rt, want.returns) < TOL_VAL
+    for k in ("policy_loss", "entropy", "value_loss", "total_loss", "grad_norm", "clip_scale"):
+        assert abs(s1[k] - want.stats[k]) <= TOL_VAL * max(abs(want.stats[k]), 1e-3) + 1e-7, (k, s1[k], want.stats[k])
+    assert rel_l2(rec["grads"], want.grads) < TOL_L2
+    assert rel_l2(rec["params_after"], want.params.astype(np.float64)) < TOL_L2
+    assert rel_l2(rec["rms_after"], want.rms.astype(np.float64)) < 2 * TOL_L2
 
 
 @pytest.mark.parametrize("ci", [1, 2])
@@ -669,6 +802,6 @@ def test_fp32_forward_error_is_at_rounding_level(paac, oracle, ci):
     torch.cuda.synchronize()
     logits, values, returns = ctx.get_train_outputs()
     want = oracle.train_step(cfg.net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, cfg.hp)
-    assert relmax(logits, want.logits) < 5e-6
-    assert relmax(values, want.values) < 5e-6
-    assert relmax(returns, want.returns) < 5e-6
+    assert relmax_tensor(logits, want.logits) < 5e-6
+    assert relmax_tensor(values, want.values) < 5e-6
+    assert relmax_tensor(returns, want.returns) < 5e-6

@@ -11,7 +11,8 @@ import pytest
 import torch
 
 from paper_1705_04862_amd import inputs as I
-from test_gpu_parity import TOL_BF16, TOL_BF16_FLIP, TOL_L2, TOL_VAL, dev, make_ctx, rel_l2, relmax, run_select
+from test_gpu_parity import (TOL_BF16, TOL_L2, TOL_VAL, dev, hip_relu_masks, make_ctx, rel_l2, relmax, relmax_tensor,
+                             run_select, tensor_errors)
 
 pytestmark = pytest.mark.gpu
 
@@ -135,14 +136,20 @@ def test_q_variant_bf16(paac, oracle):
     st = ctx.read_stats()
     q, _, returns = ctx.get_train_outputs()
     p2, r2, g = ctx.get_state()
+    # gradients with the ReLU decisions of the HIP path shared (the decision 1[pre > 0] taken in the
+    # kernel's precision on both sides), every tensor at the bf16 bar
+    masks = hip_relu_masks(ctx, net)
     want = oracle.q_train_step(net, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
-    wq = oracle.q_train_step(qnet, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp)
-    assert relmax(q, want.logits) < TOL_BF16 and relmax(returns, want.returns) < TOL_BF16
+    wq = oracle.q_train_step(qnet, params, rms, ro.states, ro.actions, ro.rewards, ro.dones, hp, masks=masks)
+    assert relmax_tensor(q, want.logits) < TOL_BF16 and relmax_tensor(returns, want.returns) < TOL_BF16
     assert abs(st["value_loss"] - want.stats["value_loss"]) <= TOL_BF16 * max(want.stats["value_loss"], 0.05)
-    assert relmax(q, wq.logits) < 2e-3
-    bound = max(TOL_BF16_FLIP, 0.25 / np.sqrt(ro.actions.size))
-    assert rel_l2(g, wq.grads) < bound, rel_l2(g, wq.grads)
+    assert relmax_tensor(q, wq.logits) < 2e-3
+    assert rel_l2(g, wq.grads) < TOL_BF16, rel_l2(g, wq.grads)
     sl = net.param_slices()
-    assert rel_l2(g[sl["pi.W"]], wq.grads[sl["pi.W"]]) < TOL_BF16
-    assert not g[sl["v.W"]].any()
-    assert rel_l2(p2 - params, wq.params.astype(np.float64) - params) < 2 * bound
+    for name, e in tensor_errors(net, g, wq.grads).items():
+        if name.startswith("v."):
+            continue
+        assert e < TOL_BF16, (name, e)
+    assert not g[sl["v.W"]].any() and not g[sl["v.b"]].any()
+    assert (wq.flips["max_abs_pre"] <= 2e-3 * wq.flips["act_abs_max"]).all(), wq.flips
+    assert rel_l2(p2 - params, wq.params.astype(np.float64) - params) < TOL_BF16
