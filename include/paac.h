@@ -95,6 +95,23 @@ int paac_init_params(paac_ctx* ctx, uint64_t seed);
 int paac_select_actions(paac_ctx* ctx, const uint8_t* states_dev, const float* uniforms_dev,
                         int32_t* actions_dev, float* values_dev, float* probs_dev);
 
+/* paac_select_actions for callers that must not allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results,
+ * but the buffers a select call writes besides its outputs (the convolution outputs of the n_e states
+ * and the fully connected layer's partial sums) live in a static device array of
+ * PAAC_NOALLOC_SCRATCH_BYTES inside the library instead of the caller's workspace, the kernels are
+ * launched one by one on the context's stream (no graph is built), and the call makes no hipMalloc,
+ * hipFree or other allocating call.  Parameters are still read from the context's workspace.
+ * A configuration whose select call needs more scratch than that (the Nature network in fp32 beyond
+ * n_e of about 80) is rejected with PAAC_E_WORKSPACE and a message naming both sizes.
+ * Each GPU holds one such array until the process ends, and every context on that GPU shares it: the
+ * array keeps the last call's contents (nothing in it has to start at zero: every byte a call reads
+ * it has written before), and two such calls that overlap in time on one GPU (different streams or
+ * contexts) race.  The call neither reads nor advances the rollout activation cache. */
+#define PAAC_NOALLOC_SCRATCH_BYTES (8u << 20)
+int paac_select_actions_noalloc(paac_ctx* ctx, const uint8_t* states_dev, const float* uniforms_dev,
+                                int32_t* actions_dev, float* values_dev, float* probs_dev);
+
 /* Algorithm 1, from the bootstrap to the parameter update, over one rollout (Section 4: the two
  * batch gradients; clipping and RMSProp per the Experiments section):
  *   R_{T+1} = V(s_{T+1});  R_t = r_t + gamma (1 - d_t) R_{t+1};  adv = R_t - V(s_t) (a constant);

@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -13,9 +14,32 @@ using namespace paac;
 
 namespace paac { thread_local ProfEvents tl_prof = {nullptr, nullptr}; }
 
+// Scratch of paac_select_actions_noalloc: one copy per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; the address kernels use is looked up once per
+// device (scratch_for_device) and passed to them as an argument.
+static __device__ __align__(256) unsigned char g_noalloc_scratch[PAAC_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of g_noalloc_scratch on `device`, which must be the current device.
+hipError_t scratch_for_device(int device, void** out) {
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 constexpr int kHpSlots = 16;
 constexpr int kMaxGraphs = 64;
 
@@ -192,6 +216,24 @@ Buffers carve(const NetDesc& n, const Arena& a, const Plan& p, bool bf16, char* 
     return b;
 }
 
+// The buffers a select call writes besides its outputs (conv outputs of n_e states, fc partial sums),
+// carved from `base` the way carve() does; base = nullptr only computes the size.
+struct SelectScratch { void* act[3]; float* fc_partial; size_t bytes; };
+SelectScratch carve_select_scratch(const NetDesc& n, const Plan& p, bool bf16, char* base) {
+    SelectScratch sc{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void* ptr = base ? base + off : nullptr;
+        off += align_up(bytes);
+        return ptr;
+    };
+    for (int l = 0; l < n.n_conv; ++l)
+        sc.act[l] = take((size_t)n.conv[l].ho * n.conv[l].wo * n.conv[l].cout * p.n_e * (bf16 ? 2 : 4));
+    sc.fc_partial = static_cast<float*>(take((size_t)p.sel_fc.n * p.n_e * n.fc * sizeof(float)));
+    sc.bytes = off;
+    return sc;
+}
+
 enum KernelId {
     K_SEL_CONV1, K_SEL_CONV2, K_SEL_CONV3, K_SEL_FC, K_SEL_HEADS,
     K_TRN_CONV1, K_TRN_CONV2, K_TRN_CONV3, K_TRN_FC, K_TRN_HEADS, K_TRN_LOSS, K_TRN_HEADS_BWD,
@@ -228,6 +270,7 @@ struct paac_ctx {
     hipStream_t stream;       // caller's stream: all work is enqueued here
     hipStream_t cap_stream;   // private stream used only for graph capture
     int device;
+    void* noalloc_scratch;    // this device's copy of the static scratch array
     bool have_params;
     bool cache_on;            // rollout activation cache enabled
     int sel_count;            // select calls since the last train step / parameter load
@@ -316,8 +359,8 @@ constexpr int kExactMinSamples = 96;
 
 // Forward trunk shared by select and train: convs, fc partial sums.
 // `row0`: first row of the activation buffers this launch writes (0, or the slab of a cached rollout).
-void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0, int row0) {
-    const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf;
+void enqueue_trunk(paac_ctx* c, const Buffers& b, Launcher& L, const uint8_t* states, int ns, Split fc_split, int id0, int row0) {
+    const NetDesc& n = c->net; const Arena& a = c->arena;
     const void* in = states;
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
     auto act_at = [&](int l) {
@@ -346,12 +389,13 @@ void enqueue_trunk(paac_ctx* c, Launcher& L, const uint8_t* states, int ns, Spli
 }
 
 // `slab` >= 0: keep activations, logits and values as rollout slab `slab` of the training buffers.
-hipError_t enqueue_select(paac_ctx* c, hipStream_t s, bool prof, const SelectArgs& x, int slab, int* err_id) {
+// `b`: the context's buffers, or a copy whose activation / partial-sum pointers lead elsewhere.
+hipError_t enqueue_select(paac_ctx* c, const Buffers& b, hipStream_t s, bool prof, const SelectArgs& x, int slab, int* err_id) {
     Launcher L{c, s, prof, hipSuccess, -1};
-    const NetDesc& n = c->net; const Arena& a = c->arena; const Buffers& b = c->buf; const Plan& p = c->plan;
+    const NetDesc& n = c->net; const Arena& a = c->arena; const Plan& p = c->plan;
     if (prof) delay_us(s, 250);
     const int row0 = slab >= 0 ? slab * p.n_e : 0;
-    enqueue_trunk(c, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1, row0);
+    enqueue_trunk(c, b, L, x.states, p.n_e, p.sel_fc, K_SEL_CONV1, row0);
     HeadsArgs h{};
     h.fc_partial = b.fc_partial; h.n_split = p.sel_fc.n; h.split_stride = (size_t)p.n_e * n.fc;
     h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
@@ -377,7 +421,7 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     const int f_row0 = cached ? p.B : 0, f_rows = cached ? p.n_e : p.Bp;      // rows the forward pass still has to compute
     const Split f_split = cached ? p.sel_fc : p.trn_fc;
     const size_t sample_bytes = (size_t)c->cfg.in_c * c->cfg.in_h * c->cfg.in_w;
-    enqueue_trunk(c, L, x.states + (size_t)f_row0 * sample_bytes, f_rows, f_split, K_TRN_CONV1, f_row0);
+    enqueue_trunk(c, b, L, x.states + (size_t)f_row0 * sample_bytes, f_rows, f_split, K_TRN_CONV1, f_row0);
     HeadsArgs h{};
     h.fc_partial = b.fc_partial; h.n_split = f_split.n; h.split_stride = (size_t)f_rows * F;
     h.fc_b = b.theta + a.fc_b; h.pi_w = b.theta + a.pi_w; h.pi_b = b.theta + a.pi_b;
@@ -556,6 +600,7 @@ int paac_create(const paac_config* cfg, void* workspace_dev, size_t workspace_by
     memset(c->hp_ev_used, 0, sizeof(c->hp_ev_used));
     memset(c->k_ms, 0, sizeof(c->k_ms)); memset(c->k_calls, 0, sizeof(c->k_calls));
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = scratch_for_device(c->device, &c->noalloc_scratch);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->hp_pinned), kHpSlots * HP_COUNT * sizeof(float), hipHostMallocDefault);
     for (int i = 0; i < kHpSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->hp_ev[i], hipEventDisableTiming);
@@ -659,9 +704,37 @@ int paac_select_actions(paac_ctx* c, const uint8_t* states_dev, const float* uni
     key.kind = 0; key.p[0] = states_dev; key.p[1] = uniforms_dev; key.p[2] = actions_dev; key.p[3] = values_dev; key.p[4] = probs_dev;
     key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(slab + 1));
     key.algorithm = c->algorithm; key.epsilon = c->epsilon;
-    const int r = run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, s, prof, x, slab, id); });
+    const int r = run_or_replay(c, key, [&](hipStream_t s, bool prof, int* id) { return enqueue_select(c, c->buf, s, prof, x, slab, id); });
     if (r == PAAC_OK && c->cache_on && c->sel_count <= c->plan.T) ++c->sel_count;
     return r;
+}
+
+int paac_select_actions_noalloc(paac_ctx* c, const uint8_t* states_dev, const float* uniforms_dev, int32_t* actions_dev,
+                                float* values_dev, float* probs_dev) {
+    if (!c) return PAAC_E_NULL;
+    if (!states_dev || !uniforms_dev || !actions_dev) return fail(c, PAAC_E_NULL, "states, uniforms and actions are required");
+    if (!c->have_params) return fail(c, PAAC_E_STATE, "no parameters: call paac_init_params or paac_set_state first");
+    if (reinterpret_cast<uintptr_t>(states_dev) % 4 != 0) return fail(c, PAAC_E_BADCONFIG, "states_dev must be 4-byte aligned");
+    const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
+    const size_t need = carve_select_scratch(c->net, c->plan, bf16, nullptr).bytes;
+    if (need > (size_t)PAAC_NOALLOC_SCRATCH_BYTES) {
+        char msg[160];
+        snprintf(msg, sizeof(msg), "n_e = %d needs %zu bytes of scratch, the static scratch holds %zu: use paac_select_actions",
+                 c->cfg.n_e, need, (size_t)PAAC_NOALLOC_SCRATCH_BYTES);
+        return fail(c, PAAC_E_WORKSPACE, msg);
+    }
+    if (!c->noalloc_scratch) return fail(c, PAAC_E_HIP, "static scratch address unknown on this device");
+    DeviceGuard dg(c->device);
+    const SelectScratch sc = carve_select_scratch(c->net, c->plan, bf16, static_cast<char*>(c->noalloc_scratch));
+    Buffers b = c->buf;                      // parameters and their mirrors stay in the workspace
+    for (int l = 0; l < c->net.n_conv; ++l) b.act[l] = sc.act[l];
+    b.fc_partial = sc.fc_partial;
+    const SelectArgs x{states_dev, uniforms_dev, actions_dev, values_dev, probs_dev};
+    int err_id = -1;
+    const hipError_t e = enqueue_select(c, b, c->stream, false, x, -1, &err_id);
+    if (e != hipSuccess)
+        return fail(c, PAAC_E_HIP, std::string("launch of ") + (err_id >= 0 ? kKernelNames[err_id] : "?") + ": " + hipGetErrorString(e));
+    return PAAC_OK;
 }
 
 int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actions_dev, const float* rewards_dev,

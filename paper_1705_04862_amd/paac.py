@@ -23,7 +23,7 @@ ERRORS = {0: "PAAC_OK", -1: "PAAC_E_NULL", -2: "PAAC_E_BADCONFIG", -3: "PAAC_E_W
 
 # every symbol include/paac.h declares
 SYMBOLS = ["paac_workspace_bytes", "paac_create", "paac_destroy", "paac_init_params",
-           "paac_select_actions", "paac_train_step", "paac_param_count", "paac_get_state",
+           "paac_select_actions", "paac_select_actions_noalloc", "paac_train_step", "paac_param_count", "paac_get_state",
            "paac_set_state", "paac_get_train_outputs", "paac_get_train_activations", "paac_fill_uniforms", "paac_set_graphs", "paac_set_activation_cache", "paac_set_algorithm",
            "paac_set_profiling", "paac_kernel_times", "paac_flops", "paac_last_error"]
 
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
         L.paac_destroy.restype = None
         L.paac_init_params.argtypes = [vp, u64]
         L.paac_select_actions.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.paac_select_actions_noalloc.argtypes = [vp, vp, vp, vp, vp, vp]
         L.paac_train_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(paac_hparams), vp]
         L.paac_param_count.argtypes = [vp]
         L.paac_param_count.restype = sz
@@ -152,6 +153,17 @@ class Paac:
         assert probs is None or (probs.dtype == torch.float32 and probs.numel() == self.n_e * self.n_actions)
         self._check(self.L.paac_select_actions(self.ctx, _ptr(states), _ptr(uniforms), _ptr(actions),
                                                _ptr(values), _ptr(probs)))
+
+    def select_actions_noalloc(self, states: torch.Tensor, uniforms: torch.Tensor, actions: torch.Tensor,
+                               values: Optional[torch.Tensor] = None, probs: Optional[torch.Tensor] = None):
+        """select_actions through the entry point that uses the library's static scratch."""
+        assert states.dtype == torch.uint8 and states.is_contiguous() and states.numel() == self.n_e * 28224
+        assert uniforms.dtype == torch.float32 and uniforms.numel() == self.n_e and uniforms.is_contiguous()
+        assert actions.dtype == torch.int32 and actions.numel() == self.n_e and actions.is_contiguous()
+        assert values is None or (values.dtype == torch.float32 and values.numel() == self.n_e)
+        assert probs is None or (probs.dtype == torch.float32 and probs.numel() == self.n_e * self.n_actions)
+        self._check(self.L.paac_select_actions_noalloc(self.ctx, _ptr(states), _ptr(uniforms), _ptr(actions),
+                                                       _ptr(values), _ptr(probs)))
 
     def train_step(self, states: torch.Tensor, actions: torch.Tensor, rewards: torch.Tensor,
                    dones: torch.Tensor, hp, stats: Optional[torch.Tensor] = None):

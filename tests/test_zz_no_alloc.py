@@ -1,0 +1,74 @@
+"""paac_select_actions_noalloc (the entry point for callers that cannot allocate: its scratch is a
+static device array inside the library) against paac_select_actions, through the C ABI: same kernels
+on other buffers, so the same bits -- which is inside every tolerance of the parity tests -- on two
+calls in a row, the second on a smaller input, all sharing the one scratch array of the GPU."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1705_04862_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def paac():
+    from paper_1705_04862_amd import paac as P
+    P.lib()
+    return P
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def select_both_ways(P, oracle, net, n_e, precision, seed):
+    ctx = P.Paac(net.arch, n_e, 2, net.n_actions, precision)
+    params = I.make_params(seed, net, bias_range=0.05)
+    ctx.set_state(params)
+    ctx.set_graphs(False)
+    st = I.make_states(seed, 1, n_e, net)[0]
+    u = I.make_uniforms(seed, 1, n_e)[0]
+    out = []
+    for call in (ctx.select_actions, ctx.select_actions_noalloc):
+        a = torch.full((n_e,), -7, dtype=torch.int32, device="cuda:0")
+        v = torch.full((n_e,), np.nan, dtype=torch.float32, device="cuda:0")
+        p = torch.full((n_e, net.n_actions), np.nan, dtype=torch.float32, device="cuda:0")
+        call(dev(st), dev(u), a, v, p)
+        torch.cuda.synchronize()
+        out.append((a.cpu().numpy(), v.cpu().numpy(), p.cpu().numpy()))
+    for x, y in zip(*out):
+        np.testing.assert_array_equal(x, y)
+    # and the answer is the oracle's (fp32 configurations: the tolerances of the select parity tests)
+    if precision == 0:
+        want = oracle.select_actions(net, params, st, u)
+        acts, vals, probs = out[1]
+        assert np.abs(vals - want["values"]).max() <= 1e-4 * np.abs(want["values"]).max()
+        assert np.abs(probs - want["probs"]).max() <= 1e-4 * np.abs(want["probs"]).max()
+        cdf = np.cumsum(want["probs"].astype(np.float64), axis=1)
+        for e in range(n_e):
+            assert acts[e] == want["actions"][e] or np.abs(cdf[e] - float(u[e])).min() < 1e-5
+    return ctx
+
+
+def test_noalloc_select_matches_select_on_two_calls_in_a_row(paac, oracle):
+    big = select_both_ways(paac, oracle, I.nature_net(18), 32, 0, 61)       # the paper's batch
+    small = select_both_ways(paac, oracle, I.nature_net(18), 5, 0, 62)      # smaller input, same scratch, stale contents behind it
+    select_both_ways(paac, oracle, I.nips_net(6), 3, 0, 63)
+    select_both_ways(paac, oracle, I.nature_net(6), 64, 1, 64)              # bf16 configuration
+    del big, small
+
+
+def test_noalloc_select_rejects_what_does_not_fit(paac):
+    net = I.nature_net(18)
+    ctx = paac.Paac(net.arch, 512, 1, net.n_actions, 0)
+    ctx.set_state(I.make_params(65, net))
+    st = dev(I.make_states(65, 1, 512, net)[0])
+    u = dev(I.make_uniforms(65, 1, 512)[0])
+    a = torch.empty(512, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(paac.PaacError) as ei:
+        ctx.select_actions_noalloc(st, u, a)
+    assert ei.value.code == -3 and "static scratch" in str(ei.value)
+    ctx.select_actions(st, u, a)                                            # the allocating caller's entry point still serves it
+    torch.cuda.synchronize()
+    assert ((a.cpu().numpy() >= 0) & (a.cpu().numpy() < 18)).all()
