@@ -7,6 +7,10 @@ paac_train_step over the n_e x t_max rollout.  Inputs are synthetic, seeded, and
 before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--n_e N] [--t_max T] [--no-cpu-baseline]
+                    [--phase both|select|train]
+
+--phase select / train runs only that call in every loop of the run (for profiler runs whose rows
+must not mix the two calls' launches of one kernel); the reported value is then not the metric.
 """
 import argparse
 import json
@@ -20,6 +24,22 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+
+# Kernels of the fp32 configuration that issue bf16 MFMAs on exact operand parts (bytes are exact in
+# bf16; an fp32 number is the sum of three bf16 parts): name -> bf16 multiply-accumulates issued per
+# algorithmic fp32 one.  Their rate is reported against the fp32 matrix peak as algorithmic work and,
+# times this factor, against the bf16 matrix peak as issued work.
+def bf16_parts_per_mac(name, rows):
+    """rows: states in the launch.  The first layer (forward, weight gradient) always runs on exact
+    parts (bytes x three weight / gradient parts); layers 2-3 forward from 96 states per launch on (six
+    part products per multiply-accumulate), alone or with the first layer in one launch."""
+    if name.endswith("conv1_fwd") or name.endswith("conv1_wgrad"):
+        return 3.0
+    if name.endswith("convs_fwd"):
+        return 5.3            # FLOP-weighted mean of 3 (first layer) and 6 (layers 2-3) on the Nature network
+    if rows >= 96 and (name.endswith("conv2_fwd") or name.endswith("conv3_fwd")):
+        return 6.0
+    return 0.0
 
 
 def kernel_work(net, n_e, t_max):
@@ -50,6 +70,10 @@ def kernel_work(net, n_e, t_max):
     w["train.fc_bwd"] = ("flop", 2 * fc * B)
     for l in range(1, len(conv)):
         w[f"train.conv{l + 1}_bwd"] = ("flop", 2 * conv[l] * B)
+    # HBM-side bytes of the first-layer forward pass (bf16 configuration: the bound there): the uint8
+    # states in, the bf16 activations out
+    c1 = shapes[0]
+    w["_conv1_fwd_bytes_per_state"] = ("byte", float(net.in_c * net.in_h * net.in_w + 2 * c1[0] * c1[1] * c1[2]))
     w["select.heads_sample"] = ("flop", hd * n_e)
     w["train.heads_fwd"] = ("flop", hd * Bp)
     w["train.heads_bwd"] = ("flop", 2 * hd * B)
@@ -69,8 +93,8 @@ def main():
     ap.add_argument("--rollouts", type=int, default=4, help="distinct resident rollouts rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=50)
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="only run a 256 MiB device-to-device copy 10 times (calibrates the HBM byte counters)")
+    ap.add_argument("--phase", choices=["both", "select", "train"], default="both",
+                    help="run only this call in every loop (profiler runs); 'both' is the metric")
     ap.add_argument("--n_e", type=int, default=0, help="override the configuration's environment count (n_e sweep)")
     ap.add_argument("--t_max", type=int, default=0, help="override the configuration's rollout length")
     ap.add_argument("--lr", type=float, default=0.0, help="override the configuration's learning rate")
@@ -84,14 +108,6 @@ def main():
 
     import numpy as np
     import torch
-    if args.copy_probe:
-        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
-        b = torch.empty_like(a)
-        for _ in range(10):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes_read": 256 << 20, "copy_probe_bytes_written": 256 << 20, "launches": 10}))
-        return
     from paper_1705_04862_amd import inputs as I
     from paper_1705_04862_amd import paac as P
 
@@ -133,7 +149,8 @@ def main():
                       values=torch.zeros(T, n_e, dtype=torch.float32, device="cuda:0")))
     stats = torch.zeros(8, dtype=torch.float32, device="cuda:0")
 
-    def step(i, what="both"):
+    def step(i, what=None):
+        what = what or args.phase
         r = R[i % len(R)]
         if what in ("both", "select"):
             for t in range(T):
@@ -141,7 +158,7 @@ def main():
         if what in ("both", "train"):
             ctx.train_step(r["states"], r["actions"], r["rewards"], r["dones"], cfg.hp, stats)
 
-    def timed(k, what="both"):
+    def timed(k, what=None):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(k):
@@ -170,8 +187,8 @@ def main():
     value = args.steps * n_e * T / elapsed
 
     # context figures: the halves of the step
-    ms_select = 1e3 * timed(k2, "select") / k2
-    ms_train = 1e3 * timed(k2, "train") / k2
+    ms_select = 1e3 * timed(k2, "select") / k2 if args.phase != "train" else 0.0
+    ms_train = 1e3 * timed(k2, "train") / k2 if args.phase != "select" else 0.0
     # context: the same step with the opt-in rollout activation cache (the train step reuses the
     # activations of the t_max select calls and only runs the forward pass of the bootstrap states);
     # never the reported value
@@ -181,40 +198,66 @@ def main():
     ms_cached = 1e3 * timed(k2) / k2
     ctx.set_activation_cache(False)
 
-    # per-kernel durations with HIP events on the library's stream
-    ctx.set_profiling(True)
-    for i in range(args.profile_steps):
-        step(i)
-    times = ctx.kernel_times()
-    ctx.set_profiling(False)
-    work = kernel_work(net, n_e, T)
-    per_kernel = {}
-    for name, t in times.items():
-        avg_us = 1e3 * t["ms"] / t["calls"]
-        kind, amount = work[name]
-        per_kernel[name] = dict(avg_us=round(avg_us, 3), calls_per_step=t["calls"] / args.profile_steps,
-                                us_per_step=round(1e3 * t["ms"] / args.profile_steps, 3))
-        if kind == "flop":
-            per_kernel[name]["tflops"] = round(amount / (avg_us * 1e-6) / 1e12, 3)
+    per_kernel, roof = {}, None
+    bf16cfg = cfg.precision == 1
+    mfma_peak = PEAK_BF16_MFMA_TFLOPS if bf16cfg else PEAK_FP32_MFMA_TFLOPS
+    if args.profile_steps > 0:
+        # per-kernel durations with HIP events on the library's stream
+        ctx.set_profiling(True)
+        for i in range(args.profile_steps):
+            step(i)
+        times = ctx.kernel_times()
+        ctx.set_profiling(False)
+        work = kernel_work(net, n_e, T)
+        per_kernel = {}
+        for name, t in times.items():
+            avg_us = 1e3 * t["ms"] / t["calls"]
+            kind, amount = work[name]
+            per_kernel[name] = dict(avg_us=round(avg_us, 3), calls_per_step=t["calls"] / args.profile_steps,
+                                    us_per_step=round(1e3 * t["ms"] / args.profile_steps, 3))
+            if kind == "flop":
+                per_kernel[name]["tflops"] = round(amount / (avg_us * 1e-6) / 1e12, 3)
+            else:
+                per_kernel[name]["gbs"] = round(amount / (avg_us * 1e-6) / 1e9, 1)
+        bf16cfg = cfg.precision == 1
+        mfma_peak = PEAK_BF16_MFMA_TFLOPS if bf16cfg else PEAK_FP32_MFMA_TFLOPS
+        for name, k in per_kernel.items():
+            if "tflops" in k:
+                k["frac_of_peak"] = round(k["tflops"] / mfma_peak, 4)
+                parts = 0.0 if bf16cfg else bf16_parts_per_mac(name, n_e if name.startswith("select.") else n_e * (T + 1))
+                if parts:                                              # issued bf16 work against the bf16 peak
+                    k["bf16_parts_per_mac"] = parts
+                    k["frac_of_bf16_peak_issued"] = round(k["tflops"] * parts / PEAK_BF16_MFMA_TFLOPS, 4)
+            else:
+                k["frac_of_peak"] = round(k["gbs"] / PEAK_HBM_GBS, 4)
+        dom = max(per_kernel, key=lambda n: per_kernel[n]["us_per_step"])
+        kind, amount = work[dom]
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath) and not (args.n_e or args.t_max):      # counters were taken at the configuration's own size
+            traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
+        avg_s = per_kernel[dom]["avg_us"] * 1e-6
+        # Which roof bounds the dominant kernel is decided by the evidence: its algorithmic FLOP rate as a
+        # fraction of the matrix peak against its HBM byte rate (counter-measured bytes per launch where the
+        # counters were taken at this size, else the algorithmic bytes) as a fraction of 8 TB/s.
+        states = n_e if dom.startswith("select.") else n_e * (T + 1)
+        alg_bytes = work["_conv1_fwd_bytes_per_state"][1] * states if dom.endswith("conv1_fwd") else None
+        mfma_frac = amount / avg_s / 1e12 / mfma_peak if kind == "flop" else 0.0
+        hbm_bytes = amount if kind == "byte" else (traffic if traffic else alg_bytes)
+        hbm_frac = hbm_bytes / avg_s / 1e9 / PEAK_HBM_GBS if hbm_bytes else 0.0
+        if kind == "flop" and mfma_frac >= hbm_frac:
+            roof = dict(bound="mfma", kernel=dom, achieved=round(amount / avg_s / 1e12, 3), peak=mfma_peak, unit="TFLOP/s",
+                        frac=round(mfma_frac, 4), traffic=traffic, avg_launch_us=per_kernel[dom]["avg_us"],
+                        algorithmic_flop_per_launch=amount, hbm_frac_of_same_kernel=round(hbm_frac, 4))
         else:
-            per_kernel[name]["gbs"] = round(amount / (avg_us * 1e-6) / 1e9, 1)
-    dom = max(per_kernel, key=lambda n: per_kernel[n]["us_per_step"])
-    kind, amount = work[dom]
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath) and not (args.n_e or args.t_max):      # counters were taken at the configuration's own size
-        traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
-    mfma_peak = PEAK_BF16_MFMA_TFLOPS if cfg.precision == 1 else PEAK_FP32_MFMA_TFLOPS
-    if kind == "flop":
-        ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e12
-        roof = dict(bound="mfma", kernel=dom, achieved=round(ach, 3), peak=mfma_peak, unit="TFLOP/s",
-                    frac=round(ach / mfma_peak, 4), traffic=traffic,
-                    avg_launch_us=per_kernel[dom]["avg_us"], algorithmic_flop_per_launch=amount)
-    else:
-        ach = amount / (per_kernel[dom]["avg_us"] * 1e-6) / 1e9
-        roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic,
-                    avg_launch_us=per_kernel[dom]["avg_us"], algorithmic_bytes_per_launch=amount)
+            ab = amount if kind == "byte" else (alg_bytes if alg_bytes else hbm_bytes)
+            roof = dict(bound="hbm", kernel=dom, achieved=round(ab / avg_s / 1e9, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(ab / avg_s / 1e9 / PEAK_HBM_GBS, 4), traffic=traffic, avg_launch_us=per_kernel[dom]["avg_us"],
+                        algorithmic_bytes_per_launch=ab, mfma_frac_of_same_kernel=round(mfma_frac, 4))
+        if "bf16_parts_per_mac" in per_kernel[dom]:
+            roof["note"] = ("this kernel issues %.1f bf16 MFMA multiply-accumulates per algorithmic fp32 one (exact operand parts): "
+                            "%.4f of the bf16 matrix peak as issued work" % (per_kernel[dom]["bf16_parts_per_mac"], per_kernel[dom]["frac_of_bf16_peak_issued"]))
+
 
     sel_f, trn_f = ctx.flops()
     step_flop = T * sel_f + trn_f
@@ -226,7 +269,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.precision == 1 else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "net": net.name, "n_e": n_e, "t_max": T, "n_actions": net.n_actions,
-                   "rollouts_rotated": len(R), "algorithm": args.algorithm,
+                   "rollouts_rotated": len(R), "algorithm": args.algorithm, "phase": args.phase,
                    "launch": "hip-graph replay (t_max select graphs + 1 train graph)" if use_graphs else "direct kernel launches on one stream"},
         "roofline": roof,
         "step_gflop": round(step_flop / 1e9, 3),
@@ -239,7 +282,7 @@ def main():
                          "about 7200 (arch_nips) / 4100-4300 (arch_nature) env-timesteps/s for this path",
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.phase == "both":
         from oracle import paac_oracle as O
         ro = host_rollouts[0]
         rms = I.make_rms(0, net)
@@ -256,11 +299,14 @@ def main():
         t0 = time.perf_counter()
         oracle_iter()
         first = time.perf_counter() - t0
-        reps = int(max(1, min(20, 10.0 / max(first, 1e-3))))
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            oracle_iter()
-        el = time.perf_counter() - t0
+        if first >= 5.0:                      # one iteration is already a bounded sample (the large configurations)
+            reps, el = 1, first
+        else:
+            reps = int(max(1, min(20, 10.0 / max(first, 1e-3))))
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                oracle_iter()
+            el = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(reps * n_e * T / el, 2), "unit": "env-timesteps/s",
                                "cores": O.threads(), "kind": "oracle",
                                "sample": "%d full iterations (t_max selects + 1 train) of %s" % (reps, cfg.name)}

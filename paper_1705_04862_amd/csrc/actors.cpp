@@ -1,7 +1,7 @@
 // Worker pool and synthetic environment of the parallel framework (host only, no GPU code).
 // n_w persistent threads each own a contiguous range of the n_e environments and step them one
-// after the other when the master publishes a new generation (Section 3: "a set of n_w workers then
-// applies all the actions to the their respective environments in parallel").
+// after the other when the master publishes a new generation (Section 3, the workers' step of
+// Algorithm 1: all actions of a timestep are applied by the n_w workers side by side).
 #include "../../include/paac_actors.h"
 
 #include <atomic>
@@ -57,7 +57,8 @@ struct paac_actors {
         for (int k = 0; k < sprites; ++k) {
             const uint64_t h = key(seed, e, s.episode, s.step, 8 + k);
             // the action shifts the sprite: the observation is a function of what the agent did
-            const int x = (int)((h & 0xffff) + 3u * (unsigned)action * (unsigned)(k + 1)) % (kW - 8);
+            // unsigned throughout: any int action (negative ones included) lands inside the row
+            const int x = (int)(((unsigned)(h & 0xffff) + 3u * (unsigned)action * (unsigned)(k + 1)) % (unsigned)(kW - 8));
             const int y = (int)((h >> 16) & 0xffff) % (kH - 8);
             const uint8_t v = (uint8_t)(64 + ((h >> 32) % 192));
             for (int dy = 0; dy < 8; ++dy) memset(frame + (y + dy) * kW + x, v, 8);

@@ -23,22 +23,6 @@
 
 namespace paac {
 
-#ifdef PAAC_KERNEL_TIMING
-// diagnostic build only: per-workgroup phase time stamps (100 MHz wall clock); record 0 is a counter
-extern __device__ unsigned long long* g_kernel_timing;
-#define PAAC_STAMP_INIT() unsigned long long* stamp__ = nullptr; \
-    if (g_kernel_timing && threadIdx.x == 0) { stamp__ = g_kernel_timing + 16 * (1 + atomicAdd(g_kernel_timing, 1ull)); stamp__[8] = stamp__[9] = stamp__[10] = stamp__[11] = 0; \
-        stamp__[5] = gridDim.x; stamp__[6] = K; stamp__[7] = M; }
-#define PAAC_STAMP(i) do { if (stamp__) stamp__[i] = wall_clock64(); } while (0)
-#define PAAC_PHASE_BEGIN() unsigned long long ph__ = clock64()
-#define PAAC_PHASE_END(i) do { const unsigned long long n__ = clock64(); if (stamp__) stamp__[8 + (i)] += n__ - ph__; ph__ = n__; } while (0)
-#else
-#define PAAC_PHASE_BEGIN() do {} while (0)
-#define PAAC_PHASE_END(i) do {} while (0)
-#define PAAC_STAMP_INIT() do {} while (0)
-#define PAAC_STAMP(i) do {} while (0)
-#endif
-
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // ----------------------------------------------------------------------------------------------
@@ -140,8 +124,6 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     const int k_begin = k_per_split > 0 ? z * k_per_split : 0;
     const int k_end = k_per_split > 0 ? min(K, k_begin + k_per_split) : K;
     const int nk = (k_end - k_begin + BK - 1) / BK;
-    PAAC_STAMP_INIT();
-    PAAC_STAMP(0);
 
     // per-thread fixed coordinates of the staging loads
     typename AL::Fixed afix[A_IT];
@@ -325,13 +307,9 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
     auto step = [&](int kt, auto stage) {
         constexpr int G = decltype(stage)::value;
         constexpr int GN = (G + 1) % S;
-        PAAC_PHASE_BEGIN();
         gload(kt + S, stage);      // stage G was stored to LDS one step ago; past the end: clamped, zeroed
-        PAAC_PHASE_END(0);
         compute_and_store(kt & 1, std::integral_constant<int, GN>(), (kt + 1) & 1);   // after the last tile: zeros nobody reads
-        PAAC_PHASE_END(1);
         __syncthreads();
-        PAAC_PHASE_END(3);
     };
     // Auxiliary epilogue operands (bias, ReLU mask) do not depend on the accumulators: their loads are
     // issued before the first operand load, so the epilogue does not start with a memory round trip
@@ -351,14 +329,12 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
             }
     };
     if constexpr (AuxEarly<EP>::value) load_aux();      // one register per column (a bias); masks would cost 16
-    PAAC_STAMP(1);
     gload(0, std::integral_constant<int, 0>());
     gload(1, std::integral_constant<int, 1>());
     if constexpr (S > 2) gload(2, std::integral_constant<int, 2>());
     if constexpr (S > 3) gload(3, std::integral_constant<int, 3>());
     lstore(std::integral_constant<int, 0>(), 0);
     __syncthreads();
-    PAAC_STAMP(2);
     // Whole rounds of S steps run without any branch, the remainder after the loop.  With a step that
     // can be skipped inside the loop the compiler sees a path on which a register stage is loaded
     // again while its previous load is still outstanding, and waits for ALL loads at the loop head:
@@ -378,7 +354,6 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
         }
     }
 
-    PAAC_STAMP(3);
     if constexpr (EP::kColSum) {
         if (mt == 0 && tid < BN && n0 + tid < N) ep.store_colsum(n0 + tid, colsum, z);
     }
@@ -426,7 +401,6 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
                 if (row < M && col < N) ep.store(row, col, acc[0][i][j][r], z, aux[i][j][r]);
             }
         }
-    PAAC_STAMP(4);
 }
 
 // ----------------------------------------------------------------------------------------------
