@@ -550,9 +550,9 @@ def test_bf16_large_batch_per_sample_weight_gradients(paac, oracle):
 
 def test_bf16_backward_at_4096_transitions(paac, oracle):
     """4096 transitions (n_e=256, t_max=16, Nature net): the batch from which the fc data gradient runs
-    on 128x128 tiles with a ragged last column tile (3136 columns) and the tiled GEMMs walk over more
-    tiles than are resident at once -- the launch shapes of the largest configuration.  The whole step,
-    every tensor, against the oracle."""
+    on 128x128 tiles with a ragged last column tile (3136 columns), as in the largest configuration
+    (whose own test additionally reaches grids that walk over more tiles than are resident at once).
+    The whole step, every tensor, against the oracle."""
     net = I.nature_net(6)
     n_e, t_max = 256, 16
     ctx = make_ctx(paac, net, n_e, t_max, precision=1)
