@@ -42,7 +42,7 @@ def bf16_parts_per_mac(name, rows):
     return 0.0
 
 
-def kernel_work(net, n_e, t_max):
+def kernel_work(net, n_e, t_max, act_bytes=4):
     """Algorithmic work per launch of every kernel: ('flop', 2 x MACs) or ('byte', HBM bytes)."""
     B, Bp, A = n_e * t_max, n_e * (t_max + 1), net.n_actions
     shapes = net.conv_out_shapes()
@@ -70,10 +70,10 @@ def kernel_work(net, n_e, t_max):
     w["train.fc_bwd"] = ("flop", 2 * fc * B)
     for l in range(1, len(conv)):
         w[f"train.conv{l + 1}_bwd"] = ("flop", 2 * conv[l] * B)
-    # HBM-side bytes of the first-layer forward pass (bf16 configuration: the bound there): the uint8
-    # states in, the bf16 activations out
+    # algorithmic HBM bytes of the first-layer forward pass per state (the bound of that kernel in the
+    # bf16 configuration): the uint8 state in, the activations out (2 bytes each in bf16, else 4)
     c1 = shapes[0]
-    w["_conv1_fwd_bytes_per_state"] = ("byte", float(net.in_c * net.in_h * net.in_w + 2 * c1[0] * c1[1] * c1[2]))
+    w["_conv1_fwd_bytes_per_state"] = ("byte", float(net.in_c * net.in_h * net.in_w + act_bytes * c1[0] * c1[1] * c1[2]))
     w["select.heads_sample"] = ("flop", hd * n_e)
     w["train.heads_fwd"] = ("flop", hd * Bp)
     w["train.heads_bwd"] = ("flop", 2 * hd * B)
@@ -208,7 +208,7 @@ def main():
             step(i)
         times = ctx.kernel_times()
         ctx.set_profiling(False)
-        work = kernel_work(net, n_e, T)
+        work = kernel_work(net, n_e, T, 2 if cfg.precision == 1 else 4)
         per_kernel = {}
         for name, t in times.items():
             avg_us = 1e3 * t["ms"] / t["calls"]
@@ -238,12 +238,13 @@ def main():
             traffic = json.load(open(tpath)).get(f"cfg{args.config}", {}).get(dom)
         avg_s = per_kernel[dom]["avg_us"] * 1e-6
         # Which roof bounds the dominant kernel is decided by the evidence: its algorithmic FLOP rate as a
-        # fraction of the matrix peak against its HBM byte rate (counter-measured bytes per launch where the
-        # counters were taken at this size, else the algorithmic bytes) as a fraction of 8 TB/s.
+        # fraction of the matrix peak against its algorithmic HBM byte rate as a fraction of 8 TB/s (for a
+        # contraction without a stated byte figure, the counter-measured bytes per launch where the counters
+        # were taken at this size); the larger fraction names the roof the kernel is closer to.
         states = n_e if dom.startswith("select.") else n_e * (T + 1)
         alg_bytes = work["_conv1_fwd_bytes_per_state"][1] * states if dom.endswith("conv1_fwd") else None
         mfma_frac = amount / avg_s / 1e12 / mfma_peak if kind == "flop" else 0.0
-        hbm_bytes = amount if kind == "byte" else (traffic if traffic else alg_bytes)
+        hbm_bytes = amount if kind == "byte" else (alg_bytes if alg_bytes else traffic)
         hbm_frac = hbm_bytes / avg_s / 1e9 / PEAK_HBM_GBS if hbm_bytes else 0.0
         if kind == "flop" and mfma_frac >= hbm_frac:
             roof = dict(bound="mfma", kernel=dom, achieved=round(amount / avg_s / 1e12, 3), peak=mfma_peak, unit="TFLOP/s",

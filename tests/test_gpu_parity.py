@@ -805,3 +805,50 @@ def test_fp32_forward_error_is_at_rounding_level(paac, oracle, ci):
     assert relmax_tensor(logits, want.logits) < 5e-6
     assert relmax_tensor(values, want.values) < 5e-6
     assert relmax_tensor(returns, want.returns) < 5e-6
+
+
+@pytest.mark.parametrize("precision,net,n_e,t_max", [(0, I.nature_net(18), 32, 5), (0, I.nips_net(6), 7, 2), (0, I.nature_net(6), 40, 3),
+                                                     (1, I.nature_net(18), 9, 2), (1, I.nature_net(6), 150, 1)],
+                         ids=["fp32_config2", "fp32_nips_7x2", "fp32_nature_160_rows_one_workgroup_per_sample", "bf16_nature_9x2", "bf16_nature_300_rows"])
+def test_stored_activations_layer_by_layer(paac, oracle, precision, net, n_e, t_max):
+    """Every layer's stored output of the train step's forward pass (paac_get_train_activations)
+    against the oracle's, element by element: fp32 at 1e-4; bf16 at 2e-2 against the plain oracle and at
+    one bf16 step (2^-8 relative, with the 2e-3 floor of the forward check) against the oracle mode that
+    rounds the same tensors.  Also the argument checks of the read-back call."""
+    import dataclasses
+    ctx = make_ctx(paac, net, n_e, t_max, precision=precision)
+    params = I.make_params(211, net, bias_range=0.05)
+    ro = I.make_rollout(211, net, n_e, t_max, 0.1)
+    ctx.set_state(params)
+    ctx.train_step(dev(ro.states), dev(ro.actions), dev(ro.rewards), dev(ro.dones), I.HParams())
+    torch.cuda.synchronize()
+    flat = ro.states.reshape(-1, net.in_c, net.in_h, net.in_w)
+    _, _, want = oracle.forward_f64(net, params.astype(np.float64), flat, want_acts=True)
+    wq = None
+    if precision == 1:
+        _, _, wq = oracle.forward_f64(dataclasses.replace(net, bf16=1), params.astype(np.float64), flat, want_acts=True)
+    per = [c * h * w for c, h, w in net.conv_out_shapes()] + [net.fc]
+    off = 0
+    for layer, n in enumerate(per):
+        got = ctx.get_train_activations(layer, n)
+        assert got.shape == (flat.shape[0], n) and (got >= 0).all() and (got > 0).any()
+        ref = want[:, off:off + n]
+        if precision == 0:
+            assert relmax(got, ref) < TOL_VAL, layer
+        else:
+            assert relmax_tensor(got, ref) < TOL_BF16, layer
+            rq = wq[:, off:off + n]
+            assert (np.abs(got - rq) <= 2.0 ** -7 * np.abs(rq) + TOL_BF16_SAME_STORAGE * np.abs(rq).max()).all(), layer
+            if layer < len(net.conv):      # stored conv outputs are bf16 numbers
+                np.testing.assert_array_equal(got, torch.tensor(got).to(torch.bfloat16).to(torch.float32).numpy())
+        # a row range gives the same rows
+        sub = ctx.get_train_activations(layer, n, 3, 2)
+        np.testing.assert_array_equal(sub, got[3:5])
+        off += n
+    L = paac.lib()
+    buf = np.empty(per[0], np.float32)
+    bp = buf.ctypes.data_as(__import__("ctypes").c_void_p)
+    assert L.paac_get_train_activations(ctx.ctx, len(per), 0, 1, bp) == -2          # layer out of range
+    assert L.paac_get_train_activations(ctx.ctx, 0, flat.shape[0], 1, bp) == -2     # rows outside the forward batch
+    assert L.paac_get_train_activations(ctx.ctx, 0, 0, 1, None) == -1
+    assert L.paac_get_train_activations(ctx.ctx, 0, 0, 0, bp) == 0
