@@ -102,13 +102,14 @@ int paac_select_actions(paac_ctx* ctx, const uint8_t* states_dev, const float* u
  * PAAC_NOALLOC_SCRATCH_BYTES inside the library instead of the caller's workspace, the kernels are
  * launched one by one on the context's stream (no graph is built), and the call makes no hipMalloc,
  * hipFree or other allocating call.  Parameters are still read from the context's workspace.
- * A configuration whose select call needs more scratch than that (the Nature network in fp32 beyond
- * n_e of about 80) is rejected with PAAC_E_WORKSPACE and a message naming both sizes.
+ * A configuration whose select call needs more scratch than that is rejected with
+ * PAAC_E_WORKSPACE and a message naming both sizes (the Nature network fits for every n_e up to 159 in
+ * fp32 and up to 243 with bf16 operands, the smaller network beyond that).
  * Each GPU holds one such array until the process ends, and every context on that GPU shares it: the
  * array keeps the last call's contents (nothing in it has to start at zero: every byte a call reads
  * it has written before), and two such calls that overlap in time on one GPU (different streams or
  * contexts) race.  The call neither reads nor advances the rollout activation cache. */
-#define PAAC_NOALLOC_SCRATCH_BYTES (8u << 20)
+#define PAAC_NOALLOC_SCRATCH_BYTES (16u << 20)
 int paac_select_actions_noalloc(paac_ctx* ctx, const uint8_t* states_dev, const float* uniforms_dev,
                                 int32_t* actions_dev, float* values_dev, float* probs_dev);
 

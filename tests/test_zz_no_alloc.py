@@ -56,6 +56,7 @@ def test_noalloc_select_matches_select_on_two_calls_in_a_row(paac, oracle):
     small = select_both_ways(paac, oracle, I.nature_net(18), 5, 0, 62)      # smaller input, same scratch, stale contents behind it
     select_both_ways(paac, oracle, I.nips_net(6), 3, 0, 63)
     select_both_ways(paac, oracle, I.nature_net(6), 64, 1, 64)              # bf16 configuration
+    select_both_ways(paac, oracle, I.nature_net(6), 159, 0, 65)             # the largest fp32 batch that fits
     del big, small
 
 
