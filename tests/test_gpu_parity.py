@@ -663,13 +663,13 @@ def test_ne_sweep_sizes_with_scaled_learning_rate(paac, oracle, n_e):
 
 
 def test_heads_kernels_agree_across_the_batch_threshold(paac, oracle):
-    """Up to 512 rows the heads run one workgroup per row, above that one wavefront per row; both must
+    """Up to 2048 rows the heads run one workgroup per row, above that one wavefront per row; both must
     give the oracle's answer, and the same bits for the same state."""
     net = I.nips_net(6)
     params = I.make_params(41, net, bias_range=0.1)
-    st = I.make_states(41, 1, 520, net)[0]
-    u = I.make_uniforms(41, 1, 520)[0]
-    big = make_ctx(paac, net, 520, 1)
+    st = I.make_states(41, 1, 2100, net)[0]
+    u = I.make_uniforms(41, 1, 2100)[0]
+    big = make_ctx(paac, net, 2100, 1)
     big.set_state(params)
     got_big = run_select(big, net, st, u)
     check_select(oracle, net, params, st, u, got_big)

@@ -94,8 +94,8 @@ def test_q_variant_configs(paac, oracle, ci):
 
 
 @pytest.mark.parametrize("net,n_e,t_max,eps", [(I.nips_net(2), 1, 1, 0.0), (I.nature_net(32), 5, 2, 1.0), (I.nips_net(7), 67, 3, 0.1),
-                                               (I.nips_net(6), 600, 1, 0.05)],
-                         ids=["nips_A2_ne1_t1_greedy", "nature_A32_ne5_random", "nips_A7_ne67", "nips_ne600_wave_per_row_kernel"])
+                                               (I.nips_net(6), 2100, 1, 0.05)],
+                         ids=["nips_A2_ne1_t1_greedy", "nature_A32_ne5_random", "nips_A7_ne67", "nips_ne2100_wave_per_row_kernel"])
 def test_q_variant_ragged_shapes_and_extreme_epsilon(paac, oracle, net, n_e, t_max, eps):
     ctx = make_ctx(paac, net, n_e, t_max)
     ctx.set_algorithm(paac.PAAC_ALG_NSTEP_Q, eps)
