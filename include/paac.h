@@ -33,7 +33,8 @@ extern "C" {
 #define PAAC_E_BADCONFIG  -2   /* a field of paac_config / paac_hparams is out of range        */
 #define PAAC_E_WORKSPACE  -3   /* workspace missing, misaligned (256 B) or too small           */
 #define PAAC_E_HIP        -4   /* a HIP runtime call failed (text in paac_last_error)          */
-#define PAAC_E_STATE      -5   /* call made before paac_init_params / paac_set_state           */
+#define PAAC_E_STATE      -5   /* call made before paac_init_params / paac_set_state, or a read-back
+                                  of train-step results before the first paac_train_step          */
 
 #define PAAC_ARCH_NIPS    0    /* conv 16@8x8/4, conv 32@4x4/2, fc 256   (Experiments: arch_nips)   */
 #define PAAC_ARCH_NATURE  1    /* conv 32@8x8/4, 64@4x4/2, 64@3x3/1, fc 512 (Experiments: arch_nature) */

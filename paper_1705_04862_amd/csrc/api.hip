@@ -272,6 +272,7 @@ struct paac_ctx {
     int device;
     void* noalloc_scratch;    // this device's copy of the static scratch array
     bool have_params;
+    bool have_train;          // a train step has run since the context was created: its intermediate results exist
     bool cache_on;            // rollout activation cache enabled
     int sel_count;            // select calls since the last train step / parameter load
     int algorithm;            // PAAC_ALG_*
@@ -594,7 +595,7 @@ int paac_create(const paac_config* cfg, void* workspace_dev, size_t workspace_by
     c->buf = carve(c->net, c->arena, c->plan, cfg->precision == PAAC_PREC_BF16, static_cast<char*>(workspace_dev));
     if (c->buf.bytes > workspace_bytes) { delete c; return PAAC_E_WORKSPACE; }
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->have_params = false; c->use_graphs = true; c->profiling = false;
+    c->have_params = false; c->have_train = false; c->use_graphs = true; c->profiling = false;
     c->algorithm = PAAC_ALG_ACTOR_CRITIC; c->epsilon = 0.f;
     c->hp_next = 0; c->hp_valid = false;
     memset(c->hp_ev_used, 0, sizeof(c->hp_ev_used));
@@ -754,6 +755,7 @@ int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actio
     const TrainArgs x{states_dev, actions_dev, rewards_dev, dones_dev, stats_dev};
     const bool cached = c->cache_on && c->sel_count == c->plan.T;
     c->sel_count = 0;
+    c->have_train = true;
     GraphKey key{};
     key.kind = 1; key.p[0] = states_dev; key.p[1] = actions_dev; key.p[2] = rewards_dev; key.p[3] = dones_dev; key.p[4] = stats_dev;
     key.p[5] = reinterpret_cast<const void*>(static_cast<uintptr_t>(cached ? 1 : 0));
@@ -763,6 +765,7 @@ int paac_train_step(paac_ctx* c, const uint8_t* states_dev, const int32_t* actio
 
 int paac_get_train_outputs(paac_ctx* c, float* logits_host, float* values_host, float* returns_host) {
     if (!c) return PAAC_E_NULL;
+    if (!c->have_train) return fail(c, PAAC_E_STATE, "no train step yet: nothing is stored");
     const Plan& p = c->plan;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (logits_host) HIP_TRY(c, hipMemcpy(logits_host, c->buf.logits, (size_t)p.Bp * c->net.n_actions * sizeof(float), hipMemcpyDeviceToHost));
@@ -775,6 +778,7 @@ int paac_get_train_activations(paac_ctx* c, int layer, int row0, int rows, float
     if (!c) return PAAC_E_NULL;
     if (!out_host) return fail(c, PAAC_E_NULL, "out_host is NULL");
     const NetDesc& n = c->net; const Plan& p = c->plan;
+    if (!c->have_train) return fail(c, PAAC_E_STATE, "no train step yet: nothing is stored");
     if (layer < 0 || layer > n.n_conv) return fail(c, PAAC_E_BADCONFIG, "layer out of range");
     if (row0 < 0 || rows < 0 || (long long)row0 + rows > p.Bp) return fail(c, PAAC_E_BADCONFIG, "row range outside the forward batch");
     HIP_TRY(c, hipStreamSynchronize(c->stream));

@@ -323,6 +323,9 @@ def test_error_codes(paac):
     a = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     assert L.paac_select_actions(ctx.ctx, st.data_ptr(), u.data_ptr(), a.data_ptr(), None, None) == -5   # no params yet
     ctx.init_params(1)
+    one = np.empty(16 * 400, np.float32)
+    assert L.paac_get_train_activations(ctx.ctx, 0, 0, 1, one.ctypes.data_as(C.c_void_p)) == -5   # no train step yet
+    assert L.paac_get_train_outputs(ctx.ctx, None, None, None) == -5
     assert L.paac_select_actions(ctx.ctx, None, u.data_ptr(), a.data_ptr(), None, None) == -1
     assert L.paac_select_actions(None, st.data_ptr(), u.data_ptr(), a.data_ptr(), None, None) == -1
     assert b"required" in L.paac_last_error(ctx.ctx)
