@@ -2,8 +2,9 @@
 oracle: epsilon-greedy selection and the n-step Q-learning update, through the C ABI.
 Tolerances as for the actor-critic path: Q values, returns and losses within 1e-4 (relative to the
 tensor's largest magnitude), gradients / parameters / RMSProp state within 1e-3 relative L2; the
-bf16 path within 2e-2 (forward) and 6e-2 (gradients, ReLU flips).  Actions must be equal unless
-the two largest Q values are closer than the forward tolerance."""
+bf16 path within 2e-2, its gradients compared with the ReLU decisions of the HIP path handed to the
+oracle.  Actions must be equal unless the two largest Q values are closer than the forward
+tolerance."""
 import dataclasses
 
 import numpy as np
