@@ -25,12 +25,13 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
     constexpr int COUT = G::COUT, CIN = G::CIN;
     constexpr int PP = COUT + 8;                       // position pitch of the padded dY (odd multiple of 16 bytes: no bank conflicts)
     constexpr int PADW = G::WO + 2, PADH = G::HO + 2;  // one zero position around the output map
+    constexpr int RP = bank_continuing_pitch(PADW * PP, G::WC, PP / 8);     // row pitch: a fragment's bank sequence continues in the next row
     constexpr int OP = CIN + 8;                        // position pitch of the dX image
     constexpr int CS = COUT / 16, KSTEPS = 4 * CS;     // 16-wide k-steps per tap, in all
     constexpr int ROWS = G::HC * G::WC, FRAGS = (ROWS + 31) / 32;
     constexpr int DY_CH = G::HO * G::WO * COUT / 8, DY_IT = (DY_CH + 255) / 256;
     constexpr int DX_CH = G::H * G::W * CIN / 8, DX_IT = (DX_CH + 255) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t dyp[PADH * PADW * PP];
+    __shared__ __attribute__((aligned(16))) bf16_t dyp[PADH * RP];
     __shared__ __attribute__((aligned(16))) bf16_t dxi[G::H * G::W * OP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
     int s = blockIdx.x;
     if (s >= ns) return;
     PAAC_PREFETCH_DY(s);
-    for (int i = tid; i < PADH * PADW * PP / 8; i += 256) reinterpret_cast<uint4*>(dyp)[i] = zero_u4();     // the border stays zero
+    for (int i = tid; i < PADH * RP / 8; i += 256) reinterpret_cast<uint4*>(dyp)[i] = zero_u4();     // the border stays zero
     __syncthreads();
 
     // block position of fragment row m (rows past the class: a valid position, never stored)
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
 #pragma unroll
     for (int f = 0; f < FRAGS; ++f) {
         const int r = min(f * 32 + m, ROWS - 1);
-        a_off[f] = ((r / G::WC + 1) * PADW + (r % G::WC + 1)) * PP + half * 8;
+        a_off[f] = (r / G::WC + 1) * RP + (r % G::WC + 1) * PP + half * 8;
     }
 
     for (; s < ns; s += gridDim.x) {
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
             const int ch = tid + i * 256;
             if (ch < DY_CH) {
                 const int pos = ch / (COUT / 8), c8 = ch % (COUT / 8);
-                *reinterpret_cast<u32x4*>(dyp + ((pos / G::WO + 1) * PADW + (pos % G::WO + 1)) * PP + c8 * 8) = pdy[i];
+                *reinterpret_cast<u32x4*>(dyp + (pos / G::WO + 1) * RP + (pos % G::WO + 1) * PP + c8 * 8) = pdy[i];
             }
         }
         __syncthreads();                               // also: the previous sample's dX image has been read
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
             for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
         // the fragments of k-step ks + 1 are read while those of ks are multiplied (the scheduling barriers
         // keep the reads ahead: read-wait-multiply in a row would expose the LDS latency 64 times a sample)
-        auto koff = [](int ks) { return (ks % CS) * 16 - (((ks / CS) >> 1) * PADW + ((ks / CS) & 1)) * PP; };   // constant after unrolling
+        auto koff = [](int ks) { return (ks % CS) * 16 - (((ks / CS) >> 1) * RP + ((ks / CS) & 1) * PP); };   // constant after unrolling
         u32x4 a_cur[FRAGS], a_nxt[FRAGS];
 #pragma unroll
         for (int f = 0; f < FRAGS; ++f) a_cur[f] = *reinterpret_cast<const u32x4*>(dyp + a_off[f] + koff(0));
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_kernel(const bf16_t*
         for (int f = 0; f < FRAGS; ++f)
 #pragma unroll
             for (int q = 0; q < 16; q += 2) {
-                const float o0 = __shfl_xor(acc[f][q], 1), o1 = __shfl_xor(acc[f][q + 1], 1);
+                const float o0 = lane_xor1(acc[f][q]), o1 = lane_xor1(acc[f][q + 1]);
                 const bool odd = m & 1;
                 const int r = f * 32 + Mma<32>::row(odd ? q + 1 : q, lane);
                 const unsigned w = odd ? pack2(o1, acc[f][q + 1]) : pack2(acc[f][q], o0);
@@ -160,22 +161,24 @@ inline hipError_t launch_conv_dgrad_direct(hipStream_t s, const bf16_t* dy, cons
 // of dY[y - ky][x - kx][co] W[ky][kx][ci][co], a full correlation, so the zero border is two positions
 // wide.  There are no parity classes; the four waves are 2 halves of the 64 input channels x 2 halves of
 // the 36 k-steps (each wave keeps 18 k-steps of weights in registers), and the two k-halves are added
-// through LDS before the image of dX is written.
+// through LDS (each wave finishes half of its block's rows) before the image of dX is written.
 template <class G>
 __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ Wd,
                                                                       const bf16_t* __restrict__ act_in, bf16_t* __restrict__ dx, int ns) {
     static_assert(G::ST == 1 && G::KS == 3 && G::CIN == 64 && G::COUT % 16 == 0, "stride-1 3x3 layer with 64 input channels");
     constexpr int COUT = G::COUT, CIN = G::CIN, T = G::KS * G::KS;
     constexpr int PP = COUT + 8, PAD = G::KS - 1, PADW = G::WO + 2 * PAD, PADH = G::HO + 2 * PAD;
+    constexpr int RP = bank_continuing_pitch(PADW * PP, G::W, PP / 8);      // row pitch: a fragment's bank sequence continues in the next row
     constexpr int OP = CIN + 8;
     constexpr int CS = COUT / 16, KSTEPS = T * CS, KH = KSTEPS / 2;
     static_assert(KSTEPS % 2 == 0, "two equal k-halves");
     constexpr int ROWS = G::H * G::W, FRAGS = (ROWS + 31) / 32;
     constexpr int DY_CH = G::HO * G::WO * COUT / 8, DY_IT = (DY_CH + 255) / 256;
     constexpr int DX_CH = ROWS * CIN / 8, DX_IT = (DX_CH + 255) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t dyp[PADH * PADW * PP];
+    __shared__ __attribute__((aligned(16))) bf16_t dyp[PADH * RP];
     __shared__ __attribute__((aligned(16))) bf16_t dxi[ROWS * OP];
-    __shared__ float red[2 * FRAGS * 16 * 64];
+    typedef KShares<2, 2, FRAGS> KS_;
+    __shared__ __attribute__((aligned(16))) float red[KS_::FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = lane & 31, half = lane >> 5;
@@ -203,14 +206,14 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
     int s = blockIdx.x;
     if (s >= ns) return;
     PAAC_PREFETCH_DY(s);
-    for (int i = tid; i < PADH * PADW * PP / 8; i += 256) reinterpret_cast<uint4*>(dyp)[i] = zero_u4();     // the border stays zero
+    for (int i = tid; i < PADH * RP / 8; i += 256) reinterpret_cast<uint4*>(dyp)[i] = zero_u4();     // the border stays zero
     __syncthreads();
 
     int a_off[FRAGS];
 #pragma unroll
     for (int f = 0; f < FRAGS; ++f) {
         const int r = min(f * 32 + m, ROWS - 1);
-        a_off[f] = ((r / G::W + PAD) * PADW + (r % G::W + PAD)) * PP + half * 8;
+        a_off[f] = (r / G::W + PAD) * RP + (r % G::W + PAD) * PP + half * 8;
     }
 
     for (; s < ns; s += gridDim.x) {
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
             const int ch = tid + i * 256;
             if (ch < DY_CH) {
                 const int pos = ch / (COUT / 8), c8 = ch % (COUT / 8);
-                *reinterpret_cast<u32x4*>(dyp + ((pos / G::WO + PAD) * PADW + (pos % G::WO + PAD)) * PP + c8 * 8) = pdy[i];
+                *reinterpret_cast<u32x4*>(dyp + (pos / G::WO + PAD) * RP + (pos % G::WO + PAD) * PP + c8 * 8) = pdy[i];
             }
         }
         __syncthreads();                               // also: the previous sample's dX image has been read
@@ -239,8 +242,8 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
         // the fragments of step i + 1 are read while those of i are multiplied
         auto koff = [&](int i) {
             const int ks0 = i, ks1 = KH + i;
-            const int off0 = (ks0 % CS) * 16 - ((ks0 / CS / G::KS) * PADW + (ks0 / CS % G::KS)) * PP;
-            const int off1 = (ks1 % CS) * 16 - ((ks1 / CS / G::KS) * PADW + (ks1 / CS % G::KS)) * PP;
+            const int off0 = (ks0 % CS) * 16 - ((ks0 / CS / G::KS) * RP + (ks0 / CS % G::KS) * PP);
+            const int off1 = (ks1 % CS) * 16 - ((ks1 / CS / G::KS) * RP + (ks1 / CS % G::KS) * PP);
             return kh ? off1 : off0;
         };
         u32x4 a_cur[FRAGS], a_nxt[FRAGS];
@@ -260,30 +263,25 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_direct_s1_kernel(const bf16
 #pragma unroll
             for (int f = 0; f < FRAGS; ++f) a_cur[f] = a_nxt[f];
         }
-        if (kh == 1) {
-#pragma unroll
-            for (int f = 0; f < FRAGS; ++f)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) red[((nb * FRAGS + f) * 16 + q) * 64 + lane] = acc[f][q];
-        }
+        with_k_share<2>(kh, [&](auto KG) __attribute__((always_inline)) { KS_::template give<decltype(KG)::value>(acc, red, nb, lane); });
         __syncthreads();                               // dY has been read by every wave
-        if (kh == 0) {
-#pragma unroll
-            for (int f = 0; f < FRAGS; ++f)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) acc[f][q] += red[((nb * FRAGS + f) * 16 + q) * 64 + lane];
+        with_k_share<2>(kh, [&](auto KG) __attribute__((always_inline)) {
+            constexpr int kgc = decltype(KG)::value;
+            KS_::template take<kgc>(acc, red, nb, lane);
             // lanes m and m ^ 1 hold neighbouring channels of one position: one word per pair
 #pragma unroll
             for (int f = 0; f < FRAGS; ++f)
 #pragma unroll
-                for (int q = 0; q < 16; q += 2) {
-                    const float o0 = __shfl_xor(acc[f][q], 1), o1 = __shfl_xor(acc[f][q + 1], 1);
-                    const bool odd = m & 1;
-                    const int r = f * 32 + Mma<32>::row(odd ? q + 1 : q, lane);
-                    const unsigned w = odd ? pack2(o1, acc[f][q + 1]) : pack2(acc[f][q], o0);
-                    if (r < ROWS) *reinterpret_cast<unsigned*>(dxi + r * OP + (ci & ~1)) = w;
-                }
-        }
+                for (int gi = 0; gi < KS_::GPO; ++gi)
+#pragma unroll
+                    for (int q = 4 * (kgc * KS_::GPO + gi); q < 4 * (kgc * KS_::GPO + gi) + 4; q += 2) {
+                        const float o0 = lane_xor1(acc[f][q]), o1 = lane_xor1(acc[f][q + 1]);
+                        const bool odd = m & 1;
+                        const int r = f * 32 + Mma<32>::row(odd ? q + 1 : q, lane);
+                        const unsigned w = odd ? pack2(o1, acc[f][q + 1]) : pack2(acc[f][q], o0);
+                        if (r < ROWS) *reinterpret_cast<unsigned*>(dxi + r * OP + (ci & ~1)) = w;
+                    }
+        });
         __syncthreads();                               // the dX image is complete
         bf16_t* out = dx + (size_t)s * (ROWS * CIN);
 #pragma unroll

@@ -6,10 +6,11 @@
 // output position (oy, ox) and k-step (ky, kx, 16 channels) is 16 bytes at base(oy, ox) + a
 // compile-time offset.  For the stride-2 layer the image is de-interleaved by the parity of x: the
 // positions x = 2 ox + kx of consecutive ox are then neighbours, and the position pitch (channels + 8
-// elements) is an odd multiple of 16 bytes, so sixteen lanes read sixteen different bank groups.
+// elements) is an odd multiple of 16 bytes, so sixteen lanes read sixteen different bank groups; the row
+// pitch keeps that true for the lanes behind the end of an output row.
 // The four waves are (32-wide block of output channels) x (share of the k-steps); each keeps its
-// weights in registers for all samples, the k-shares are added through LDS, and bias + ReLU + bf16
-// results leave through an LDS image as contiguous 16-byte stores.
+// weights in registers for all samples, the k-shares are added through LDS (every wave finishes a part
+// of the block's rows), and bias + ReLU + bf16 results leave through an LDS image as contiguous 16-byte stores.
 #pragma once
 #include "gemm_bf16.hip.h"
 
@@ -29,9 +30,15 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_direct_kernel(const bf16_t* _
     constexpr int IN_POS = G::H * G::W;
     constexpr int IN_CH = IN_POS * CIN / 8, IN_IT = (IN_CH + 255) / 256;
     constexpr int OUT_CH = ROWS * COUT / 8, OUT_IT = (OUT_CH + 255) / 256;
-    constexpr int IMG = IN_POS * PI > ROWS * PO ? IN_POS * PI : ROWS * PO;      // the output image reuses the input image's LDS
+    // image rows (stride 1) or pairs of image rows with their two x-parity planes each (stride 2) start at a
+    // pitch that continues the bank sequence of a fragment from one output row to the next
+    constexpr int RP = ST == 1 ? bank_continuing_pitch(G::W * PI, G::WO, PI / 8) : bank_continuing_pitch(2 * G::W * PI, G::WO, PI / 8);
+    constexpr int IMG_IN = (ST == 1 ? G::H : G::H / 2) * RP;
+    static_assert(ST == 1 || G::H % 2 == 0, "pairs of image rows");
+    constexpr int IMG = IMG_IN > ROWS * PO ? IMG_IN : ROWS * PO;      // the output image reuses the input image's LDS
     __shared__ __attribute__((aligned(16))) bf16_t img[IMG];
-    __shared__ float red[(KW - 1) * NB * FRAGS * 16 * 64];
+    typedef KShares<NB, KW, FRAGS> KS_;
+    __shared__ __attribute__((aligned(16))) float red[KS_::FLOATS];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -39,12 +46,12 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_direct_kernel(const bf16_t* _
     const int nb = wave % NB, kg = wave / NB;
     const int co = nb * 32 + m;
 
-    // LDS position of input (y, x)
-    auto ipos = [](int y, int x) { return ST == 2 ? (y * 2 + (x & 1)) * (G::W / 2) + (x >> 1) : y * G::W + x; };
+    // LDS offset (elements) of input (y, x); additive in (2 oy, 2 ox) + (ky, kx) for the stride-2 layer
+    auto ioff = [](int y, int x) { return ST == 2 ? (y >> 1) * RP + (((y & 1) * 2 + (x & 1)) * (G::W / 2) + (x >> 1)) * PI : y * RP + x * PI; };
     // offset of k-step ks = (ky, kx, channel group) relative to a row's base
     auto koff = [&](int ks) {
         const int tap = ks / CSI, cs = ks % CSI, ky = tap / KS, kx = tap % KS;
-        return ipos(ky, kx) * PI + cs * 16;
+        return ioff(ky, kx) + cs * 16;
     };
 
     bf16x8 bfr[KPW];
@@ -57,7 +64,7 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_direct_kernel(const bf16_t* _
 #pragma unroll
     for (int f = 0; f < FRAGS; ++f) {
         const int r = min(f * 32 + m, ROWS - 1);          // rows past the map: a valid position, never stored
-        a_off[f] = ipos((r / G::WO) * ST, (r % G::WO) * ST) * PI + half * 8;
+        a_off[f] = ioff((r / G::WO) * ST, (r % G::WO) * ST) + half * 8;
     }
 
     u32x4 pin[IN_IT];
@@ -76,7 +83,7 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_direct_kernel(const bf16_t* _
             const int ch = tid + i * 256;
             if (ch < IN_CH) {
                 const int pos = ch / (CIN / 8), c8 = ch % (CIN / 8);
-                *reinterpret_cast<u32x4*>(img + ipos(pos / G::W, pos % G::W) * PI + c8 * 8) = pin[i];
+                *reinterpret_cast<u32x4*>(img + ioff(pos / G::W, pos % G::W) + c8 * 8) = pin[i];
             }
         }
         __syncthreads();
@@ -107,33 +114,26 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_direct_kernel(const bf16_t* _
 #pragma unroll
             for (int f = 0; f < FRAGS; ++f) a_cur[f] = a_nxt[f];
         }
-        if (kg > 0) {
-#pragma unroll
-            for (int f = 0; f < FRAGS; ++f)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) red[((((kg - 1) * NB + nb) * FRAGS + f) * 16 + q) * 64 + lane] = acc[f][q];
-        }
+        with_k_share<KW>(kg, [&](auto KG) __attribute__((always_inline)) { KS_::template give<decltype(KG)::value>(acc, red, nb, lane); });
         __syncthreads();                               // the input image has been read by every wave
-        if (kg == 0) {
-#pragma unroll
-            for (int g = 1; g < KW; ++g)
-#pragma unroll
-                for (int f = 0; f < FRAGS; ++f)
-#pragma unroll
-                    for (int q = 0; q < 16; ++q) acc[f][q] += red[((((g - 1) * NB + nb) * FRAGS + f) * 16 + q) * 64 + lane];
+        with_k_share<KW>(kg, [&](auto KG) __attribute__((always_inline)) {
+            constexpr int kgc = decltype(KG)::value;
+            KS_::template take<kgc>(acc, red, nb, lane);
             // lanes m and m ^ 1 hold neighbouring channels of one position: one word per pair
 #pragma unroll
             for (int f = 0; f < FRAGS; ++f)
 #pragma unroll
-                for (int q = 0; q < 16; q += 2) {
-                    const float v0 = fmaxf(acc[f][q] + bias_r, 0.f), v1 = fmaxf(acc[f][q + 1] + bias_r, 0.f);
-                    const float o0 = __shfl_xor(v0, 1), o1 = __shfl_xor(v1, 1);
-                    const bool odd = m & 1;
-                    const int r = f * 32 + Mma<32>::row(odd ? q + 1 : q, lane);
-                    const unsigned w = odd ? pack2(o1, v1) : pack2(v0, o0);
-                    if (r < ROWS) *reinterpret_cast<unsigned*>(img + r * PO + (co & ~1)) = w;
-                }
-        }
+                for (int gi = 0; gi < KS_::GPO; ++gi)
+#pragma unroll
+                    for (int q = 4 * (kgc * KS_::GPO + gi); q < 4 * (kgc * KS_::GPO + gi) + 4; q += 2) {
+                        const float v0 = fmaxf(acc[f][q] + bias_r, 0.f), v1 = fmaxf(acc[f][q + 1] + bias_r, 0.f);
+                        const float o0 = lane_xor1(v0), o1 = lane_xor1(v1);
+                        const bool odd = m & 1;
+                        const int r = f * 32 + Mma<32>::row(odd ? q + 1 : q, lane);
+                        const unsigned w = odd ? pack2(o1, v1) : pack2(v0, o0);
+                        if (r < ROWS) *reinterpret_cast<unsigned*>(img + r * PO + (co & ~1)) = w;
+                    }
+        });
         __syncthreads();                               // the output image is complete
         bf16_t* dst = out + (size_t)s * (ROWS * COUT);
 #pragma unroll

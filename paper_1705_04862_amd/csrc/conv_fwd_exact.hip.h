@@ -406,7 +406,7 @@ __global__ __launch_bounds__(256, 1) void trunk_fwd_exact_kernel(const uint8_t* 
             for (int q = 0; q < 16; q += 2) {
                 const float v0 = fmaxf(acc1[j][q] * scale + bias1, 0.f), v1 = fmaxf(acc1[j][q + 1] * scale + bias1, 0.f);
                 const int r0 = f * 32 + Mma<32>::row(q, lane), r1 = f * 32 + Mma<32>::row(q + 1, lane);
-                const float p0 = __shfl_xor(v0, 1), p1 = __shfl_xor(v1, 1);
+                const float p0 = lane_xor1(v0), p1 = lane_xor1(v1);
                 const bool odd = fidx & 1;
                 const int rr = odd ? r1 : r0;
                 unsigned hi, mid, lo;

@@ -23,24 +23,117 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ bf16_t f2bf(float f) { __bf16 b = (__bf16)f; return __builtin_bit_cast(unsigned short, b); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
-__device__ __forceinline__ unsigned pack2(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+// both conversions as one vector conversion: a single v_cvt_pk_bf16_f32 (the two scalar conversions
+// became two of them plus a shift and an OR); same rounding
+__device__ __forceinline__ unsigned pack2(float lo, float hi) {
+    const f32x2v v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
 // acc + lo + hi of a packed bf16 pair: one v_dot2 against (1, 1)
 __device__ __forceinline__ float dot2_ones(unsigned pair, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
 }
 __device__ __forceinline__ bool bf16_positive(bf16_t a) { return (a & 0x7fffu) != 0 && !(a & 0x8000u); }
-// keep the bf16 halves of v whose counterpart in a is a positive number
+// keep the bf16 halves of v whose counterpart in a is a positive number: as a signed 16-bit integer a
+// positive bf16 (NaN with a clear sign bit included, as above) is > 0; three packed 16-bit operations
+// (clamp below at 0, above at 1, times 0xffff) and the AND instead of two compare chains per half
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned mask2(unsigned v, unsigned a) {
-    const unsigned lo = bf16_positive((bf16_t)(a & 0xffffu)) ? 0x0000ffffu : 0u;
-    const unsigned hi = bf16_positive((bf16_t)(a >> 16)) ? 0xffff0000u : 0u;
-    return v & (lo | hi);
+    const i16x2 zero = {0, 0}, one = {1, 1};
+    const i16x2 pos = __builtin_elementwise_min(__builtin_elementwise_max(__builtin_bit_cast(i16x2, a), zero), one);    // 1 where a > 0
+    const u16x2 all = {0xffffu, 0xffffu};
+    return v & __builtin_bit_cast(unsigned, (u16x2)(__builtin_bit_cast(u16x2, pos) * all));
 }
 
 // staging registers as a native vector type: an array of the uint4 struct that is only copied in and
 // out is lowered to memcpy through private memory (scratch) instead of registers
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
+// The value lane ^ 1 holds: a DPP move inside the quad.  (__shfl_xor goes through the LDS crossbar and is
+// waited for like an LDS read: 24 such round trips were 3 000 of the 8 700 cycles a sample took in the
+// third layer's data gradient.)  Every lane of the wave must be active.
+__device__ __forceinline__ float lane_xor1(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+}
+// Row pitch of an LDS image whose rows an MFMA A fragment walks: lane m reads 16 bytes of the m-th
+// position, positions are `pos_chunks` 16-byte chunks apart (odd: sixteen consecutive positions of a
+// row hit the sixteen 16-byte bank groups once), and after `lanes_per_row` positions the fragment
+// continues in the next image row.  A ds_read_b128 is served sixteen consecutive lanes per cycle; with
+// the natural row pitch the lanes behind a row end land on bank groups that lanes before it use
+// (measured: 8-10 cycles per fragment read instead of 4.4).  Returned: the smallest pitch (elements,
+// a multiple of eight) >= min_elems that continues the bank sequence across the row end, i.e. whose
+// chunk count is lanes_per_row * pos_chunks modulo 16.
+constexpr int bank_continuing_pitch(int min_elems, int lanes_per_row, int pos_chunks) {
+    int c = (min_elems + 7) / 8;
+    while (c % 16 != (lanes_per_row * pos_chunks) % 16) ++c;
+    return c * 8;
+}
+// Waves that split the k-steps of one 32-wide column block add their 32 x 32 accumulators through LDS.
+// Every wave of the KW finishes its own groups of four accumulator registers (group g of a fragment =
+// rows 8 g + 4 (lane / 32) .. + 3): it hands the other waves' groups over as 16-byte stores, and after
+// the workgroup's barrier adds what the others left for it, in wave order whichever wave adds.  With
+// the first wave of a block adding and finishing everything, the others idled through the longest
+// part of a sample (2 000 of 7 500 cycles in the third layer's data gradient).
+template <int NB, int KW, int FRAGS> struct KShares {
+    static_assert(KW == 1 || KW == 2 || KW == 4, "groups of four registers divide evenly");
+    static constexpr int GPO = 4 / KW;                 // groups per owner and fragment
+    static constexpr int FLOATS = NB * KW * (KW - 1) * FRAGS * GPO * 64 * 4;
+    static __device__ __forceinline__ int slot(int nb, int owner, int src, int f, int gi, int lane) {
+        return (((((nb * KW + owner) * (KW - 1) + (src - (src > owner ? 1 : 0))) * FRAGS + f) * GPO + gi) * 64 + lane) * 4;
+    }
+    template <int KG> static __device__ __forceinline__ void give(const f32x16 (&acc)[FRAGS], float* red, int nb, int lane) {
+#pragma unroll
+        for (int o = 0; o < KW; ++o)
+            if (o != KG) {
+#pragma unroll
+                for (int f = 0; f < FRAGS; ++f)
+#pragma unroll
+                    for (int gi = 0; gi < GPO; ++gi) {
+                        const int g = o * GPO + gi;
+                        const f32x4 v = {acc[f][4 * g], acc[f][4 * g + 1], acc[f][4 * g + 2], acc[f][4 * g + 3]};
+                        *reinterpret_cast<f32x4*>(red + slot(nb, o, KG, f, gi, lane)) = v;
+                    }
+            }
+    }
+    // after the barrier: the sums of wave KG's groups, in acc[f][4 g ..] for g = KG * GPO + gi
+    template <int KG> static __device__ __forceinline__ void take(f32x16 (&acc)[FRAGS], const float* red, int nb, int lane) {
+        if constexpr (KW > 1) {
+            f32x4 got[KW - 1][FRAGS][GPO];
+#pragma unroll
+            for (int src = 0; src < KW; ++src)
+                if (src != KG) {
+#pragma unroll
+                    for (int f = 0; f < FRAGS; ++f)
+#pragma unroll
+                        for (int gi = 0; gi < GPO; ++gi)
+                            got[src - (src > KG ? 1 : 0)][f][gi] = *reinterpret_cast<const f32x4*>(red + slot(nb, KG, src, f, gi, lane));
+                }
+#pragma unroll
+            for (int f = 0; f < FRAGS; ++f)
+#pragma unroll
+                for (int gi = 0; gi < GPO; ++gi) {
+                    const int g = KG * GPO + gi;
+                    const f32x4 own = {acc[f][4 * g], acc[f][4 * g + 1], acc[f][4 * g + 2], acc[f][4 * g + 3]};
+                    f32x4 t = KG == 0 ? own : got[0][f][gi];
+#pragma unroll
+                    for (int src = 1; src < KW; ++src) t += src == KG ? own : got[src - (src > KG ? 1 : 0)][f][gi];
+                    acc[f][4 * g] = t.x; acc[f][4 * g + 1] = t.y; acc[f][4 * g + 2] = t.z; acc[f][4 * g + 3] = t.w;
+                }
+        }
+    }
+};
+// runs fn(std::integral_constant<int, kg>) for the wave-uniform kg in [0, KW): accumulator indices stay constants
+template <int KW, class F> __device__ __forceinline__ void with_k_share(int kg, F&& fn) {
+    if (kg == 0) fn(std::integral_constant<int, 0>());
+    if constexpr (KW > 1) { if (kg == 1) fn(std::integral_constant<int, 1>()); }
+    if constexpr (KW > 2) {
+        if (kg == 2) fn(std::integral_constant<int, 2>());
+        if (kg == 3) fn(std::integral_constant<int, 3>());
+    }
+}
 __device__ __forceinline__ uint4 keep_if_u4(bool ok, uint4 v) {
     return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
 }
