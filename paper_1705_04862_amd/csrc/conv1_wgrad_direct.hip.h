@@ -35,18 +35,24 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
     constexpr int COPY = 4 * IR * 4 * PW;                         // one de-interleaved band: [(c, y)][phase][PW]
     constexpr int NPART = EXACT ? 3 : 1, SP = 136;                // dY parts; slot pitch (128 slots + 8: conflict-free 16-byte reads)
     constexpr int IMG_ITEMS = 4 * IR * 6, IMG_IT = (IMG_ITEMS + 255) / 256;     // (c, y, quad of x/4) per band
-    constexpr int QUADS = BR * 5, DY_IT = (QUADS + 7) / 8;        // quads of positions per band; eight quads per pass of the workgroup
+    constexpr int QUADS = BR * 5;                                 // quads of positions per band
+    // dY arrives as 16-byte loads (CPT channels of one position); a thread owns one quad of positions of one
+    // channel group.  (One element per load, a thread per channel, was 64 of the 88 loads a wave issued per
+    // band, and the rate at which a compute unit accepts loads bounded the kernel.)
+    constexpr int CPT = EXACT ? 4 : 8, CGS = G::COUT / CPT, DY_UNITS = QUADS * CGS;
+    static_assert(G::COUT % CPT == 0 && DY_UNITS <= 256, "one unit per thread");
     __shared__ __attribute__((aligned(16))) bf16_t img[2 * COPY];
     __shared__ __attribute__((aligned(16))) bf16_t dyt[NPART * 32 * SP];
-    __shared__ float dbs[256];
+    __shared__ float dbs[G::COUT * QUADS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int items = ns * NB;
-    const int co = tid & 31, q8 = tid >> 5;                       // this thread's output channel and quad lane for dY
+    const int dcg = tid % CGS, dqd = tid / CGS;                   // this thread's channel group and quad of dY
+    const bool dy_unit = tid < DY_UNITS;
 
     // raw data of the next item, in registers during the MFMA phase of the current one
     uint4 iw[IMG_IT]; uint32_t inx[IMG_IT];
-    float dyr[DY_IT][4];
+    u32x4 dyr[4];
     auto prefetch = [&](int item) __attribute__((always_inline)) {
         const int s = item / NB, b = item % NB;
         const uint8_t* base = x + (size_t)s * SAMPLE + (size_t)(b * BR * G::ST) * G::W;
@@ -64,16 +70,12 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
             }
         }
         const size_t r0 = (size_t)s * (G::HO * G::WO) + (size_t)b * (BR * G::WO);
+        const int qd = min(dqd, QUADS - 1);                       // threads without a unit: a valid address, not stored
 #pragma unroll
-        for (int j = 0; j < DY_IT; ++j) {
-            const int qd = min(q8 + 8 * j, QUADS - 1);
-            const int cc = co < G::COUT ? co : 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const size_t at = (r0 + 4 * qd + e) * G::COUT + cc;
-                if constexpr (EXACT) dyr[j][e] = static_cast<const float*>(dy_)[at];
-                else dyr[j][e] = __uint_as_float((uint32_t)static_cast<const bf16_t*>(dy_)[at] << 16);
-            }
+        for (int e = 0; e < 4; ++e) {
+            const size_t at = (r0 + 4 * qd + e) * G::COUT + dcg * CPT;
+            if constexpr (EXACT) dyr[e] = *reinterpret_cast<const u32x4*>(static_cast<const float*>(dy_) + at);
+            else dyr[e] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(dy_) + at);
         }
     };
     auto pack_hi = [](float a, float b) __attribute__((always_inline)) {   // two fp32 with zero low halves -> two bf16
@@ -88,7 +90,9 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
     f32x16 acc[2];
 #pragma unroll
     for (int q = 0; q < 16; ++q) { acc[0][q] = 0.f; acc[1][q] = 0.f; }
-    float db = 0.f;
+    float db[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) db[c] = 0.f;
 
     // MFMA row m of a block of 32 k-values: m = (kx / 4) * 16 + ky_l * 4 + kx % 4 (sixteen lanes then read
     // sixteen different bank groups of one copy)
@@ -114,14 +118,14 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
                 }
             }
         }
-        if (co < G::COUT) {
+        if (dy_unit) {
+            const int slot = (dqd / 5) * 24 + (dqd % 5) * 4;
 #pragma unroll
-            for (int j = 0; j < DY_IT; ++j) {
-                const int qd = q8 + 8 * j;
-                if (qd < QUADS) {
-                    const int slot = (qd / 5) * 24 + (qd % 5) * 4;
-                    float v[4] = {dyr[j][0], dyr[j][1], dyr[j][2], dyr[j][3]};
-                    db += (v[0] + v[1]) + (v[2] + v[3]);
+            for (int c = 0; c < CPT; ++c) {                       // channel c of the group: its four positions as one 8-byte word per part
+                bf16_t* at = dyt + (dcg * CPT + c) * SP + slot;
+                if constexpr (EXACT) {
+                    float v[4] = {__uint_as_float(dyr[0][c]), __uint_as_float(dyr[1][c]), __uint_as_float(dyr[2][c]), __uint_as_float(dyr[3][c])};
+                    db[c] += (v[0] + v[1]) + (v[2] + v[3]);
 #pragma unroll
                     for (int part = 0; part < NPART; ++part) {
                         float h[4];
@@ -130,8 +134,15 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
                             h[e] = __uint_as_float(__float_as_uint(v[e]) & 0xffff0000u);
                             v[e] -= h[e];                           // exact residual: the next part is cut from it
                         }
-                        *reinterpret_cast<uint2*>(dyt + (part * 32 + co) * SP + slot) = make_uint2(pack_hi(h[0], h[1]), pack_hi(h[2], h[3]));
+                        *reinterpret_cast<uint2*>(at + part * 32 * SP) = make_uint2(pack_hi(h[0], h[1]), pack_hi(h[2], h[3]));
                     }
+                } else {
+                    const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                    uint2 o;
+                    o.x = __builtin_amdgcn_perm(dyr[1][c >> 1], dyr[0][c >> 1], sel);
+                    o.y = __builtin_amdgcn_perm(dyr[3][c >> 1], dyr[2][c >> 1], sel);
+                    db[c] = dot2_ones(o.y, dot2_ones(o.x, db[c]));
+                    *reinterpret_cast<uint2*>(at) = o;
                 }
             }
         }
@@ -176,12 +187,15 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
                 out[(wave * 64 + ky * 8 + kx) * G::COUT + m] = acc[blk][q] * scale;
             }
     }
-    dbs[tid] = db;
+    if (dy_unit) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) dbs[(dcg * CPT + c) * QUADS + dqd] = db[c];
+    }
     __syncthreads();
     if (tid < G::COUT) {
         float sdb = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) sdb += dbs[tid + 32 * j];
+        for (int j = 0; j < QUADS; ++j) sdb += dbs[tid * QUADS + j];
         pb[(size_t)blockIdx.x * G::COUT + tid] = sdb;
     }
 }
