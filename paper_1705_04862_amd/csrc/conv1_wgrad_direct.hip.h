@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256, 2) void conv1_wgrad_direct_kernel(const uint8_
             else dyr[e] = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(dy_) + at);
         }
     };
-    auto pack_hi = [](float a, float b) __attribute__((always_inline)) {   // two fp32 with zero low halves -> two bf16
-        return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xffff0000u);
+    auto pack_hi = [](float a, float b) __attribute__((always_inline)) {   // two fp32 with zero low halves -> two bf16 (exact: one packed conversion)
+        return pack2(a, b);
     };
 
     int item = blockIdx.x;
