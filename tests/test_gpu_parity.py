@@ -565,6 +565,20 @@ def test_bf16_backward_at_4096_transitions(paac, oracle):
     check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16_256x16", unconditioned=False)
 
 
+def test_bf16_per_sample_weight_gradient_with_uneven_shares(paac, oracle):
+    """2100 transitions (n_e=700, t_max=3, Nature net): the smallest kind of batch that takes the per-sample
+    weight-gradient kernels of layers 2-3 (from 2048 samples on), with a sample count that the workgroups
+    do not share evenly: some walk over nine samples, the others over eight, so the ends of their
+    pipelines (last transposition, last requests, last barrier) differ between workgroups."""
+    net = I.nature_net(6)
+    n_e, t_max = 700, 3
+    ctx = make_ctx(paac, net, n_e, t_max, precision=1)
+    params = I.make_params(89, net, bias_range=0.05)
+    rms = I.make_rms(89, net, hi=0.01)
+    ro = I.make_rollout(89, net, n_e, t_max, 0.02)
+    check_train_bf16(oracle, net, ctx, params, rms, ro, I.HParams(), "bf16_700x3", unconditioned=False)
+
+
 def test_bf16_graph_replay_deterministic(paac):
     cfg = I.CONFIGS[3]
     net = cfg.net
