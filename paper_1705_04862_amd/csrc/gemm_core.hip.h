@@ -84,6 +84,13 @@ struct Tile {
 
 template <class E, class = void> struct AuxEarly { static constexpr bool value = false; };
 template <class E> struct AuxEarly<E, std::enable_if_t<E::kAuxEarly>> { static constexpr bool value = true; };
+// Epilogues whose element address is a sum of a row part and a column part declare kSplitAddr and give
+//   int row_part(int row, int z) const; int col_part(int col, int z) const;   (element offsets)
+//   const float* mask() const; float* dst() const;      out[rp + cp] = mask[rp + cp] > 0 ? v : 0
+// A thread then computes 16 row parts and one column part per fragment instead of the address of every
+// element twice (its divisions by the geometry's constants were most of a scatter epilogue's instructions).
+template <class E, class = void> struct SplitAddr { static constexpr bool value = false; };
+template <class E> struct SplitAddr<E, std::enable_if_t<E::kSplitAddr>> { static constexpr bool value = true; };
 template <class L, class = void> struct RowFast { static constexpr bool value = false; };
 template <class L> struct RowFast<L, std::enable_if_t<L::kRowFast>> { static constexpr bool value = true; };
 template <class L> __host__ __device__ constexpr bool row_fast() { return RowFast<L>::value; }
@@ -389,6 +396,39 @@ __device__ __forceinline__ void gemm_body(const AL& al, const BL& bl, const EP& 
                     for (int r = 0; r < MM::NACC; ++r) acc[0][i][j][r] += src[((i * TN + j) * MM::NACC + r) * 64];
         }
     }
+    if constexpr (SplitAddr<EP>::value) {
+        int cp[TN]; bool cok[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * (TN * MF) + j * MF + MM::col(lane);
+            cok[j] = col < N;
+            cp[j] = ep.col_part(cok[j] ? col : 0, z);
+        }
+        const float* const mk = ep.mask();
+        float* const out = ep.dst();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int at[TN][MM::NACC];
+            float a[TN][MM::NACC];
+#pragma unroll
+            for (int r = 0; r < MM::NACC; ++r) {
+                const int row = m0 + wm * (TM * MF) + i * MF + MM::row(r, lane);
+                const bool rok = row < M;
+                const int rp = ep.row_part(rok ? row : 0, z);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    at[j][r] = rok && cok[j] ? rp + cp[j] : -1;
+                    a[j][r] = mk[at[j][r] >= 0 ? at[j][r] : 0];       // every mask load of the fragment row, then the stores
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < MM::NACC; ++r)
+                    if (at[j][r] >= 0) out[at[j][r]] = a[j][r] > 0.f ? acc[0][i][j][r] : 0.f;
+        }
+        return;
+    }
     if constexpr (!AuxEarly<EP>::value) load_aux();     // every auxiliary load of the tile, then the stores
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -603,9 +643,16 @@ template <bool COLSUM> struct EpiPartial {   // out[z][row][col] = v ; optional 
 };
 
 template <class G> struct EpiDgradMask {     // scatter a parity class back to NHWC, times ReLU'
-    static constexpr bool kColSum = false;
+    static constexpr bool kColSum = false, kSplitAddr = true;
     typedef float Aux;
     float* dx; const float* act;
+    __device__ __forceinline__ int row_part(int row, int) const {
+        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
+        return ((n * G::H + yy * G::ST) * G::W + xx * G::ST) * G::CIN;
+    }
+    __device__ __forceinline__ int col_part(int col, int z) const { return ((z / G::ST) * G::W + z % G::ST) * G::CIN + col; }
+    __device__ __forceinline__ const float* mask() const { return act; }
+    __device__ __forceinline__ float* dst() const { return dx; }
     __device__ __forceinline__ size_t addr(int row, int col, int z) const {
         const int py = z / G::ST, px = z % G::ST;
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
@@ -618,9 +665,19 @@ template <class G> struct EpiDgradMask {     // scatter a parity class back to N
 };
 
 template <class G> struct EpiDgradMaskAll {  // the same for columns n = (z, ci) of all parity classes
-    static constexpr bool kColSum = false;
+    static constexpr bool kColSum = false, kSplitAddr = true;
     typedef float Aux;
     float* dx; const float* act;
+    __device__ __forceinline__ int row_part(int row, int) const {
+        const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
+        return ((n * G::H + yy * G::ST) * G::W + xx * G::ST) * G::CIN;
+    }
+    __device__ __forceinline__ int col_part(int col, int) const {
+        const int z = col / G::CIN, ci = col % G::CIN;
+        return ((z / G::ST) * G::W + z % G::ST) * G::CIN + ci;
+    }
+    __device__ __forceinline__ const float* mask() const { return act; }
+    __device__ __forceinline__ float* dst() const { return dx; }
     __device__ __forceinline__ size_t addr(int row, int col) const {
         const int z = col / G::CIN, ci = col % G::CIN, py = z / G::ST, px = z % G::ST;
         const int n = row / (G::HC * G::WC), r = row % (G::HC * G::WC), yy = r / G::WC, xx = r % G::WC;
