@@ -3,6 +3,7 @@
 // Experiments section (arch_nips: 16@8x8/4, 32@4x4/2, fc 256; arch_nature: 32@8x8/4, 64@4x4/2,
 // 64@3x3/1, fc 512; input 4x84x84, no padding).
 #include "gemm_core.hip.h"
+#include "gemm_reg16.hip.h"
 #include "internal.h"
 
 namespace paac {
@@ -62,7 +63,12 @@ static hipError_t launch_auto(hipStream_t s, const AL& al, const BL& bl, const E
     auto wgs = [&](int bm, int bn) { return (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * z; };
     if (wgs(TBig::BM, TBig::BN) >= kMinWgs) return launch_gemm<TBig>(s, al, bl, ep, M, N, K, z, 0);
     if (wgs(TMid::BM, TMid::BN) >= kMinWgs) return launch_gemm<TMid>(s, al, bl, ep, M, N, K, z, 0);
-    if (wgs(TSmall::BM, TSmall::BN) < kMinWgs) return launch_gemm<T16x16>(s, al, bl, ep, M, N, K, z, 0);
+    if (wgs(TSmall::BM, TSmall::BN) < kMinWgs) {
+        if constexpr (std::is_same_v<BL, DenseKCols> && AL::kContig && !SplitAddr<EP>::value && !EP::kColSum)
+            return launch_gemm_reg16(s, al, bl, ep, M, N, K, z, 0);
+        else
+            return launch_gemm<T16x16>(s, al, bl, ep, M, N, K, z, 0);
+    }
     return launch_gemm<TSmall>(s, al, bl, ep, M, N, K, z, 0);
 }
 
@@ -256,7 +262,7 @@ hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float
     DenseRowsK al{x, ns, flat};
     DenseKCols bl{W, fc, fc};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
-    if (fc_small(ns)) return launch_gemm<T16x16>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+    if (fc_small(ns)) return launch_gemm_reg16(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
     return launch_gemm<T64x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
 }
 
