@@ -99,6 +99,7 @@ struct Plan {
     int n_e, T, B, Bp;
     Split sel_fc, trn_fc, wg[3], fc_wg;
     int head_chunks, n_loss_blocks;
+    bool fused_loss;
 };
 
 Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
@@ -129,7 +130,10 @@ Plan make_plan(const NetDesc& n, int n_e, int T, bool bf16) {
     const int c1_cap = bf16 ? 768 : 384;
     p.wg[0].n = 4 * p.B < c1_cap ? 4 * p.B : c1_cap; p.wg[0].k_per = 0;
     p.head_chunks = p.B / 8 < 1 ? 1 : (p.B / 8 > 128 ? 128 : p.B / 8);
-    p.n_loss_blocks = loss_blocks(n_e);
+    // below 1024 rows the returns + loss work rides in the head-backward launch, which leaves one
+    // partial sum of the loss terms per chunk of rows instead of one per block of the loss kernel
+    p.fused_loss = heads_bwd_fuses_loss(p.B, n.n_actions, p.T, n.fc);
+    p.n_loss_blocks = p.fused_loss ? p.head_chunks : loss_blocks(n_e);
     return p;
 }
 
@@ -439,13 +443,14 @@ hipError_t enqueue_train(paac_ctx* c, hipStream_t s, bool prof, const TrainArgs&
     la.hp = b.hp; la.T = p.T; la.n_e = p.n_e; la.A = A;
     la.returns = b.returns; la.dz = b.dz; la.dv = b.dv; la.loss_partials = b.loss_partials;
     la.algorithm = c->algorithm;
-    L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
+    const bool fused_loss = p.fused_loss;
+    if (!fused_loss) L.run(K_TRN_LOSS, [&] { return returns_loss(L.s, la); });
     // heads backward
     const bool bf16 = c->cfg.precision == PAAC_PREC_BF16;
     float* const fc_pw = p.fc_wg.n > 1 ? b.fc_pw : b.grads + a.fc_w;
     L.run(K_TRN_HEADS_BWD, [&] {
         return heads_bwd(L.s, F, A, p.B, p.head_chunks, b.dz, b.dv, b.theta + a.pi_w, b.theta + a.v_w, b.h, bf16 ? nullptr : (float*)b.dh,
-                         bf16 ? (bf16_t*)b.dh : nullptr, b.hd_pw, b.hd_pb);
+                         bf16 ? (bf16_t*)b.dh : nullptr, b.hd_pw, b.hd_pb, fused_loss ? &la : nullptr);
     });
     // fc backward
     if (bf16) {

@@ -155,7 +155,10 @@ hipError_t returns_loss(hipStream_t s, const LossArgs& a);
 // head backward in one launch: dh (fp32, or bf16 when dh_b is non-null) and the split weight gradients
 // partial_w[chunk][A+1][F] (row A = value head), partial_b[chunk][A+1]
 hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv, const float* pi_w,
-                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* partial_w, float* partial_b);
+                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* partial_w, float* partial_b, const LossArgs* fused_loss);
+// whether heads_bwd takes the returns + loss work into its own launch: then fused_loss is given,
+// returns_loss is not launched, and loss_partials holds one entry per chunk of rows (n_chunk of them)
+bool heads_bwd_fuses_loss(int rows, int A, int T, int F);
 
 enum { ALG_ACTOR_CRITIC = 0, ALG_NSTEP_Q = 1 };
 enum { HP_GAMMA = 0, HP_BETA, HP_VCOEF, HP_LR, HP_ALPHA, HP_EPS, HP_CLIP, HP_COUNT = 8 };

@@ -334,6 +334,58 @@ hipError_t returns_loss(hipStream_t s, const LossArgs& a) {
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------ returns + loss, one row per wavefront
+// The same quantities as returns_loss_kernel for one batch row, computed by a whole wavefront: lane k < A
+// works on logit k, the sums over the actions are wave reductions, the return R_t is recomputed from the
+// bootstrap value by the recursion over t' = T-1 .. t (lane t' holds r_t' and the terminal flag, T <= 64).
+// A row takes a few hundred cycles instead of the few thousand of one thread walking over all actions:
+// this is what lets the head-backward launch compute its own coefficients (below).
+struct RowIn { float z, V, boot, r; int act; unsigned d; };
+struct RowOut { float coef, R, pl, H, vl; };       // coef: dL/dlogit_lane (lane < A), dL/dV (lane A), else 0
+// every load of a row (row is uniform in the wavefront and a valid index)
+__device__ __forceinline__ RowIn row_load(const LossArgs& a, int row, int lane) {
+    const int A = a.A, e = row % a.n_e, B = a.T * a.n_e, lk = min(lane, A - 1), lt = min(lane, a.T - 1);
+    RowIn in;
+    in.z = a.logits[(size_t)row * A + lk];
+    in.V = a.values[row];
+    in.act = a.actions[row];
+    in.boot = a.algorithm == ALG_NSTEP_Q ? a.logits[(size_t)(B + e) * A + lk] : a.values[B + e];
+    in.r = a.rewards[lt * a.n_e + e];
+    in.d = a.dones[lt * a.n_e + e];
+    return in;
+}
+__device__ __forceinline__ RowOut row_compute(const LossArgs& a, const RowIn& in, int row, int lane, float gamma, float beta,
+                                              float cv, float invB) {
+    const int A = a.A, t = row / a.n_e;
+    // R_{T+1} = V(s_{T+1}), or max_a' Q(s_{T+1}, a') for the value-based variant
+    float R = a.algorithm == ALG_NSTEP_Q ? wave_max(lane < A ? in.boot : -INFINITY) : in.boot;
+    for (int tt = a.T - 1; tt >= t; --tt) {
+        const float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(in.r), tt));
+        const unsigned d = (unsigned)__builtin_amdgcn_readlane((int)in.d, tt);
+        R = r + gamma * (d ? 0.f : 1.f) * R;
+    }
+    const int act = in.act < 0 ? 0 : (in.act >= A ? A - 1 : in.act);
+    RowOut o;
+    o.R = R;
+    if (a.algorithm == ALG_NSTEP_Q) {             // L = c (R - Q(s,a))^2 averaged; the value node is unused
+        const float td = R - wave_max(lane == act ? in.z : -INFINITY);
+        o.coef = lane == act ? -2.f * cv * td * invB : 0.f;
+        o.pl = 0.f; o.H = 0.f; o.vl = td * td;
+        return o;
+    }
+    const float m = wave_max(lane < A ? in.z : -INFINITY);
+    const float ex = lane < A ? expf(in.z - m) : 0.f;
+    const float se = wave_sum(ex);
+    const float lp = in.z - m - logf(se), p = ex * (1.0f / se);
+    const float H = -wave_sum(lane < A ? p * lp : 0.f);
+    const float lp_act = wave_sum(lane == act ? lp : 0.f);          // one non-zero term: exact
+    const float adv = R - in.V;
+    o.coef = lane < A ? (-adv * ((lane == act ? 1.f : 0.f) - p) + beta * p * (lp + H)) * invB
+                      : (lane == A ? 2.f * cv * (in.V - R) * invB : 0.f);
+    o.pl = -adv * lp_act; o.H = H; o.vl = adv * adv;
+    return o;
+}
+
 // ------------------------------------------------------------------------------------ head backward
 // Two independent jobs that both start from dz / dv share one launch (at the paper's batch each is a
 // few microseconds of latency, and a kernel boundary costs 2.5):
@@ -416,27 +468,52 @@ __global__ __launch_bounds__(256) void heads_bwd_kernel(int F, int A, int rows, 
 // chunk read the same rows of h again and again (6.7 times the bytes, measured); here a block owns 64
 // hidden units of a chunk for all outputs, its four waves take every fourth row, and their sums meet
 // in LDS in wave order.
-template <int AMAX>
-__global__ __launch_bounds__(256) void heads_bwd_rows_kernel(int F, int A, int rows, int n_dh, int rows_per_dh, int rows_per_chunk, const float* dz,
-                                                             const float* dv, const float* pi_w, const float* v_w, const float* h,
-                                                             float* dh, bf16_t* dh_b, float* pw, float* pb) {
-    if ((int)blockIdx.x < n_dh) {
+//
+// FUSED (batches below 1024 rows, where the returns + loss kernel is one short block and a kernel
+// boundary costs as much as its work): no returns + loss launch precedes this one.  Every wavefront
+// computes the coefficients of the row it works on itself (row_compute), the first weight-gradient block
+// of each chunk of rows also writes what the loss kernel would have written for those rows: returns, dz,
+// dv, and the chunk's sums of the three loss terms as loss_partials[chunk].
+struct HeadsBwdArgs {
+    int F, A, rows, n_dh, rows_per_dh, rows_per_chunk;
+    const float* dz; const float* dv; const float* pi_w; const float* v_w; const float* h;
+    float* dh; bf16_t* dh_b; float* pw; float* pb;
+    LossArgs loss;                                  // FUSED only
+};
+template <int AMAX, bool FUSED>
+__global__ __launch_bounds__(256) void heads_bwd_rows_kernel(const HeadsBwdArgs a) {
+    const int F = a.F, A = a.A, rows = a.rows;
+    float gamma = 0.f, beta = 0.f, cvc = 0.f, invB = 0.f;
+    if constexpr (FUSED) {
+        gamma = a.loss.hp[HP_GAMMA]; beta = a.loss.hp[HP_BETA]; cvc = a.loss.hp[HP_VCOEF];
+        invB = 1.0f / (float)(a.loss.T * a.loss.n_e);
+    }
+    if ((int)blockIdx.x < a.n_dh) {
         // dh for rows_per_dh rows: a thread keeps the head weights of its four hidden units in
         // registers for all of them (one row at a time they are fetched again for every row: 20 KB per
         // wave from L2), a wave works on one row at a time, so dz and dv are scalar loads
         const int F4 = F / 4, quad = threadIdx.x % F4, rpi = 256 / F4, j = quad * 4;
         const int sub = __builtin_amdgcn_readfirstlane(threadIdx.x / F4);      // F4 is a multiple of 64: uniform in a wave
+        const int lane = threadIdx.x & 63;
+        const int row_end = min(rows, ((int)blockIdx.x + 1) * a.rows_per_dh);
+        const int row_first = blockIdx.x * a.rows_per_dh + sub;
+        RowIn in0{};
+        if constexpr (FUSED) in0 = row_load(a.loss, min(row_first, rows - 1), lane);      // the first row's inputs go out with the weights
         float4 w[AMAX];
 #pragma unroll
-        for (int k = 0; k < AMAX; ++k) w[k] = *reinterpret_cast<const float4*>(pi_w + (size_t)min(k, A - 1) * F + j);
-        const float4 wv = *reinterpret_cast<const float4*>(v_w + j);
-        const int row_end = min(rows, ((int)blockIdx.x + 1) * rows_per_dh);
+        for (int k = 0; k < AMAX; ++k) w[k] = *reinterpret_cast<const float4*>(a.pi_w + (size_t)min(k, A - 1) * F + j);
+        const float4 wv = *reinterpret_cast<const float4*>(a.v_w + j);
 #pragma unroll 4
-        for (int row = blockIdx.x * rows_per_dh + sub; row < row_end; row += rpi) {
-            const float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * F + j);
+        for (int row = row_first; row < row_end; row += rpi) {
+            const float4 hv = *reinterpret_cast<const float4*>(a.h + (size_t)row * F + j);
             // the row's A + 1 coefficients: one load (lane k fetches coefficient k), then broadcasts
-            const int lane = threadIdx.x & 63;
-            const float cv = lane < A ? dz[(size_t)row * A + lane] : (lane == A ? dv[row] : 0.f);
+            float cv;
+            if constexpr (FUSED) {
+                const RowIn in = row == row_first ? in0 : row_load(a.loss, row, lane);
+                cv = row_compute(a.loss, in, row, lane, gamma, beta, cvc, invB).coef;
+            } else {
+                cv = lane < A ? a.dz[(size_t)row * A + lane] : (lane == A ? a.dv[row] : 0.f);
+            }
             const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cv), A));
             float4 acc = make_float4(d * wv.x, d * wv.y, d * wv.z, d * wv.w);
 #pragma unroll
@@ -447,34 +524,56 @@ __global__ __launch_bounds__(256) void heads_bwd_rows_kernel(int F, int A, int r
                 }
             acc.x = hv.x > 0.f ? acc.x : 0.f; acc.y = hv.y > 0.f ? acc.y : 0.f;
             acc.z = hv.z > 0.f ? acc.z : 0.f; acc.w = hv.w > 0.f ? acc.w : 0.f;
-            if (dh_b) {
+            if (a.dh_b) {
                 auto bf = [](float f) { __bf16 b = (__bf16)f; return (unsigned)__builtin_bit_cast(unsigned short, b); };
-                *reinterpret_cast<uint2*>(dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
+                *reinterpret_cast<uint2*>(a.dh_b + (size_t)row * F + j) = make_uint2(bf(acc.x) | (bf(acc.y) << 16), bf(acc.z) | (bf(acc.w) << 16));
             } else {
-                *reinterpret_cast<float4*>(dh + (size_t)row * F + j) = acc;
+                *reinterpret_cast<float4*>(a.dh + (size_t)row * F + j) = acc;
             }
         }
         return;
     }
+    constexpr int RQ = FUSED ? 4 : 8;               // rows of a wave in flight
     __shared__ float part[4][AMAX + 1][64];
     __shared__ float partb[4][AMAX + 1];
+    __shared__ float lossp[4][3];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wb = blockIdx.x - n_dh, fx = F / 64, fxi = wb % fx, c = wb / fx, K1 = A + 1;
+    const int wb = blockIdx.x - a.n_dh, fx = F / 64, fxi = wb % fx, c = wb / fx, K1 = A + 1;
     const int j = fxi * 64 + lane;
-    const int r0 = c * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);      // a trailing chunk may be empty: zeros
+    const int r0 = c * a.rows_per_chunk, r1 = min(rows, r0 + a.rows_per_chunk);      // a trailing chunk may be empty: zeros
     float acc[AMAX + 1], accb[AMAX + 1];
 #pragma unroll
     for (int k = 0; k <= AMAX; ++k) { acc[k] = 0.f; accb[k] = 0.f; }
-    for (int r = r0 + wave; r < r1; r += 32) {         // eight of this wave's rows in flight
-        float hv[8], cv[8];                            // cv: lane k holds coefficient k of the row (zero past the chunk)
+    float s_pl = 0.f, s_h = 0.f, s_vl = 0.f;
+    for (int r = r0 + wave; r < r1; r += 4 * RQ) {     // RQ of this wave's rows in flight
+        float hv[RQ], cv[RQ];                          // cv: lane k holds coefficient k of the row (zero past the chunk)
+        RowIn in[RQ];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < RQ; ++q) {
             const int rr = r + 4 * q;
-            hv[q] = h[(size_t)min(rr, r1 - 1) * F + j];
-            cv[q] = (rr < r1 && lane < K1) ? (lane < A ? dz[(size_t)rr * A + lane] : dv[rr]) : 0.f;
+            hv[q] = a.h[(size_t)min(rr, r1 - 1) * F + j];
+            if constexpr (FUSED) in[q] = row_load(a.loss, min(rr, r1 - 1), lane);
+            else cv[q] = (rr < r1 && lane < K1) ? (lane < A ? a.dz[(size_t)rr * A + lane] : a.dv[rr]) : 0.f;
+        }
+        if constexpr (FUSED) {
+#pragma unroll
+            for (int q = 0; q < RQ; ++q) {
+                const int rr = r + 4 * q;
+                cv[q] = 0.f;
+                if (rr < r1) {                         // uniform in the wavefront
+                    const RowOut o = row_compute(a.loss, in[q], rr, lane, gamma, beta, cvc, invB);
+                    cv[q] = o.coef;
+                    if (fxi == 0) {
+                        s_pl += o.pl; s_h += o.H; s_vl += o.vl;
+                        if (lane < A) a.loss.dz[(size_t)rr * A + lane] = o.coef;
+                        if (lane == A) a.loss.dv[rr] = o.coef;
+                        if (lane == 0) a.loss.returns[rr] = o.R;
+                    }
+                }
+            }
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < RQ; ++q) {
 #pragma unroll
             for (int k = 0; k <= AMAX; ++k)
                 if (k < K1) {
@@ -486,29 +585,49 @@ __global__ __launch_bounds__(256) void heads_bwd_rows_kernel(int F, int A, int r
 #pragma unroll
     for (int k = 0; k <= AMAX; ++k)
         if (k < K1) { part[wave][k][lane] = acc[k]; if (lane == 0) partb[wave][k] = accb[k]; }
+    if (FUSED && lane == 0) { lossp[wave][0] = s_pl * invB; lossp[wave][1] = s_h * invB; lossp[wave][2] = s_vl * invB; }
     __syncthreads();
     for (int e = tid; e < K1 * 64; e += 256) {
         const int k = e / 64, l = e % 64;
-        pw[((size_t)c * K1 + k) * F + fxi * 64 + l] = ((part[0][k][l] + part[1][k][l]) + part[2][k][l]) + part[3][k][l];
+        a.pw[((size_t)c * K1 + k) * F + fxi * 64 + l] = ((part[0][k][l] + part[1][k][l]) + part[2][k][l]) + part[3][k][l];
     }
-    if (fxi == 0 && tid < K1) pb[c * K1 + tid] = ((partb[0][tid] + partb[1][tid]) + partb[2][tid]) + partb[3][tid];
+    if (fxi == 0 && tid < K1) a.pb[c * K1 + tid] = ((partb[0][tid] + partb[1][tid]) + partb[2][tid]) + partb[3][tid];
+    // the chunk's share of the three loss means (each carries the 1/B of the batch mean)
+    if (FUSED && fxi == 0 && tid < 3) a.loss.loss_partials[c * 4 + tid] = ((lossp[0][tid] + lossp[1][tid]) + lossp[2][tid]) + lossp[3][tid];
+}
+
+bool heads_bwd_fuses_loss(int rows, int A, int T, int F) {
+    return rows < 1024 && A <= 32 && T <= 64 && (F / 4) % 64 == 0 && 256 % (F / 4) == 0;
+}
+
+template <bool FUSED> static void launch_heads_bwd_rows(hipStream_t s, const dim3 grid, const HeadsBwdArgs& a) {
+    if (a.A <= 8) launch_k((heads_bwd_rows_kernel<8, FUSED>), grid, dim3(256), s, a);
+    else if (a.A <= 18) launch_k((heads_bwd_rows_kernel<18, FUSED>), grid, dim3(256), s, a);
+    else launch_k((heads_bwd_rows_kernel<32, FUSED>), grid, dim3(256), s, a);
 }
 
 hipError_t heads_bwd(hipStream_t s, int F, int A, int rows, int n_chunk, const float* dz, const float* dv, const float* pi_w,
-                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* pw, float* pb) {
+                     const float* v_w, const float* h, float* dh, bf16_t* dh_b, float* pw, float* pb, const LossArgs* fused_loss) {
     if (rows <= 0 || n_chunk <= 0 || F % 256 != 0) return hipErrorInvalidValue;
     const int n_dh = (rows * (F / 4) + 255) / 256;
     const int rpc = (rows + n_chunk - 1) / n_chunk;
+    if (fused_loss) {
+        const LossArgs& la = *fused_loss;
+        if (!heads_bwd_fuses_loss(rows, A, la.T, F) || la.A != A || la.T * la.n_e != rows) return hipErrorInvalidValue;
+        const int rpi = 256 / (F / 4);                       // one pass of a dh block: a row per wave or pair of waves
+        const int n_dh_rows = (rows + rpi - 1) / rpi;
+        HeadsBwdArgs a{F, A, rows, n_dh_rows, rpi, rpc, nullptr, nullptr, pi_w, v_w, h, dh, dh_b, pw, pb, la};
+        launch_heads_bwd_rows<true>(s, dim3(n_dh_rows + (F / 64) * n_chunk), a);
+        return hipGetLastError();
+    }
     if (rows >= 1024 && A <= 32 && (F / 4) % 64 == 0 && 256 % (F / 4) == 0) {            // large batches: h is read once
         const int rpi = 256 / (F / 4);                       // rows a dh block works on at once
         int rpd = rows / 512;                                // enough dh blocks to fill the chip, at most 32 rows each
         rpd = rpd > 32 ? 32 : rpd;
         rpd = (rpd + rpi - 1) / rpi * rpi;
         const int n_dh = (rows + rpd - 1) / rpd;
-        const dim3 grid(n_dh + (F / 64) * n_chunk);
-        if (A <= 8) launch_k(heads_bwd_rows_kernel<8>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
-        else if (A <= 18) launch_k(heads_bwd_rows_kernel<18>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
-        else launch_k(heads_bwd_rows_kernel<32>, grid, dim3(256), s, F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb);
+        HeadsBwdArgs a{F, A, rows, n_dh, rpd, rpc, dz, dv, pi_w, v_w, h, dh, dh_b, pw, pb, LossArgs{}};
+        launch_heads_bwd_rows<false>(s, dim3(n_dh + (F / 64) * n_chunk), a);
         return hipGetLastError();
     }
     launch_k(heads_bwd_kernel, dim3(n_dh + (F / 256) * (A + 1) * n_chunk), dim3(256), s, F, A, rows, n_dh, rpc, dz, dv, pi_w, v_w, h,
@@ -772,9 +891,12 @@ __global__ __launch_bounds__(256) void rmsprop_update_kernel(int n4, float4* the
         update(i + stride, gb, vb, tb);
     }
     if (i < n4) update(i, grads[i], g2[i], theta[i]);
-    if ((int)blockIdx.x == ws_blocks && threadIdx.x == 0) {
+    if ((int)blockIdx.x == ws_blocks && threadIdx.x < 64) {
+        // lane l adds the partials l, l + 64, ... in ascending order, then the lanes are added: a fixed order
         float pl = 0.f, en = 0.f, vl = 0.f;
-        for (int b = 0; b < n_loss_blocks; ++b) { pl += loss_partials[b * 4]; en += loss_partials[b * 4 + 1]; vl += loss_partials[b * 4 + 2]; }
+        for (int b = threadIdx.x; b < n_loss_blocks; b += 64) { pl += loss_partials[b * 4]; en += loss_partials[b * 4 + 1]; vl += loss_partials[b * 4 + 2]; }
+        pl = wave_sum(pl); en = wave_sum(en); vl = wave_sum(vl);
+        if (threadIdx.x != 0) return;
         StatsOut st;
         // each block's partial already carries the 1/B of the batch mean
         st.policy_loss = pl; st.entropy = en; st.value_loss = vl;

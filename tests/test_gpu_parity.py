@@ -196,8 +196,11 @@ def test_train_step_configs(paac, oracle, ci):
 
 @pytest.mark.parametrize("net,n_e,t_max,p_done", [
     (I.nips_net(3), 1, 1, 0.0), (I.nature_net(5), 3, 2, 0.5), (I.nips_net(6), 7, 20, 0.1),
-    (I.nature_net(18), 2, 3, 1.0), (I.nips_net(6), 70, 2, 0.02)],
-    ids=["nips_1x1", "nature_3x2", "nips_7x20", "nature_all_done", "nips_70x2"])
+    (I.nature_net(18), 2, 3, 1.0), (I.nips_net(6), 70, 2, 0.02),
+    # head backward with the returns and losses computed in the same launch: an odd number of rows, the
+    # longest rollout it takes (64 steps); one step more and the loss kernel runs on its own again
+    (I.nature_net(5), 3, 3, 0.3), (I.nips_net(6), 2, 64, 0.1), (I.nips_net(4), 2, 65, 0.1)],
+    ids=["nips_1x1", "nature_3x2", "nips_7x20", "nature_all_done", "nips_70x2", "nature_3x3", "nips_2x64", "nips_2x65"])
 def test_train_ragged_and_degenerate(paac, oracle, net, n_e, t_max, p_done):
     ctx = make_ctx(paac, net, n_e, t_max)
     params = I.make_params(17, net, bias_range=0.1)
