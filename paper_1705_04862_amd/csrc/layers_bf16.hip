@@ -19,6 +19,7 @@ typedef ConvGeom<64, 9, 9, 3, 1, 64> NatC3;
 // 128 rows, four waves along m; 32 or 64 columns (a 16-wide output uses the 32-wide tile)
 typedef TileB<128, 32, 64, 4, 1, 3, 3> B128x32;
 typedef TileB<128, 64, 64, 4, 1, 3> B128x64;
+typedef TileB<64, 64, 64, 2, 2, 3> B64x64;
 // plain fc GEMMs: 2 x 2 fragments per wave, so that two LDS fragment reads feed two MFMAs each
 // (the 128x64 tile with four waves along m reads three fragments for two MFMAs and is bound by LDS reads)
 typedef TileB<128, 128, 32, 2, 2, 3> B128x128;
@@ -136,8 +137,13 @@ static void fc_dims(int arch, int& flat, int& fc) {
 
 // up to 1024 rows (select calls) the narrower tile gives more workgroups and is faster
 static bool fc_fwd_wide(int ns) { return ns > 1024; }
+// up to 256 rows 64-row tiles: twice the tiles, so half as many k-splits fill the chip, and every split is a
+// partial sum that the heads kernel has to add (n_e = 256: fc 7.7 -> 6.2 us, heads 6.2 -> 5.4 us per select
+// call; n_e = 128: 7.4 -> 5.4 and 6.1 -> 5.3; at 512 rows the step did not gain)
+static bool fc_fwd_64(int ns) { return ns <= 256; }
 int fc_fwd_tiles_bf16(int arch, int ns) {
     int flat, fc; fc_dims(arch, flat, fc);
+    if (fc_fwd_64(ns)) return ((ns + 63) / 64) * (fc / 64);
     return ((ns + 127) / 128) * (fc / (fc_fwd_wide(ns) ? 128 : 64));
 }
 
@@ -148,6 +154,7 @@ hipError_t fc_fwd_bf16(hipStream_t s, int arch, const bf16_t* x, const bf16_t* W
     DenseRowsK8 bl{Wt, fc, flat};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
     if (fc_fwd_wide(ns)) return launch_gemm_bf16<B128x128K64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
+    if (fc_fwd_64(ns)) return launch_gemm_bf16<B64x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
     return launch_gemm_bf16<B128x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per, 1);
 }
 
