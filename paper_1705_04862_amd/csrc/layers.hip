@@ -254,9 +254,14 @@ static bool fc_small(int ns) { return ns <= 48; }
 // up to 48 rows: 16x16 tiles and about 512 workgroups (fewer, longer k-splits than with wider tiles:
 // fewer partial sums for the heads kernel to add; arch_nips select: fc 4.5 -> 4.2 us, heads 5.4 -> 4.6 us)
 int fc_fwd_target_wgs(int ns) { return fc_small(ns) ? 512 : 256; }
+// 49 to 64 rows: 32x32 tiles, four times the tiles of the 64x64 ones and so a quarter of the k-splits, each
+// of which is a partial sum for the heads kernel to add (n_e = 64: heads 5.8 -> 4.65 us per select call, the
+// GEMM unchanged, step +1.5 %; at 128 rows +0.3 %, at 256 -1.2 %)
+static bool fc_mid(int ns) { return ns <= 64; }
 int fc_fwd_tiles(int arch, int ns) {
     int flat, fc; fc_dims(arch, flat, fc);
     if (fc_small(ns)) return ((ns + 15) / 16) * (fc / 16);
+    if (fc_mid(ns)) return ((ns + 31) / 32) * (fc / 32);
     return ((ns + 63) / 64) * (fc / 64);
 }
 
@@ -266,6 +271,7 @@ hipError_t fc_fwd(hipStream_t s, int arch, const float* x, const float* W, float
     DenseKCols bl{W, fc, fc};
     EpiPartial<false> ep{partial, (size_t)ns * fc, fc, nullptr, 0};
     if (fc_small(ns)) return launch_gemm_reg16(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
+    if (fc_mid(ns)) return launch_gemm<T32x32>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
     return launch_gemm<T64x64>(s, al, bl, ep, ns, fc, flat, sp.n, sp.k_per);
 }
 
