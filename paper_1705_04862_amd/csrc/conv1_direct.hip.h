@@ -320,26 +320,29 @@ __global__ __launch_bounds__(256, 1) void conv1_exact_kernel(const uint8_t* __re
     }
 }
 
-// The same for small batches (a quarter of a sample per workgroup, one item each): a wave that takes
+// The same for small batches (a quarter or a tenth of a sample per workgroup, one item each): a wave that takes
 // whole fragments needs all 48 KB of weight parts for 48 MFMAs, and loading them is what the kernel
 // then waits for.  Here wave c takes input channel c (a quarter of the k-steps, 12 KB of weights) for
-// all four fragments of the band; the four partial sums of a fragment meet in LDS, wave f finishing
-// fragment f (own share first, then the others by wave: a fixed order).
-template <class G>
+// all fragments of the band (four, or two with ten bands); the four partial sums of a fragment meet in LDS,
+// every wave finishing a quarter of the band's accumulator registers (own share first, then the others by
+// wave: a fixed order).
+template <class G, int PARTS>
 __global__ __launch_bounds__(256, 1) void conv1_exact_ksplit_kernel(const uint8_t* __restrict__ x, const bf16_t* __restrict__ Wp,
                                                                     const float* __restrict__ bias, float* __restrict__ out, int ns,
                                                                     float scale) {
     static_assert(G::CIN == 4 && G::H == 84 && G::W == 84 && G::KS == 8 && G::ST == 4 && G::COUT <= 32, "first layer");
-    constexpr int PARTS = 4;
     static_assert(G::HO % PARTS == 0, "bands of whole output rows");
     constexpr int SAMPLE = G::CIN * G::H * G::W, PLANE = G::H * G::W;
     constexpr int BR = G::HO / PARTS, IR = 4 * BR + 4;
     constexpr int CPC = IR * G::W / 16, CHUNKS = 4 * CPC, IT = (CHUNKS + 255) / 256;
     constexpr int ROWS = BR * G::WO, FRAGS = (ROWS + 31) / 32;
-    static_assert(FRAGS == 4, "one fragment per wave to finish");
+    // the band's FRAGS x 16 accumulator registers are finished in four units, one per wave: unit u is
+    // fragment u % FRAGS, registers (u / FRAGS) RPU .. + RPU (a whole fragment with four fragments, half of one with two)
+    static_assert(FRAGS == 4 || FRAGS == 2, "four finishing units of whole or half fragments");
+    constexpr int RPU = 16 * FRAGS / 4;
     static_assert((IR * G::W) % 16 == 0 && (G::ST * G::W * BR) % 16 == 0 && PLANE % 16 == 0, "whole 16-byte chunks");
     __shared__ __attribute__((aligned(16))) bf16_t img[4 * IR * G::W];
-    __shared__ float red[FRAGS * 3 * 16 * 64];
+    __shared__ float red[4 * 3 * RPU * 64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -402,27 +405,28 @@ __global__ __launch_bounds__(256, 1) void conv1_exact_ksplit_kernel(const uint8_
         if (wave == 2) fn(std::integral_constant<int, 2>());
         if (wave == 3) fn(std::integral_constant<int, 3>());
     };
-    auto slot = [&](int dst, int src, int q) { return ((dst * 3 + (src < dst ? src : src - 1)) * 16 + q) * 64 + lane; };
+    auto slot = [&](int dst, int src, int q) { return ((dst * 3 + (src < dst ? src : src - 1)) * RPU + q) * 64 + lane; };
     per_wave([&](auto WV) __attribute__((always_inline)) {
         constexpr int wv = decltype(WV)::value;
 #pragma unroll
-        for (int f = 0; f < FRAGS; ++f)
-            if (f != wv) {
+        for (int u = 0; u < 4; ++u)
+            if (u != wv) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) red[slot(f, wv, q)] = acc[f][q];
+                for (int q = 0; q < RPU; ++q) red[slot(u, wv, q)] = acc[u % FRAGS][(u / FRAGS) * RPU + q];
             }
     });
     __syncthreads();
     const size_t orow0 = (size_t)(p / PARTS) * (G::HO * G::WO) + (size_t)(p % PARTS) * ROWS;
     per_wave([&](auto WV) __attribute__((always_inline)) {
         constexpr int wv = decltype(WV)::value;
+        constexpr int f = wv % FRAGS, q0 = (wv / FRAGS) * RPU;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            float v = acc[wv][q];
+        for (int q = 0; q < RPU; ++q) {
+            float v = acc[f][q0 + q];
 #pragma unroll
             for (int g = 0; g < 4; ++g)
                 if (g != wv) v += red[slot(wv, g, q)];
-            const int lr = wv * 32 + Mma<32>::row(q, lane);
+            const int lr = f * 32 + Mma<32>::row(q0 + q, lane);
             if (fidx < G::COUT && lr < ROWS) out[(orow0 + lr) * G::COUT + fidx] = fmaxf(v * scale + bias_r, 0.f);
         }
     });
@@ -444,7 +448,10 @@ inline hipError_t launch_conv1_exact(hipStream_t s, const uint8_t* x, const bf16
     // one workgroup per compute unit (its registers allow no more): split samples into bands while
     // that still gives every workgroup a compute unit of its own
     const int parts = ns * 4 <= cus ? 4 : (ns * 2 <= cus ? 2 : 1);
-    if (parts == 4) launch_k((conv1_exact_ksplit_kernel<G>), dim3(ns * 4), dim3(256), s, x, Wk, bias, out, ns, 1.0f / 255.0f);
+    // up to a fifth of a sample per compute unit: ten bands of two output rows (two fragments, each finished in
+    // halves), two workgroups per compute unit (n_e = 32: 5.85 -> 5.5 us per select call, n_e = 4: 5.0 -> 4.35 us)
+    if (ns * 10 <= 2 * cus) launch_k((conv1_exact_ksplit_kernel<G, 10>), dim3(ns * 10), dim3(256), s, x, Wk, bias, out, ns, 1.0f / 255.0f);
+    else if (parts == 4) launch_k((conv1_exact_ksplit_kernel<G, 4>), dim3(ns * 4), dim3(256), s, x, Wk, bias, out, ns, 1.0f / 255.0f);
     else if (parts == 2) launch_conv1_exact_p<G, 2>(s, cus, x, Wk, bias, out, ns);
     else launch_conv1_exact_p<G, 1>(s, cus, x, Wk, bias, out, ns);
     return hipGetLastError();
