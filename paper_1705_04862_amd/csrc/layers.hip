@@ -121,7 +121,7 @@ static hipError_t conv_fwd_f32(hipStream_t s, const void* in, const float* W, co
     // up to 64 samples the register-only 16x16 kernel also beats the 32x32 tiles that launch_auto would
     // pick from 38 samples on (whole step at n_e = 48: +1.2 %, 64: +1.0 %; at 90 it loses 0.7 %)
     // the third layer (49 rows per sample, 392 tiles of 16x16 at n_e = 32) on 16x32 tiles: 6.0 -> 5.55 us per select
-    // call; the second layer on them 6.95 -> 7.2 us, the third on 16x64 8.1 us
+    // call; the second layer on them 6.95 -> 7.2 us (and on 32x16 tiles 6.7 -> 7.9 us), the third on 16x64 8.1 us
     if (ns <= 64 && G::ST == 1) return launch_gemm_reg16<2>(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
     if (ns <= 64) return launch_gemm_reg16(s, al, bl, ep, M, G::COUT, G::KK, 1, 0);
     return launch_auto<typename TS::big, typename TS::mid, typename TS::small>(s, al, bl, ep, M, G::COUT, G::KK, 1);
