@@ -306,6 +306,18 @@ hipError_t fc_bwd(hipStream_t s, int arch, const float* x, const float* dh, cons
     DenseKCols wal{x, flat, flat};
     DenseKCols wbl{dh, fc, fc};
     EpiPartial<true> wep{pw, (size_t)flat * fc, fc, pb, fc};
+    // arch_nature, 128 to 384 rows: the weight gradient on 64x128 tiles.  Its reduction dimension is the batch, a
+    // handful of k tiles, so a workgroup's start-up and its 16 KB of output stores weigh as much as its
+    // MFMAs; the wider tile halves the workgroups and doubles the MFMAs of each (n_e = 32: 21.2 -> 19.05 us,
+    // n_e = 64: 35.9 -> 31.5; at 80 rows 13.7 -> 15.2, at 640 rows 55 -> 69, arch_nips at 160 rows 11.7 -> 15.5: not there)
+    if (arch == 1 && ns >= 128 && ns <= 384) {
+        const auto wide = make_call<T64x128>(wal, wbl, wep, flat, fc, ns, sp.n, sp.k_per);
+        DenseRowsK al{dh, ns, fc};
+        DenseRowsK bl{W, flat, fc};
+        EpiDenseMask ep{dx, x, flat};
+        if ((long)((ns + 63) / 64) * (flat / 64) >= kMinWgs) return launch_pair(s, make_call<T64x64>(al, bl, ep, ns, flat, fc, 1, 0), wide);
+        return launch_pair(s, make_call<T32x64>(al, bl, ep, ns, flat, fc, 1, 0), wide);
+    }
     const auto wcall = make_call<T64x64>(wal, wbl, wep, flat, fc, ns, sp.n, sp.k_per);
     DenseRowsK al{dh, ns, fc};
     DenseRowsK bl{W, flat, fc};
